@@ -1,0 +1,5 @@
+"""CPU oracle for the APRIL rollout path.  TEST INFRASTRUCTURE ONLY.
+
+Only tests/, __graft_entry__.smoke() and bench.py's cpu_baseline leg may import
+this package; the product path never does.
+"""

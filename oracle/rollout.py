@@ -1,0 +1,63 @@
+"""APRIL rollouts with the oracle model: scheduler + decoder + sampler.
+TEST INFRASTRUCTURE ONLY.
+
+Glue between oracle/scheduler.py (Section 2.2's step) and oracle/model.py:
+every in-flight rollout owns a KV cache; a rollout that is carried over keeps
+its cache (the policy does not change between steps in this build, so the
+cached state is exact), or drops it and recomputes it from its tokens when
+`drop_kv` is asked for (the paper's buffer holds tokens: Section 3.2.3, "tokens
+from incomplete trajectories are cached and reused").
+"""
+import numpy as np
+
+from . import sampler as _sampler
+from .philox import uniform_for
+from .scheduler import Rollout, rollout_step
+
+
+class OracleRollouts:
+    def __init__(self, decoder, sampler="greedy", top_k=50, temperature=1.0, seed=0,
+                 eos_token=-1, keep_logits=False):
+        self.dec = decoder
+        self.sampler = sampler
+        self.top_k = top_k
+        self.temperature = temperature
+        self.seed = seed
+        self.eos_token = eos_token
+        self.keep_logits = keep_logits
+        self.buffer = []
+        self.logits = {}            # (request_id, gen_index) -> logits row, if keep_logits
+
+    def _pick(self, r, logits):
+        if self.keep_logits:
+            self.logits[(r.request_id, r.gen)] = logits.copy()
+        if self.sampler == "greedy":
+            return _sampler.greedy(logits)
+        u = uniform_for(self.seed, r.request_id, r.gen)
+        return _sampler.top_k_sample(logits, self.top_k, self.temperature, u)
+
+    def _next_token(self, r):
+        st = r.user
+        if st["cache"] is None:                       # new, or carried over without KV
+            st["cache"] = self.dec.new_cache()
+            fed = list(st["prompt"]) + list(r.tokens)
+            logits = self.dec.forward_block(fed, st["cache"])[-1]
+        else:                                         # KV resident: feed the last token
+            logits = self.dec.decode_step(r.tokens[-1], st["cache"])
+        return self._pick(r, logits)
+
+    def make_rollout(self, request_id, prompt, forced_len):
+        return Rollout(request_id=request_id, prompt_len=len(prompt), forced_len=forced_len,
+                       user={"prompt": np.asarray(prompt), "cache": None})
+
+    def drop_kv(self):
+        for r in self.buffer:
+            r.user["cache"] = None
+
+    def step(self, new_rollouts, n_target, n_overprovision, max_new):
+        out = rollout_step(self.buffer, new_rollouts, n_target, n_overprovision, max_new,
+                           next_token=self._next_token, eos_token=self.eos_token)
+        self.buffer = out.buffer
+        for r in out.completed:
+            r.user["cache"] = None                    # finished: its KV is released
+        return out

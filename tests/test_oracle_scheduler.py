@@ -1,0 +1,131 @@
+"""Pins for oracle/scheduler.py: an independently derived order-statistics closed
+form, the method's invariants, and the paper's worked sizes."""
+import numpy as np
+import pytest
+
+import april_inputs as ai
+from oracle.scheduler import Rollout, rollout_step
+
+
+def closed_form_step(rem, n_done_surplus, n_target):
+    """Independent derivation.  Every in-flight rollout gains one token per iteration,
+    so a rollout with `rem` tokens to go completes at iteration `rem`.  The step ends
+    at the iteration at which the (N - D)-th in-flight rollout completes: T = that
+    order statistic of `rem` (0 when D >= N).  Each rollout gains min(rem, T)."""
+    need = n_target - n_done_surplus
+    if need <= 0:
+        return 0, [0] * len(rem)
+    T = sorted(rem)[need - 1]
+    return T, [min(r, T) for r in rem]
+
+
+def run_steps(lengths, prompt_len, n_target, n_over, max_new, steps):
+    reqs = [Rollout(request_id=i, prompt_len=prompt_len, forced_len=int(l)) for i, l in enumerate(lengths)]
+    buf, nxt, outs = [], 0, []
+    for _ in range(steps):
+        # closed-form prediction from the state BEFORE the step
+        resumed = sorted(buf, key=lambda r: r.request_id)
+        D = sum(r.done for r in resumed)
+        infl = [r for r in resumed if not r.done]
+        k = nxt
+        while len(infl) < n_over - D and k < len(reqs):
+            infl.append(reqs[k]); k += 1
+        rem = [min(r.forced_len, max_new) - r.gen for r in infl]
+        T, gains = closed_form_step(rem, D, n_target)
+        gen_before = {r.request_id: r.gen for r in infl}
+        out = rollout_step(buf, reqs[nxt:], n_target, n_over, max_new)
+        assert out.decode_iters == T
+        assert out.tokens_generated == sum(gains)
+        for r, g in zip(infl, gains):
+            assert r.gen - gen_before[r.request_id] == g
+        assert out.n_new_consumed == k - nxt
+        nxt += out.n_new_consumed
+        buf = out.buffer
+        outs.append(out)
+    return reqs, outs
+
+
+@pytest.mark.parametrize("seed", range(20))
+def test_event_loop_equals_closed_form_random_tiny(seed):
+    rng = np.random.default_rng(seed)
+    n = int(rng.integers(1, 7))
+    n_over = n + int(rng.integers(0, 9))
+    lengths = rng.integers(1, 12, size=200)          # many ties on purpose
+    run_steps(lengths, 4, n, n_over, int(rng.integers(3, 12)), steps=6)
+
+
+@pytest.mark.parametrize("name", list(ai.WORKLOADS))
+def test_all_five_workloads_closed_form_and_invariants(name):
+    w = ai.WORKLOADS[name]
+    lens = ai.make_forced_lengths(ai.requests_needed(w), w.len_mu, w.len_sigma, w.len_lo, w.len_hi, w.seed)
+    reqs, outs = run_steps(lens, w.prompt_len, w.n_target, w.n_overprovision, w.max_new, w.steps)
+    returned = []
+    admitted = 0
+    for out in outs:
+        admitted += out.n_new_consumed
+        # exactly N per step, all complete, ascending id among simultaneous finishers
+        assert len(out.completed) == w.n_target
+        assert all(r.done and r.gen == r.limit for r in out.completed)
+        # buffer holds N' - N rollouts after every step
+        assert len(out.buffer) == w.n_overprovision - w.n_target
+        assert [r.request_id for r in out.buffer] == sorted(r.request_id for r in out.buffer)
+        returned += [r.request_id for r in out.completed]
+        # nothing discarded: every admitted id is returned once or sits in the buffer
+        in_buf = [r.request_id for r in out.buffer]
+        assert len(set(returned)) == len(returned)
+        assert sorted(returned + in_buf) == list(range(admitted))
+        assert out.tokens_generated == sum(out.live_per_iter)
+    # total tokens accounted for
+    assert sum(o.tokens_generated for o in outs) == sum(r.gen for r in reqs)
+    for r in reqs:
+        assert len(r.tokens) == r.gen
+
+
+def test_paper_worked_sizes_256_of_512():
+    """Section 3.1: 512 rollouts requested, the step ends after the first 256 complete,
+    so 256 are carried over; the next step then starts only 256 new ones."""
+    lens = ai.make_forced_lengths(2000, 7.0, 1.2, 16, 16384, 0)
+    reqs = [Rollout(request_id=i, prompt_len=8, forced_len=int(l)) for i, l in enumerate(lens)]
+    out1 = rollout_step([], reqs, 256, 512, 16384)
+    assert len(out1.completed) == 256 and len(out1.buffer) == 256 and out1.n_new_consumed == 512
+    out2 = rollout_step(out1.buffer, reqs[512:], 256, 512, 16384)
+    assert out2.n_new_consumed == 256 and len(out2.buffer) == 256
+    # buffered rollouts were resumed (prioritised): every unfinished one advanced
+    assert all(r.n_resumes >= 1 for r in out1.buffer if r in out2.completed or r in out2.buffer)
+
+
+def test_wait_for_all_is_n_equal_nprime():
+    lens = [5, 9, 2, 7, 30, 4, 4, 11]
+    reqs = [Rollout(request_id=i, prompt_len=3, forced_len=l) for i, l in enumerate(lens)]
+    out = rollout_step([], reqs, 4, 4, 20)
+    assert out.decode_iters == max(lens[:4]) and out.buffer == []
+    assert out.tokens_generated == sum(lens[:4])
+    out = rollout_step([], reqs[4:], 4, 4, 20)
+    assert out.decode_iters == 20                     # clipped by max_new
+    assert [r.gen for r in out.completed] == [4, 4, 11, 20]   # completion order, ties by id
+
+
+def test_surplus_finishers_are_kept_and_returned_first():
+    lens = [3, 3, 3, 9, 9]
+    reqs = [Rollout(request_id=i, prompt_len=1, forced_len=l) for i, l in enumerate(lens)]
+    out = rollout_step([], reqs, 2, 5, 50)
+    assert [r.request_id for r in out.completed] == [0, 1]
+    assert [(r.request_id, r.done) for r in out.buffer] == [(2, True), (3, False), (4, False)]
+    more = [Rollout(request_id=5 + i, prompt_len=1, forced_len=1) for i in range(5)]
+    out2 = rollout_step(out.buffer, more, 2, 5, 50)
+    # request 2 is delivered first; N' - D = 4 in flight => 2 new admitted
+    assert out2.completed[0].request_id == 2 and out2.n_new_consumed == 2
+    assert out2.decode_iters == 1 and out2.completed[1].request_id == 5
+
+
+def test_eos_token_terminates_early():
+    reqs = [Rollout(request_id=i, prompt_len=1, forced_len=0) for i in range(3)]
+    seq = {0: [7, 7, 2], 1: [7, 2], 2: [7, 7, 7, 7, 7, 7]}
+    out = rollout_step([], reqs, 2, 3, 6, next_token=lambda r: seq[r.request_id][r.gen], eos_token=2)
+    assert [r.request_id for r in out.completed] == [1, 0] and out.decode_iters == 3
+    assert out.buffer[0].tokens == [7, 7, 7]
+
+
+def test_starved_raises():
+    with pytest.raises(RuntimeError):
+        rollout_step([], [Rollout(request_id=0, prompt_len=1, forced_len=2)], 2, 3, 5)

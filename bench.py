@@ -1,0 +1,197 @@
+#!/usr/bin/env python3
+"""Benchmark of the APRIL rollout hot path on one MI355X.
+
+A "step" is one rollout step (admission, prefill, decode loop with early termination,
+parking) of the configured workload.  The metric is the paper's rollout throughput
+(Section 3.2.1: tokens generated divided by the wall-clock time of the rollout
+iterations), reported for APRIL (N' > N) with the wait-for-all baseline (N' = N) on
+the same request stream beside it.  Inputs are synthetic and already resident in HBM
+(weights, KV pool); prompts are a few KB per step.
+
+Prints ONE JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+BF16_PEAK_TFLOPS = 2500.0      # dense bf16 MFMA, published
+
+
+def run_arm(ap, ctx, reqs, n_target, n_over, max_new, steps, profile_every=0):
+    """Run `steps` rollout steps from a clean context state; returns per-step results."""
+    ap.april_profile_enable(ctx, profile_every)
+    nxt, results = 0, []
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        new = [dict(request_id=r.request_id, tokens=r.tokens, forced_len=r.forced_len) for r in reqs[nxt:nxt + n_over]]
+        res = ap.april_rollout_step(ctx, new, n_target, n_over, max_new)
+        nxt += res.n_new_consumed
+        results.append(res)
+        ap.april_resume(ctx, res.buffer)
+    import torch
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    return results, wall
+
+
+def cpu_baseline(w, weights, reqs, budget_s=20.0):
+    """The oracle as it stands, timed on the host cores for a bounded slice of the
+    workload: whole rollouts (prefill of the prompt, then decode) one after another
+    until the time budget is used."""
+    import numpy as np
+    from oracle.model import Decoder
+    from oracle.rollout import OracleRollouts
+    import threadpoolctl
+    eng = OracleRollouts(Decoder(w.shape, weights), "topk" if w.sampler else "greedy", top_k=max(w.top_k, 1),
+                         seed=w.seed)
+    t0 = time.perf_counter()
+    tokens = 0
+    n_roll = 0
+    per_roll = 8
+    while time.perf_counter() - t0 < budget_s and n_roll < len(reqs):
+        r = reqs[n_roll]
+        roll = eng.make_rollout(r.request_id, r.tokens, per_roll)
+        eng.buffer = []
+        out = eng.step([roll], 1, 1, per_roll)
+        tokens += out.tokens_generated
+        n_roll += 1
+    dt = time.perf_counter() - t0
+    threads = max((p.get("num_threads", 1) for p in threadpoolctl.threadpool_info()), default=1)
+    return dict(value=tokens / dt, unit="tokens/s", cores=int(threads), kind="oracle",
+                sample=f"{n_roll} rollouts of the workload, each: prefill of its {w.prompt_len}-token prompt + "
+                       f"{per_roll} generated tokens, one rollout at a time ({dt:.1f} s)")
+
+
+def main():
+    p = argparse.ArgumentParser()
+    p.add_argument("--gpus", type=int, default=1)
+    p.add_argument("--steps", type=int, default=5)
+    p.add_argument("--warmup", type=int, default=1)
+    p.add_argument("--workload", default="cfg2_small_bf16")
+    p.add_argument("--layers", type=int, default=0, help="override the layer count (debug only; invalidates the number)")
+    p.add_argument("--no-cpu-baseline", action="store_true")
+    p.add_argument("--no-wait-all", action="store_true")
+    p.add_argument("--profile-every", type=int, default=16)
+    args = p.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no sharding, no collectives); --gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import april_inputs as ai
+    import paper_2509_18521_amd as ap
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        sys.exit(3)
+    w = ai.WORKLOADS[args.workload]
+    if args.layers:
+        w = ai.reduced(w, n_layers=args.layers)
+    s = w.shape
+    t_setup = time.perf_counter()
+    weights = ai.make_weights(s, w.seed)
+    total_steps = args.steps
+    reqs = ai.make_requests(w, ai.requests_needed(w, max(total_steps, args.warmup)))
+    cfg = ap.make_cfg(s, max_inflight=w.n_overprovision + 32, max_ctx=w.prompt_len + w.max_new + 16,
+                      sampler=w.sampler, top_k=max(w.top_k, 1), temperature=1.0, seed=w.seed,
+                      stream=torch.cuda.current_stream().cuda_stream or None)
+    ctx = ap.april_init(cfg, ap.pack_weights(s, weights))
+    info = ap.april_get_info(ctx)
+    setup_s = time.perf_counter() - t_setup
+
+    def fresh_arm(n_over, steps, profile_every):
+        """Run an arm on the current engine (created fresh for each arm by reset_engine)."""
+        results, wall = run_arm(ap, ctx, reqs, w.n_target, n_over, w.max_new, steps, profile_every)
+        ap.april_profile_enable(ctx, 0)
+        return results, wall
+
+    def reset_engine():
+        nonlocal ctx
+        ap.april_destroy(ctx)
+        ctx = ap.april_init(cfg, ap.pack_weights(s, weights))
+
+    # warm-up (untimed), then a fresh engine for the timed region
+    if args.warmup > 0:
+        fresh_arm(w.n_overprovision, args.warmup, 0)
+        reset_engine()
+    torch.cuda.synchronize()
+    ap.april_profile_reset(ctx)
+    res_april, wall_april = fresh_arm(w.n_overprovision, total_steps, args.profile_every)
+    stats = ap.april_profile_get(ctx)
+    torch.cuda.synchronize()
+
+    tok_april = sum(r.tokens_generated for r in res_april)
+    delivered_april = sum(len(t) for r in res_april for t in r.tokens)
+    step_time = sum(r.t_total_s for r in res_april)
+    decode_time = sum(r.t_decode_s for r in res_april)
+    iters = sum(r.decode_iters for r in res_april)
+    value = tok_april / step_time
+    # Algorithmic bytes of the decode iterations that t_decode_s covers (iterations 2.. of
+    # every step): all decode weights once per iteration, the KV of every live context
+    # read once, one KV row written per live rollout, the fp32 residual stream around each
+    # sub-block, token in / token out.
+    sum_live = sum(r.dec_sum_live for r in res_april)
+    sum_ctx = sum(r.dec_sum_ctx for r in res_april)
+    kv_tok = info["kv_bytes_per_token"]
+    dec_bytes = (sum(max(r.decode_iters - 1, 0) for r in res_april) * info["decode_weight_bytes"]
+                 + sum_ctx * kv_tok + sum_live * kv_tok
+                 + sum_live * s.d_model * 4 * 2 * (2 * s.n_layers + 1) + sum_live * 8)
+    decode_gbs = dec_bytes / decode_time / 1e9 if decode_time > 0 else 0.0
+
+    out = {
+        "metric": "rollout tokens/s on 1 MI355X (APRIL vs wait-all); decode HBM GB/s % of peak",
+        "value": value, "unit": "tokens/s", "n_gpus": 1, "steps": total_steps, "warmup": args.warmup,
+        "ms_per_step": 1e3 * step_time / total_steps, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16" if s.dtype == ai.DTYPE_BF16 else "f32", "data": "synthetic",
+        "config": {"workload": w.name, "n_layers": s.n_layers, "d_model": s.d_model, "vocab": s.vocab,
+                   "n_target": w.n_target, "n_overprovision": w.n_overprovision, "max_new": w.max_new,
+                   "prompt_len": w.prompt_len, "sampler": "top-k" if w.sampler else "greedy", "top_k": w.top_k,
+                   "forced_len": f"lognormal(mu={w.len_mu}, sigma={w.len_sigma}) clipped to [{w.len_lo},{w.len_hi}]"},
+        "april": {"tokens_generated": tok_april, "tokens_delivered": delivered_april, "decode_iters": iters,
+                  "step_time_s": step_time, "decode_time_s": decode_time,
+                  "prefill_time_s": sum(r.t_prefill_s for r in res_april), "wall_s": wall_april,
+                  "delivered_tokens_per_s": delivered_april / step_time},
+        "decode": {"algorithmic_bytes": dec_bytes, "GBps": decode_gbs, "frac_of_hbm_peak": decode_gbs / HBM_PEAK_GBS,
+                   "sum_live": sum_live, "sum_ctx": sum_ctx},
+        "setup_s": setup_s,
+    }
+
+    # roofline of the dominant kernel (largest share of the timed decode launches)
+    timed = [k for k in stats if k["launches"] > 0 and k["name"] != "sched"]
+    if timed:
+        dom = max(timed, key=lambda k: k["total_ms"])
+        ach = dom["alg_bytes"] / (dom["total_ms"] * 1e-3) / 1e9
+        out["roofline"] = {"kernel": dom["name"], "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS,
+                           "unit": "GB/s", "frac": ach / HBM_PEAK_GBS, "traffic": None,
+                           "avg_launch_us": 1e3 * dom["total_ms"] / dom["launches"], "launches_timed": dom["launches"]}
+        tot = sum(k["total_ms"] for k in timed)
+        out["kernels"] = [{"name": k["name"], "launches": k["launches"], "avg_us": 1e3 * k["total_ms"] / k["launches"],
+                           "share": k["total_ms"] / tot,
+                           "GBps": k["alg_bytes"] / (k["total_ms"] * 1e-3) / 1e9,
+                           "TFLOPs": k["alg_flops"] / (k["total_ms"] * 1e-3) / 1e12} for k in timed]
+
+    if not args.no_wait_all:
+        reset_engine()
+        res_wait, wall_wait = fresh_arm(w.n_target, total_steps, 0)
+        tok_wait = sum(r.tokens_generated for r in res_wait)
+        t_wait = sum(r.t_total_s for r in res_wait)
+        out["wait_all"] = {"tokens_generated": tok_wait, "decode_iters": sum(r.decode_iters for r in res_wait),
+                           "step_time_s": t_wait, "tokens_per_s": tok_wait / t_wait, "wall_s": wall_wait}
+        out["april_speedup_vs_wait_all"] = value / (tok_wait / t_wait)
+    ap.april_destroy(ctx)
+
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w, weights, reqs)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,1109 @@
+// Host side of the APRIL rollout engine: C ABI, context, weights, KV pool, the
+// rollout step (admission, prefill, decode loop, early termination, parking).
+// Method: paper Section 2.2 (over-provisioned generation, early termination,
+// buffering continuations, prioritized resumption).
+#include <algorithm>
+#include <chrono>
+#include <cstdarg>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <map>
+#include <string>
+#include <vector>
+
+#include "../../include/april.h"
+#include "kernels.h"
+
+using namespace april;
+
+namespace {
+
+thread_local std::string g_init_error;
+
+double now_s() {
+  return std::chrono::duration<double>(std::chrono::steady_clock::now().time_since_epoch()).count();
+}
+
+enum KernelClass {
+  KC_SCHED = 0, KC_EMBED, KC_NORM, KC_GEMM_QKV, KC_ROPE, KC_ATTN, KC_GEMM_O, KC_GEMM_GATEUP, KC_SILU,
+  KC_GEMM_DOWN, KC_GEMM_LMHEAD, KC_SAMPLE, KC_COUNT
+};
+const char* kKernelNames[KC_COUNT] = {"sched", "embed", "add_rmsnorm", "gemm_qkv", "rope_append", "attn_decode",
+                                      "gemm_o", "gemm_gateup", "silu_mul", "gemm_down", "gemm_lmhead", "sample"};
+
+struct LayerW {
+  float *attn_norm = nullptr, *mlp_norm = nullptr;
+  void *wqkv = nullptr, *wo = nullptr, *wgu = nullptr, *wd = nullptr;            // plain [N][K]
+  bf16_t *wqkv_s = nullptr, *wo_s = nullptr, *wg_s = nullptr, *wu_s = nullptr, *wd_s = nullptr;  // fragment-tiled
+};
+
+struct SlotH {
+  int state = SLOT_FREE;
+  long long req = -1;
+  int prompt_len = 0, gen = 0, limit = 0, kv_len = 0, n_blocks = 0, n_resumes = 0;
+  std::vector<int> prompt;
+  std::vector<int> forced;
+};
+
+struct Entry {
+  long long req = -1;
+  int slot = -1;                 // -1: token-level entry without a slot
+  std::vector<int> prompt, generated;
+  int limit = 0, n_resumes = 0, done = 0;
+};
+
+}  // namespace
+
+struct april_buffer {
+  uint64_t magic = 0xA9B1FFEEull;
+  std::vector<Entry> entries;
+  bool alive = true;
+};
+
+struct ProfRec { int kc; hipEvent_t e0, e1; double bytes, flops; int snap; };
+
+struct april_ctx {
+  april_model_cfg cfg;
+  ModelDims dm;
+  hipStream_t stream = nullptr;
+  bool own_stream = false;
+  std::string err;
+  bool bf16 = false, use_mfma = false;
+  size_t esz = 4;
+
+  // weights
+  void* tok_emb = nullptr;
+  std::vector<LayerW> layers;
+  float* final_norm = nullptr;
+  void* lm_head = nullptr;
+  bf16_t* lm_head_s = nullptr;
+  int64_t weight_bytes = 0, decode_weight_bytes = 0;
+  std::vector<void*> allocs;
+
+  // KV pool
+  void* kv_pool = nullptr;
+  KVLayout kvl;
+  int n_pages = 0;
+  int64_t kv_pool_bytes = 0, kv_bytes_per_token = 0;
+  int free_pages_host = 0;
+
+  // scheduler state
+  int n_slots = 0, max_blocks = 0, max_ctx = 0;
+  Slots ds;
+  Ctrl* d_ctrl = nullptr;
+  Ctrl* h_ctrl = nullptr;        // pinned
+  int* d_free_stack = nullptr;
+  int *d_row_slot = nullptr, *d_row_pos = nullptr;
+  std::vector<SlotH> slots;
+  Watch dwatch{};
+  int watch_rows_cap = 0, watch_rows_used = 0, n_watch = 0, watch_cap = 64;
+  std::map<std::pair<long long, int>, int> watch_row_of;
+
+  // prefill staging (device) + pinned host staging
+  int prefill_cap = 0;
+  int *d_pf_row_slot = nullptr, *d_pf_row_pos = nullptr, *d_pf_nrows = nullptr;
+  int *d_pf_srow_slot = nullptr, *d_pf_srow_pos = nullptr, *d_pf_nsrows = nullptr, *d_pf_gather = nullptr;
+  int *d_list_a = nullptr, *d_list_b = nullptr;
+  int* h_stage = nullptr;        // pinned
+  size_t h_stage_ints = 0;
+  int* h_slot_arrays = nullptr;  // pinned: mirrors for D2H/H2D of per-slot ints
+  long long* h_req = nullptr;    // pinned
+
+  // workspaces
+  int m_cap = 0;
+  float *x_res = nullptr, *qkv = nullptr, *q_rot = nullptr, *proj = nullptr, *gu = nullptr, *logits = nullptr;
+  void *h_act = nullptr, *attn_out = nullptr, *act = nullptr, *hf = nullptr;
+  float *rope_cos = nullptr, *rope_sin = nullptr;
+  int s_qkv = 1, s_o = 1, s_down = 1;
+  size_t qkv_stride = 0, proj_stride = 0;
+
+  // pending resume
+  std::vector<Entry> pending;
+  bool have_pending = false;
+  std::vector<april_buffer*> buffers;
+
+  // result storage
+  std::vector<long long> r_req;
+  std::vector<std::vector<int>> r_tokens;
+  std::vector<const int32_t*> r_tok_ptrs;
+  std::vector<int> r_ntok, r_nres;
+  std::vector<std::vector<int>> export_store;
+
+  // profiling
+  int prof_every = 0;
+  std::vector<ProfRec> prof_recs;
+  std::vector<std::pair<hipEvent_t, hipEvent_t>> ev_pool;
+  size_t ev_used = 0;
+  Ctrl* h_snaps = nullptr;       // pinned ring
+  int snaps_cap = 0, snaps_used = 0;
+  april_kernel_stat stats[KC_COUNT];
+  bool prof_now = false;
+  int prof_snap = -1;
+};
+
+namespace {
+
+int fail(april_ctx* c, int code, const char* fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof buf, fmt, ap);
+  va_end(ap);
+  if (c) c->err = buf; else g_init_error = buf;
+  return code;
+}
+
+#define HIPCHK(c, expr)                                                                       \
+  do {                                                                                        \
+    hipError_t e_ = (expr);                                                                   \
+    if (e_ != hipSuccess)                                                                     \
+      return fail(c, APRIL_EDEVICE, "%s failed: %s (%s:%d)", #expr, hipGetErrorString(e_), __FILE__, __LINE__); \
+  } while (0)
+
+template <typename T>
+int dev_alloc(april_ctx* c, T** p, size_t n_elems, bool zero = true) {
+  void* q = nullptr;
+  size_t bytes = std::max<size_t>(n_elems * sizeof(T), 256);
+  hipError_t e = hipMalloc(&q, bytes);
+  if (e != hipSuccess) return fail(c, APRIL_ENOMEM, "hipMalloc(%zu bytes) failed: %s", bytes, hipGetErrorString(e));
+  if (zero) {
+    e = hipMemsetAsync(q, 0, bytes, c->stream);
+    if (e != hipSuccess) return fail(c, APRIL_EDEVICE, "hipMemsetAsync failed: %s", hipGetErrorString(e));
+  }
+  c->allocs.push_back(q);
+  *p = reinterpret_cast<T*>(q);
+  return APRIL_OK;
+}
+int dev_alloc_bytes(april_ctx* c, void** p, size_t bytes, bool zero = true) {
+  char* q = nullptr;
+  int rc = dev_alloc<char>(c, &q, bytes, zero);
+  *p = q;
+  return rc;
+}
+
+const april_tensor* find_tensor(const april_tensor* w, int n, const std::string& name) {
+  for (int i = 0; i < n; ++i)
+    if (w[i].name && name == w[i].name) return &w[i];
+  return nullptr;
+}
+
+// Copy a named tensor (host or device source) to dst (device).
+int fetch_tensor(april_ctx* c, const april_tensor* w, int n, const std::string& name, void* dst, size_t bytes) {
+  const april_tensor* t = find_tensor(w, n, name);
+  if (!t) return fail(c, APRIL_EINVAL, "weight tensor '%s' missing", name.c_str());
+  if ((size_t)t->nbytes != bytes)
+    return fail(c, APRIL_EINVAL, "weight tensor '%s': %lld bytes given, %zu expected", name.c_str(),
+                (long long)t->nbytes, bytes);
+  HIPCHK(c, hipMemcpyAsync(dst, t->data, bytes, t->on_device ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice,
+                           c->stream));
+  if (!t->on_device) HIPCHK(c, hipStreamSynchronize(c->stream));   // the caller's buffer is only borrowed
+  return APRIL_OK;
+}
+
+int pick_ksplit(int N, int K) {
+  const int n_tiles = N / 32, KT = K / 16;
+  if (n_tiles >= 512) return 1;
+  int s = KT / 8;
+  if (s < 1) s = 1;
+  if (s > 16) s = 16;
+  return s;
+}
+
+// ---- profiling helpers -------------------------------------------------------
+struct ProfScope {
+  april_ctx* c; int idx;
+  ProfScope(april_ctx* c_, int kc, double bytes, double flops) : c(c_), idx(-1) {
+    if (!c->prof_now) return;
+    if (c->ev_used == c->ev_pool.size()) {
+      hipEvent_t a, b;
+      if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) return;
+      c->ev_pool.push_back({a, b});
+    }
+    auto& ev = c->ev_pool[c->ev_used++];
+    c->prof_recs.push_back({kc, ev.first, ev.second, bytes, flops, c->prof_snap});
+    idx = (int)c->prof_recs.size() - 1;
+    hipEventRecord(ev.first, c->stream);
+  }
+  ~ProfScope() {
+    if (idx >= 0) hipEventRecord(c->prof_recs[idx].e1, c->stream);
+  }
+};
+
+void prof_collect(april_ctx* c) {   // stream must be idle
+  for (auto& r : c->prof_recs) {
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, r.e0, r.e1) != hipSuccess) continue;
+    double bytes = r.bytes, flops = r.flops;
+    auto& st = c->stats[r.kc];
+    st.launches += 1;
+    st.total_ms += ms;
+    st.alg_bytes += bytes;
+    st.alg_flops += flops;
+  }
+  c->prof_recs.clear();
+  c->ev_used = 0;
+  c->snaps_used = 0;
+}
+
+// ---- forward pass --------------------------------------------------------------
+// rows: the tokens fed; srows: the rows that are sampled (decode: the same rows;
+// prefill: the last token of each sequence, `gather` maps them into `rows`).
+// B / C: host estimates of live rows and summed context, used only for the
+// algorithmic-byte bookkeeping of profiled launches.
+void forward(april_ctx* c, RowCtx rows, RowCtx srows, const int* gather, double B, double C) {
+  const ModelDims& m = c->dm;
+  hipStream_t st = c->stream;
+  const int d = m.d_model, dh = m.head_dim, Hq = m.n_q_heads, Hkv = m.n_kv_heads, F = m.d_ffn, V = m.vocab;
+  const int nq = Hq * dh, nkv = Hkv * dh, nqkv = nq + 2 * nkv;
+  const double e = (double)c->esz;
+  {
+    ProfScope p(c, KC_EMBED, B * d * (e + 4), 0);
+    if (c->bf16) launch_embed<bf16_t>(st, rows, c->ds, (const bf16_t*)c->tok_emb, c->x_res, d);
+    else launch_embed<float>(st, rows, c->ds, (const float*)c->tok_emb, c->x_res, d);
+  }
+  auto norm = [&](RowCtx rc, int n_part, const float* gain, void* out, const int* gth, double rowsB) {
+    ProfScope p(c, KC_NORM, rowsB * d * (4.0 * (2 + (n_part > 0 ? 1 : 0)) + e), 0);
+    if (c->bf16) launch_add_rmsnorm<bf16_t, true>(st, rc, c->x_res, c->proj, n_part, c->proj_stride, gain, (bf16_t*)out, d, m.rms_eps, gth);
+    else launch_add_rmsnorm<float, false>(st, rc, c->x_res, c->proj, n_part, c->proj_stride, gain, (float*)out, d, m.rms_eps, gth);
+  };
+  auto gemm = [&](int kc, RowCtx rc, const void* x, const void* w_plain, const bf16_t* w_s, float* out, int N, int K,
+                  int ks, size_t stride, double rowsB) {
+    ProfScope p(c, kc, (double)N * K * e + rowsB * K * e + rowsB * N * 4.0, 2.0 * rowsB * N * K);
+    if (c->use_mfma) launch_gemm_mfma(st, rc, (const bf16_t*)x, w_s, out, N, K, ks, stride);
+    else if (c->bf16) launch_gemm_ref<bf16_t, true>(st, rc, (const bf16_t*)x, (const bf16_t*)w_plain, out, N, K);
+    else launch_gemm_ref<float, false>(st, rc, (const float*)x, (const float*)w_plain, out, N, K);
+  };
+  for (int l = 0; l < m.n_layers; ++l) {
+    const LayerW& L = c->layers[l];
+    norm(rows, l == 0 ? 0 : c->s_down, L.attn_norm, c->h_act, nullptr, B);
+    gemm(KC_GEMM_QKV, rows, c->h_act, L.wqkv, L.wqkv_s, c->qkv, nqkv, d, c->s_qkv, c->qkv_stride, B);
+    {
+      ProfScope p(c, KC_ROPE, B * (nqkv * 4.0 + nq * 4.0 + 2 * nkv * e), 0);
+      if (c->bf16) launch_rope_append<bf16_t>(st, rows, c->ds, c->qkv, c->s_qkv, c->qkv_stride, c->rope_cos, c->rope_sin, c->q_rot, (bf16_t*)c->kv_pool, c->kvl, l, Hq);
+      else launch_rope_append<float>(st, rows, c->ds, c->qkv, c->s_qkv, c->qkv_stride, c->rope_cos, c->rope_sin, c->q_rot, (float*)c->kv_pool, c->kvl, l, Hq);
+    }
+    {
+      ProfScope p(c, KC_ATTN, C * 2.0 * nkv * e + B * nq * (4.0 + e), 4.0 * C * nq);
+      if (c->bf16) launch_attn_ref<bf16_t, true>(st, rows, c->ds, c->q_rot, (const bf16_t*)c->kv_pool, c->kvl, l, Hq, (bf16_t*)c->attn_out);
+      else launch_attn_ref<float, false>(st, rows, c->ds, c->q_rot, (const float*)c->kv_pool, c->kvl, l, Hq, (float*)c->attn_out);
+    }
+    gemm(KC_GEMM_O, rows, c->attn_out, L.wo, L.wo_s, c->proj, d, nq, c->s_o, c->proj_stride, B);
+    norm(rows, c->s_o, L.mlp_norm, c->h_act, nullptr, B);
+    if (c->use_mfma) {
+      ProfScope p(c, KC_GEMM_GATEUP, 2.0 * F * d * e + B * d * e + B * F * e, 4.0 * B * F * d);
+      launch_gemm_mfma_swiglu(st, rows, (const bf16_t*)c->h_act, L.wg_s, L.wu_s, (bf16_t*)c->act, F, d);
+    } else {
+      gemm(KC_GEMM_GATEUP, rows, c->h_act, L.wgu, nullptr, c->gu, 2 * F, d, 1, 0, B);
+      ProfScope p(c, KC_SILU, B * F * (8.0 + e), 0);
+      if (c->bf16) launch_silu_mul<bf16_t, true>(st, rows, c->gu, F, (bf16_t*)c->act);
+      else launch_silu_mul<float, false>(st, rows, c->gu, F, (float*)c->act);
+    }
+    gemm(KC_GEMM_DOWN, rows, c->act, L.wd, L.wd_s, c->proj, d, F, c->s_down, c->proj_stride, B);
+  }
+  const double SB = gather ? (double)srows.max_rows : B;
+  norm(srows, c->s_down, c->final_norm, c->hf, gather, SB);
+  {
+    ProfScope p(c, KC_GEMM_LMHEAD, (double)V * d * e + SB * d * e, 2.0 * SB * V * d);
+    if (c->use_mfma) launch_gemm_mfma(st, srows, (const bf16_t*)c->hf, c->lm_head_s, c->logits, V, d, 1, 0);
+    else if (c->bf16) launch_gemm_ref<bf16_t, true>(st, srows, (const bf16_t*)c->hf, (const bf16_t*)c->lm_head, c->logits, V, d);
+    else launch_gemm_ref<float, false>(st, srows, (const float*)c->hf, (const float*)c->lm_head, c->logits, V, d);
+  }
+  {
+    ProfScope p(c, KC_SAMPLE, SB * V * 4.0, 0);
+    SamplerCfg sc{c->cfg.sampler, c->cfg.top_k, c->cfg.temperature, (unsigned long long)c->cfg.seed};
+    Watch w = c->cfg.debug_logits ? c->dwatch : Watch{};
+    launch_sample(st, srows, c->ds, c->d_ctrl, c->logits, V, sc, w, 1, nullptr, nullptr, nullptr);
+  }
+}
+
+int alloc_slot(april_ctx* c) {
+  for (int i = 0; i < c->n_slots; ++i)
+    if (c->slots[i].state == SLOT_FREE) return i;
+  return -1;
+}
+
+int upload_slot_tables(april_ctx* c) {
+  // host mirrors are authoritative between steps
+  const int S = c->n_slots;
+  int* a = c->h_slot_arrays;
+  for (int i = 0; i < S; ++i) {
+    const SlotH& s = c->slots[i];
+    a[0 * S + i] = s.prompt_len; a[1 * S + i] = s.gen; a[2 * S + i] = s.limit;
+    a[3 * S + i] = s.state; a[4 * S + i] = s.kv_len; a[5 * S + i] = s.n_blocks;
+    a[6 * S + i] = 0;
+    c->h_req[i] = s.req;
+  }
+  int* dst[7] = {c->ds.prompt_len, c->ds.gen, c->ds.limit, c->ds.state, c->ds.kv_len, c->ds.n_blocks, c->ds.finish_iter};
+  for (int k = 0; k < 7; ++k)
+    HIPCHK(c, hipMemcpyAsync(dst[k], a + k * S, S * sizeof(int), hipMemcpyHostToDevice, c->stream));
+  HIPCHK(c, hipMemcpyAsync(c->ds.req_id, c->h_req, S * sizeof(long long), hipMemcpyHostToDevice, c->stream));
+  return APRIL_OK;
+}
+
+}  // namespace
+
+// =============================================================================
+// C ABI
+// =============================================================================
+extern "C" {
+
+const char* april_last_error(const april_ctx* ctx) { return ctx ? ctx->err.c_str() : g_init_error.c_str(); }
+
+int april_init(const april_model_cfg* cfg, const april_tensor* weights, int32_t n_weights, april_ctx** out) {
+  if (!cfg || !weights || !out) return fail(nullptr, APRIL_EINVAL, "null argument");
+  *out = nullptr;
+  int ndev = 0;
+  if (hipGetDeviceCount(&ndev) != hipSuccess || ndev <= 0) return fail(nullptr, APRIL_EDEVICE, "no HIP device");
+  const april_model_cfg& g = *cfg;
+  if (g.n_experts != 0) return fail(nullptr, APRIL_EINVAL, "routed experts are not built yet");
+  if (g.kv_block_tokens != 16) return fail(nullptr, APRIL_EINVAL, "kv_block_tokens must be 16");
+  if (g.n_layers <= 0 || g.d_model <= 0 || g.n_q_heads <= 0 || g.n_kv_heads <= 0 || g.vocab <= 0 || g.d_ffn <= 0)
+    return fail(nullptr, APRIL_EINVAL, "non-positive model dimension");
+  if (g.n_q_heads % g.n_kv_heads) return fail(nullptr, APRIL_EINVAL, "n_q_heads must be a multiple of n_kv_heads");
+  if (g.head_dim != 32 && g.head_dim != 64 && g.head_dim != 128) return fail(nullptr, APRIL_EINVAL, "head_dim must be 32, 64 or 128");
+  if (g.d_model % 8 || g.d_model > 8192) return fail(nullptr, APRIL_EINVAL, "d_model must be a multiple of 8, at most 8192");
+  if (g.dtype != APRIL_DTYPE_FP32 && g.dtype != APRIL_DTYPE_BF16) return fail(nullptr, APRIL_EINVAL, "bad dtype");
+  if (g.max_inflight <= 0 || g.max_inflight > 2048) return fail(nullptr, APRIL_EINVAL, "max_inflight must be in 1..2048");
+  if (g.max_ctx <= 1) return fail(nullptr, APRIL_EINVAL, "max_ctx too small");
+  if (g.sampler == APRIL_SAMPLER_TOPK && (g.top_k < 1 || g.top_k > 64 || !(g.temperature > 0.f)))
+    return fail(nullptr, APRIL_EINVAL, "top_k must be in 1..64 and temperature > 0");
+  const int nq = g.n_q_heads * g.head_dim, nkv = g.n_kv_heads * g.head_dim, nqkv = nq + 2 * nkv;
+  const int d = g.d_model, F = g.d_ffn, V = g.vocab;
+  if (g.dtype == APRIL_DTYPE_BF16 && (d % 32 || F % 32 || V % 32 || nq % 32 || nqkv % 32))
+    return fail(nullptr, APRIL_EINVAL, "bf16 path needs d_model, d_ffn, vocab, head widths multiple of 32");
+
+  april_ctx* c = new april_ctx();
+  c->cfg = g;
+  c->dm = ModelDims{g.n_layers, d, g.n_q_heads, g.n_kv_heads, g.head_dim, F, V, 0, 0, 0, g.rope_theta, g.rms_eps, 16};
+  c->bf16 = g.dtype == APRIL_DTYPE_BF16;
+  c->esz = c->bf16 ? 2 : 4;
+  const char* gm = getenv("APRIL_GEMM");
+  c->use_mfma = c->bf16 && !(gm && !strcmp(gm, "ref"));
+  for (int i = 0; i < KC_COUNT; ++i) c->stats[i] = april_kernel_stat{kKernelNames[i], 0, 0, 0, 0};
+  auto bail = [&](int rc) { g_init_error = c->err; april_destroy(c); return rc; };
+#define TRY(x) do { int rc_ = (x); if (rc_ != APRIL_OK) return bail(rc_); } while (0)
+#define HIPTRY(expr) do { hipError_t e_ = (expr); if (e_ != hipSuccess) { fail(c, APRIL_EDEVICE, "%s failed: %s", #expr, hipGetErrorString(e_)); return bail(APRIL_EDEVICE); } } while (0)
+
+  if (g.stream) c->stream = (hipStream_t)g.stream;
+  else { HIPTRY(hipStreamCreate(&c->stream)); c->own_stream = true; }
+
+  // ---- weights ------------------------------------------------------------------
+  const size_t e = c->esz;
+  size_t stage_bytes = std::max<size_t>((size_t)V * d, (size_t)2 * F * d) * e;
+  void* stage = nullptr;
+  if (c->use_mfma) HIPTRY(hipMalloc(&stage, stage_bytes));
+  auto free_stage = [&]() { if (stage) { hipFree(stage); stage = nullptr; } };
+#define TRYW(x) do { int rc_ = (x); if (rc_ != APRIL_OK) { free_stage(); return bail(rc_); } } while (0)
+
+  TRYW(dev_alloc_bytes(c, &c->tok_emb, (size_t)V * d * e, false));
+  TRYW(fetch_tensor(c, weights, n_weights, "tok_emb", c->tok_emb, (size_t)V * d * e));
+  TRYW(dev_alloc(c, &c->final_norm, d, false));
+  TRYW(fetch_tensor(c, weights, n_weights, "final_norm", c->final_norm, d * sizeof(float)));
+  c->weight_bytes = (int64_t)V * d * e;
+  c->layers.resize(g.n_layers);
+  const bool keep_plain = !c->use_mfma;
+  // Fetch a matrix into `plain` (kept) or into the staging buffer, and re-lay it for MFMA.
+  auto load_matrix = [&](const std::string& name, int N, int K, void* plain_dst, bf16_t** shuffled) -> int {
+    void* dstp = keep_plain ? plain_dst : stage;
+    int rc = fetch_tensor(c, weights, n_weights, name, dstp, (size_t)N * K * e);
+    if (rc != APRIL_OK) return rc;
+    if (c->use_mfma && shuffled) {
+      rc = dev_alloc(c, shuffled, (size_t)N * K, false);
+      if (rc != APRIL_OK) return rc;
+      launch_shuffle_weights(c->stream, (const bf16_t*)dstp, *shuffled, N, K);
+      HIPCHK(c, hipStreamSynchronize(c->stream));
+    }
+    return APRIL_OK;
+  };
+  for (int l = 0; l < g.n_layers; ++l) {
+    LayerW& L = c->layers[l];
+    const std::string sl = "." + std::to_string(l);
+    TRYW(dev_alloc(c, &L.attn_norm, d, false));
+    TRYW(dev_alloc(c, &L.mlp_norm, d, false));
+    TRYW(fetch_tensor(c, weights, n_weights, "attn_norm" + sl, L.attn_norm, d * sizeof(float)));
+    TRYW(fetch_tensor(c, weights, n_weights, "mlp_norm" + sl, L.mlp_norm, d * sizeof(float)));
+    // q, k, v concatenated along the output dimension
+    void* qkv_dst = nullptr;
+    if (keep_plain) { TRYW(dev_alloc_bytes(c, &L.wqkv, (size_t)nqkv * d * e, false)); qkv_dst = L.wqkv; }
+    else qkv_dst = stage;
+    TRYW(fetch_tensor(c, weights, n_weights, "wq" + sl, qkv_dst, (size_t)nq * d * e));
+    TRYW(fetch_tensor(c, weights, n_weights, "wk" + sl, (char*)qkv_dst + (size_t)nq * d * e, (size_t)nkv * d * e));
+    TRYW(fetch_tensor(c, weights, n_weights, "wv" + sl, (char*)qkv_dst + (size_t)(nq + nkv) * d * e, (size_t)nkv * d * e));
+    if (c->use_mfma) {
+      TRYW(dev_alloc(c, &L.wqkv_s, (size_t)nqkv * d, false));
+      launch_shuffle_weights(c->stream, (const bf16_t*)qkv_dst, L.wqkv_s, nqkv, d);
+      HIPTRY(hipStreamSynchronize(c->stream));
+    }
+    if (keep_plain) {
+      TRYW(dev_alloc_bytes(c, &L.wo, (size_t)d * nq * e, false));
+      TRYW(dev_alloc_bytes(c, &L.wgu, (size_t)2 * F * d * e, false));
+      TRYW(dev_alloc_bytes(c, &L.wd, (size_t)d * F * e, false));
+      TRYW(load_matrix("wo" + sl, d, nq, L.wo, nullptr));
+      TRYW(load_matrix("w_gate" + sl, F, d, L.wgu, nullptr));
+      TRYW(load_matrix("w_up" + sl, F, d, (char*)L.wgu + (size_t)F * d * e, nullptr));
+      TRYW(load_matrix("w_down" + sl, d, F, L.wd, nullptr));
+    } else {
+      TRYW(load_matrix("wo" + sl, d, nq, nullptr, &L.wo_s));
+      TRYW(load_matrix("w_gate" + sl, F, d, nullptr, &L.wg_s));
+      TRYW(load_matrix("w_up" + sl, F, d, nullptr, &L.wu_s));
+      TRYW(load_matrix("w_down" + sl, d, F, nullptr, &L.wd_s));
+    }
+    c->decode_weight_bytes += ((int64_t)nqkv * d + (int64_t)d * nq + (int64_t)3 * F * d) * e + 2 * d * 4;
+  }
+  if (keep_plain) {
+    TRYW(dev_alloc_bytes(c, &c->lm_head, (size_t)V * d * e, false));
+    TRYW(load_matrix("lm_head", V, d, c->lm_head, nullptr));
+  } else {
+    TRYW(load_matrix("lm_head", V, d, nullptr, &c->lm_head_s));
+  }
+  free_stage();
+  c->decode_weight_bytes += (int64_t)V * d * e + d * 4;
+  c->weight_bytes += c->decode_weight_bytes;
+
+  // ---- scheduler state ------------------------------------------------------------
+  const int S = g.max_inflight;
+  c->n_slots = S;
+  c->max_ctx = g.max_ctx;
+  c->max_blocks = ceil_div(g.max_ctx, 16);
+  c->slots.assign(S, SlotH());
+  c->ds.max_blocks = c->max_blocks;
+  c->ds.max_ctx = c->max_ctx;
+  TRY(dev_alloc(c, &c->ds.req_id, S));
+  TRY(dev_alloc(c, &c->ds.prompt_len, S)); TRY(dev_alloc(c, &c->ds.gen, S)); TRY(dev_alloc(c, &c->ds.limit, S));
+  TRY(dev_alloc(c, &c->ds.state, S)); TRY(dev_alloc(c, &c->ds.kv_len, S)); TRY(dev_alloc(c, &c->ds.n_blocks, S));
+  TRY(dev_alloc(c, &c->ds.finish_iter, S));
+  TRY(dev_alloc(c, &c->ds.block_table, (size_t)S * c->max_blocks));
+  TRY(dev_alloc(c, &c->ds.tokens, (size_t)S * c->max_ctx));
+  c->ds.forced = nullptr;
+  if (g.debug_logits) {
+    TRY(dev_alloc(c, &c->ds.forced, (size_t)S * c->max_ctx, false));
+    launch_fill_i32(c->stream, c->ds.forced, -1, (size_t)S * c->max_ctx);
+  }
+  TRY(dev_alloc(c, &c->d_ctrl, 1));
+  HIPTRY(hipHostMalloc((void**)&c->h_ctrl, sizeof(Ctrl)));
+  HIPTRY(hipHostMalloc((void**)&c->h_slot_arrays, (size_t)8 * S * sizeof(int)));
+  HIPTRY(hipHostMalloc((void**)&c->h_req, (size_t)S * sizeof(long long)));
+  TRY(dev_alloc(c, &c->d_row_slot, S)); TRY(dev_alloc(c, &c->d_row_pos, S));
+  TRY(dev_alloc(c, &c->d_list_a, 2048)); TRY(dev_alloc(c, &c->d_list_b, 2048));
+
+  // ---- KV pool --------------------------------------------------------------------
+  c->kv_bytes_per_token = (int64_t)2 * g.n_layers * nkv * e;
+  const int64_t page_bytes = c->kv_bytes_per_token * 16;
+  int64_t pool = g.kv_pool_bytes;
+  if (pool <= 0) pool = (int64_t)S * c->max_blocks * page_bytes;
+  c->n_pages = (int)std::min<int64_t>(pool / page_bytes, (int64_t)1 << 30);
+  if (c->n_pages < 1) { fail(c, APRIL_ENOMEM, "KV pool smaller than one page"); return bail(APRIL_ENOMEM); }
+  c->kv_pool_bytes = (int64_t)c->n_pages * page_bytes;
+  TRY(dev_alloc_bytes(c, &c->kv_pool, (size_t)c->kv_pool_bytes, false));
+  c->kvl.n_kv_heads = g.n_kv_heads; c->kvl.head_dim = g.head_dim; c->kvl.blk = 16;
+  c->kvl.kv_stride = (size_t)c->n_pages * nkv * 16;
+  c->kvl.layer_stride = 2 * c->kvl.kv_stride;
+  TRY(dev_alloc(c, &c->d_free_stack, c->n_pages, false));
+  launch_init_free_stack(c->stream, c->d_free_stack, c->n_pages);
+  c->free_pages_host = c->n_pages;
+  memset(c->h_ctrl, 0, sizeof(Ctrl));
+  c->h_ctrl->free_top = c->n_pages;
+  c->h_ctrl->n_slots = S;
+  c->h_ctrl->eos_token = g.eos_token;
+  c->h_ctrl->stop = 1;
+  HIPTRY(hipMemcpyAsync(c->d_ctrl, c->h_ctrl, sizeof(Ctrl), hipMemcpyHostToDevice, c->stream));
+  HIPTRY(hipStreamSynchronize(c->stream));
+
+  // ---- workspaces -----------------------------------------------------------------
+  c->prefill_cap = std::max(g.max_ctx, 4096);
+  c->m_cap = ((std::max(c->prefill_cap, S) + 31) / 32) * 32;
+  const size_t M = c->m_cap;
+  if (c->use_mfma) { c->s_qkv = pick_ksplit(nqkv, d); c->s_o = pick_ksplit(d, nq); c->s_down = pick_ksplit(d, F); }
+  c->qkv_stride = M * nqkv;
+  c->proj_stride = M * d;
+  TRY(dev_alloc(c, &c->x_res, M * d));
+  TRY(dev_alloc(c, &c->qkv, (size_t)c->s_qkv * c->qkv_stride));
+  TRY(dev_alloc(c, &c->q_rot, M * nq));
+  TRY(dev_alloc(c, &c->proj, (size_t)std::max(c->s_o, c->s_down) * c->proj_stride));
+  if (!c->use_mfma) TRY(dev_alloc(c, &c->gu, M * 2 * F));
+  const size_t SR = ((size_t)S + 31) / 32 * 32;
+  TRY(dev_alloc(c, &c->logits, SR * V));
+  TRY(dev_alloc_bytes(c, &c->h_act, M * d * e));
+  TRY(dev_alloc_bytes(c, &c->attn_out, M * nq * e));
+  TRY(dev_alloc_bytes(c, &c->act, M * F * e));
+  TRY(dev_alloc_bytes(c, &c->hf, SR * d * e));
+  TRY(dev_alloc(c, &c->rope_cos, (size_t)g.max_ctx * g.head_dim / 2, false));
+  TRY(dev_alloc(c, &c->rope_sin, (size_t)g.max_ctx * g.head_dim / 2, false));
+  launch_rope_table(c->stream, c->rope_cos, c->rope_sin, g.max_ctx, g.head_dim, g.rope_theta);
+  TRY(dev_alloc(c, &c->d_pf_row_slot, M)); TRY(dev_alloc(c, &c->d_pf_row_pos, M));
+  TRY(dev_alloc(c, &c->d_pf_nrows, 1)); TRY(dev_alloc(c, &c->d_pf_nsrows, 1));
+  TRY(dev_alloc(c, &c->d_pf_srow_slot, S)); TRY(dev_alloc(c, &c->d_pf_srow_pos, S)); TRY(dev_alloc(c, &c->d_pf_gather, S));
+  c->h_stage_ints = 2 * M + 8 * (size_t)S + 64;
+  HIPTRY(hipHostMalloc((void**)&c->h_stage, c->h_stage_ints * sizeof(int)));
+
+  // ---- parity-mode capture ----------------------------------------------------------
+  if (g.debug_logits) {
+    c->watch_rows_cap = (int)std::max<int64_t>(16, std::min<int64_t>(4096, ((int64_t)512 << 20) / ((int64_t)V * 4)));
+    TRY(dev_alloc(c, &c->dwatch.req, c->watch_cap)); TRY(dev_alloc(c, &c->dwatch.first, c->watch_cap));
+    TRY(dev_alloc(c, &c->dwatch.count, c->watch_cap)); TRY(dev_alloc(c, &c->dwatch.row0, c->watch_cap));
+    TRY(dev_alloc(c, &c->dwatch.logits, (size_t)c->watch_rows_cap * V));
+    TRY(dev_alloc(c, &c->dwatch.sampled, c->watch_rows_cap)); TRY(dev_alloc(c, &c->dwatch.filled, c->watch_rows_cap));
+  }
+  HIPTRY(hipStreamSynchronize(c->stream));
+  *out = c;
+  return APRIL_OK;
+#undef TRY
+#undef TRYW
+#undef HIPTRY
+}
+
+void april_destroy(april_ctx* c) {
+  if (!c) return;
+  if (c->stream) hipStreamSynchronize(c->stream);
+  for (void* p : c->allocs) hipFree(p);
+  if (c->h_ctrl) hipHostFree(c->h_ctrl);
+  if (c->h_slot_arrays) hipHostFree(c->h_slot_arrays);
+  if (c->h_req) hipHostFree(c->h_req);
+  if (c->h_stage) hipHostFree(c->h_stage);
+  if (c->h_snaps) hipHostFree(c->h_snaps);
+  for (auto& ev : c->ev_pool) { hipEventDestroy(ev.first); hipEventDestroy(ev.second); }
+  for (april_buffer* b : c->buffers) delete b;
+  if (c->own_stream && c->stream) hipStreamDestroy(c->stream);
+  delete c;
+}
+
+int april_get_info(april_ctx* c, april_info* out) {
+  if (!c || !out) return APRIL_EINVAL;
+  size_t fr = 0, tot = 0;
+  HIPCHK(c, hipMemGetInfo(&fr, &tot));
+  out->hbm_total = (int64_t)tot; out->hbm_free = (int64_t)fr;
+  out->kv_pool_bytes = c->kv_pool_bytes; out->kv_blocks_total = c->n_pages; out->kv_blocks_free = c->free_pages_host;
+  out->weight_bytes = c->weight_bytes; out->decode_weight_bytes = c->decode_weight_bytes;
+  out->kv_bytes_per_token = c->kv_bytes_per_token;
+  return APRIL_OK;
+}
+
+static april_buffer* find_buffer(const april_ctx* c, const april_buffer* b) {
+  for (april_buffer* x : c->buffers)
+    if (x == b && x->alive && x->magic == 0xA9B1FFEEull) return x;
+  return nullptr;
+}
+static april_buffer* new_buffer(april_ctx* c) {
+  april_buffer* b = new april_buffer();
+  c->buffers.push_back(b);
+  return b;
+}
+static void retire_buffer(april_ctx* c, april_buffer* b) {
+  b->alive = false;
+  b->entries.clear();
+  auto it = std::find(c->buffers.begin(), c->buffers.end(), b);
+  if (it != c->buffers.end()) c->buffers.erase(it);
+  delete b;
+}
+
+int april_resume(april_ctx* c, april_buffer* buffer) {
+  if (!c) return APRIL_EINVAL;
+  april_buffer* b = find_buffer(c, buffer);
+  if (!b) return fail(c, APRIL_EHANDLE, "april_resume: unknown or stale buffer handle");
+  for (auto& e : b->entries) c->pending.push_back(std::move(e));
+  c->have_pending = true;
+  retire_buffer(c, b);
+  return APRIL_OK;
+}
+
+int april_buffer_size(const april_ctx* c, const april_buffer* buffer) {
+  if (!c) return APRIL_EINVAL;
+  april_buffer* b = find_buffer(c, buffer);
+  if (!b) return APRIL_EHANDLE;
+  return (int)b->entries.size();
+}
+
+// Make sure the host copy of an entry's tokens is current (slot-resident entries).
+static int sync_entry_tokens(april_ctx* c, Entry& e) {
+  if (e.slot < 0) return APRIL_OK;
+  const SlotH& s = c->slots[e.slot];
+  e.prompt = s.prompt;
+  e.generated.resize(s.gen);
+  if (s.gen > 0) {
+    HIPCHK(c, hipMemcpyAsync(e.generated.data(), c->ds.tokens + (size_t)e.slot * c->max_ctx + s.prompt_len,
+                             (size_t)s.gen * sizeof(int), hipMemcpyDeviceToHost, c->stream));
+    HIPCHK(c, hipStreamSynchronize(c->stream));
+  }
+  return APRIL_OK;
+}
+
+int april_buffer_export(april_ctx* c, const april_buffer* buffer, april_partial* out, int32_t cap) {
+  if (!c) return APRIL_EINVAL;
+  april_buffer* b = find_buffer(c, buffer);
+  if (!b) return fail(c, APRIL_EHANDLE, "april_buffer_export: unknown or stale buffer handle");
+  const int n = (int)b->entries.size();
+  for (int i = 0; i < n && i < cap; ++i) {
+    Entry& e = b->entries[i];
+    int rc = sync_entry_tokens(c, e);
+    if (rc != APRIL_OK) return rc;
+    out[i].request_id = e.req;
+    out[i].prompt = e.prompt.data(); out[i].n_prompt = (int)e.prompt.size();
+    out[i].generated = e.generated.data(); out[i].n_generated = (int)e.generated.size();
+    out[i].limit = e.limit; out[i].n_resumes = e.n_resumes; out[i].done = e.done;
+    out[i].kv_resident = (e.slot >= 0 && c->slots[e.slot].kv_len > 0) ? 1 : 0;
+  }
+  return n;
+}
+
+int april_buffer_import(april_ctx* c, const april_partial* in, int32_t n, april_buffer** out) {
+  if (!c || !out || (n > 0 && !in)) return APRIL_EINVAL;
+  for (int i = 0; i < n; ++i) {
+    if (in[i].n_prompt <= 0 || !in[i].prompt || in[i].n_generated < 0 || in[i].limit <= 0 ||
+        (in[i].n_generated > 0 && !in[i].generated))
+      return fail(c, APRIL_EINVAL, "april_buffer_import: bad entry %d", i);
+    if (in[i].n_prompt + in[i].limit > c->max_ctx)
+      return fail(c, APRIL_EINVAL, "april_buffer_import: entry %d exceeds max_ctx", i);
+    const bool done = in[i].n_generated >= in[i].limit;
+    if ((in[i].done != 0) != done && in[i].done)
+      return fail(c, APRIL_EINVAL, "april_buffer_import: entry %d flagged done below its limit", i);
+  }
+  april_buffer* b = new_buffer(c);
+  for (int i = 0; i < n; ++i) {
+    Entry e;
+    e.req = in[i].request_id;
+    e.prompt.assign(in[i].prompt, in[i].prompt + in[i].n_prompt);
+    e.generated.assign(in[i].generated, in[i].generated + in[i].n_generated);
+    e.limit = in[i].limit; e.n_resumes = in[i].n_resumes;
+    e.done = in[i].n_generated >= in[i].limit ? 1 : (in[i].done ? 1 : 0);
+    b->entries.push_back(std::move(e));
+  }
+  *out = b;
+  return APRIL_OK;
+}
+
+static int free_slot_pages(april_ctx* c, const std::vector<int>& slot_ids) {
+  // returns the pages of the listed slots to the device stack, 2048 slots per launch
+  if (slot_ids.empty()) return APRIL_OK;
+  std::vector<int> with_pages;
+  for (int s : slot_ids) if (c->slots[s].n_blocks > 0) with_pages.push_back(s);
+  if (with_pages.empty()) return APRIL_OK;
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  memcpy(c->h_stage, with_pages.data(), with_pages.size() * sizeof(int));
+  HIPCHK(c, hipMemcpyAsync(c->d_list_a, c->h_stage, with_pages.size() * sizeof(int), hipMemcpyHostToDevice, c->stream));
+  launch_free_slots(c->stream, c->d_ctrl, c->ds, c->d_list_a, (int)with_pages.size(), c->d_free_stack);
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  for (int s : with_pages) { c->free_pages_host += c->slots[s].n_blocks; c->slots[s].n_blocks = 0; c->slots[s].kv_len = 0; }
+  return APRIL_OK;
+}
+
+int april_buffer_drop_kv(april_ctx* c, april_buffer* buffer) {
+  if (!c) return APRIL_EINVAL;
+  april_buffer* b = find_buffer(c, buffer);
+  if (!b) return fail(c, APRIL_EHANDLE, "april_buffer_drop_kv: unknown or stale buffer handle");
+  std::vector<int> ids;
+  for (auto& e : b->entries) if (e.slot >= 0) ids.push_back(e.slot);
+  return free_slot_pages(c, ids);
+}
+
+void april_buffer_free(april_ctx* c, april_buffer* buffer) {
+  if (!c) return;
+  april_buffer* b = find_buffer(c, buffer);
+  if (!b) return;
+  std::vector<int> ids;
+  for (auto& e : b->entries) if (e.slot >= 0) ids.push_back(e.slot);
+  free_slot_pages(c, ids);
+  for (int s : ids) c->slots[s] = SlotH();
+  retire_buffer(c, b);
+}
+
+int april_debug_watch(april_ctx* c, int64_t request_id, int32_t first_gen, int32_t n_gen) {
+  if (!c) return APRIL_EINVAL;
+  if (!c->cfg.debug_logits) return fail(c, APRIL_EINVAL, "context was not created with debug_logits");
+  if (n_gen <= 0 || first_gen < 0) return fail(c, APRIL_EINVAL, "bad watch range");
+  if (c->n_watch >= c->watch_cap || c->watch_rows_used + n_gen > c->watch_rows_cap)
+    return fail(c, APRIL_ENOMEM, "watch capacity exceeded");
+  long long req = request_id;
+  int row0 = c->watch_rows_used;
+  const int i = c->n_watch;
+  HIPCHK(c, hipMemcpy(c->dwatch.req + i, &req, sizeof req, hipMemcpyHostToDevice));
+  HIPCHK(c, hipMemcpy(c->dwatch.first + i, &first_gen, sizeof(int), hipMemcpyHostToDevice));
+  HIPCHK(c, hipMemcpy(c->dwatch.count + i, &n_gen, sizeof(int), hipMemcpyHostToDevice));
+  HIPCHK(c, hipMemcpy(c->dwatch.row0 + i, &row0, sizeof(int), hipMemcpyHostToDevice));
+  for (int k = 0; k < n_gen; ++k) c->watch_row_of[{req, first_gen + k}] = row0 + k;
+  c->watch_rows_used += n_gen;
+  c->n_watch += 1;
+  return APRIL_OK;
+}
+
+int april_debug_logits(april_ctx* c, int64_t request_id, int32_t gen_index, float* out_logits, int32_t* out_sampled) {
+  if (!c) return APRIL_EINVAL;
+  auto it = c->watch_row_of.find({(long long)request_id, gen_index});
+  if (it == c->watch_row_of.end()) return fail(c, APRIL_EHANDLE, "request/generated index is not watched");
+  const int row = it->second;
+  int filled = 0, sampled = -1;
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  HIPCHK(c, hipMemcpy(&filled, c->dwatch.filled + row, sizeof(int), hipMemcpyDeviceToHost));
+  if (!filled) return fail(c, APRIL_EHANDLE, "watched logits were not produced yet");
+  if (out_logits)
+    HIPCHK(c, hipMemcpy(out_logits, c->dwatch.logits + (size_t)row * c->dm.vocab, (size_t)c->dm.vocab * sizeof(float), hipMemcpyDeviceToHost));
+  HIPCHK(c, hipMemcpy(&sampled, c->dwatch.sampled + row, sizeof(int), hipMemcpyDeviceToHost));
+  if (out_sampled) *out_sampled = sampled;
+  return APRIL_OK;
+}
+
+int april_sample_rows(april_ctx* c, const float* logits, int32_t n_rows, const int64_t* request_ids,
+                      const int32_t* gen_index, int32_t* out_tokens) {
+  if (!c || !logits || !request_ids || !gen_index || !out_tokens || n_rows <= 0) return APRIL_EINVAL;
+  long long* d_req = nullptr; int *d_gen = nullptr, *d_out = nullptr, *d_n = nullptr;
+  HIPCHK(c, hipMalloc((void**)&d_req, n_rows * sizeof(long long)));
+  HIPCHK(c, hipMalloc((void**)&d_gen, n_rows * sizeof(int)));
+  HIPCHK(c, hipMalloc((void**)&d_out, n_rows * sizeof(int)));
+  HIPCHK(c, hipMalloc((void**)&d_n, sizeof(int)));
+  HIPCHK(c, hipMemcpy(d_req, request_ids, n_rows * sizeof(long long), hipMemcpyHostToDevice));
+  HIPCHK(c, hipMemcpy(d_gen, gen_index, n_rows * sizeof(int), hipMemcpyHostToDevice));
+  HIPCHK(c, hipMemcpy(d_n, &n_rows, sizeof(int), hipMemcpyHostToDevice));
+  RowCtx rc{nullptr, nullptr, d_n, nullptr, n_rows};
+  SamplerCfg sc{c->cfg.sampler, c->cfg.top_k, c->cfg.temperature, (unsigned long long)c->cfg.seed};
+  launch_sample(c->stream, rc, c->ds, nullptr, logits, c->dm.vocab, sc, Watch{}, 0, d_req, d_gen, d_out);
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  HIPCHK(c, hipMemcpy(out_tokens, d_out, n_rows * sizeof(int), hipMemcpyDeviceToHost));
+  hipFree(d_req); hipFree(d_gen); hipFree(d_out); hipFree(d_n);
+  return APRIL_OK;
+}
+
+int april_profile_enable(april_ctx* c, int32_t every) {
+  if (!c || every < 0) return APRIL_EINVAL;
+  c->prof_every = every;
+  if (every > 0 && !c->h_snaps) {
+    c->snaps_cap = 4096;
+    HIPCHK(c, hipHostMalloc((void**)&c->h_snaps, c->snaps_cap * sizeof(Ctrl)));
+  }
+  return APRIL_OK;
+}
+int april_profile_reset(april_ctx* c) {
+  if (!c) return APRIL_EINVAL;
+  for (int i = 0; i < KC_COUNT; ++i) c->stats[i] = april_kernel_stat{kKernelNames[i], 0, 0, 0, 0};
+  return APRIL_OK;
+}
+int april_profile_get(april_ctx* c, april_kernel_stat* out, int32_t cap) {
+  if (!c || !out) return APRIL_EINVAL;
+  int n = 0;
+  for (int i = 0; i < KC_COUNT && n < cap; ++i) out[n++] = c->stats[i];
+  return n;
+}
+
+// -----------------------------------------------------------------------------
+// The rollout step
+// -----------------------------------------------------------------------------
+int april_rollout_step(april_ctx* c, const april_request* new_reqs, int32_t n_new_avail, int32_t N_target,
+                       int32_t N_over, int32_t max_new, april_step_result* out) {
+  if (!c || !out) return APRIL_EINVAL;
+  if (N_target <= 0 || N_over < N_target || max_new <= 0 || n_new_avail < 0 || (n_new_avail > 0 && !new_reqs))
+    return fail(c, APRIL_EINVAL, "bad step arguments (need 0 < N_target <= N_overprovision, max_new > 0)");
+  const double t_begin = now_s();
+  hipStream_t st = c->stream;
+  const int blk = 16;
+
+  // ---- admission plan (nothing is modified until every check has passed) -------------
+  std::vector<Entry>& pend = c->pending;
+  std::sort(pend.begin(), pend.end(), [](const Entry& a, const Entry& b) { return a.req < b.req; });
+  std::vector<int> deliver_idx, resume_idx;          // indices into pend
+  for (int i = 0; i < (int)pend.size(); ++i) (pend[i].done ? deliver_idx : resume_idx).push_back(i);
+  const int D = (int)deliver_idx.size();
+  int n_inflight = (int)resume_idx.size();
+  int n_admit = 0;
+  while (n_inflight + n_admit < N_over - D && n_admit < n_new_avail) ++n_admit;
+  n_inflight += n_admit;
+  if (D + n_inflight < N_target)
+    return fail(c, APRIL_ESTARVED, "only %d rollouts available, %d needed", D + n_inflight, N_target);
+  int slots_needed = n_admit;
+  for (int i : resume_idx) if (pend[i].slot < 0) ++slots_needed;
+  int slots_free = 0;
+  for (auto& s : c->slots) if (s.state == SLOT_FREE) ++slots_free;
+  if (slots_needed > slots_free) return fail(c, APRIL_ENOMEM, "%d sequence slots needed, %d free (max_inflight)", slots_needed, slots_free);
+  for (int i = 0; i < n_admit; ++i) {
+    const april_request& r = new_reqs[i];
+    if (r.n_tokens <= 0 || !r.tokens) return fail(c, APRIL_EINVAL, "request %d: empty prompt", i);
+    const int lim = r.forced_len > 0 ? std::min(r.forced_len, max_new) : max_new;
+    if (r.n_tokens + lim > c->max_ctx) return fail(c, APRIL_EINVAL, "request %d: prompt %d + limit %d exceeds max_ctx %d", i, r.n_tokens, lim, c->max_ctx);
+    for (int k = 0; k < r.n_tokens; ++k)
+      if (r.tokens[k] < 0 || r.tokens[k] >= c->dm.vocab) return fail(c, APRIL_EINVAL, "request %d: token out of range", i);
+    if (r.forced_tokens && !c->cfg.debug_logits) return fail(c, APRIL_EINVAL, "forced_tokens need a debug_logits context");
+  }
+  // worst-case page demand of the step (no preemption: refuse up front)
+  {
+    long long need = 0;
+    for (int i : resume_idx) {
+      const Entry& e = pend[i];
+      const int P = e.slot >= 0 ? c->slots[e.slot].prompt_len : (int)e.prompt.size();
+      const int have = e.slot >= 0 ? c->slots[e.slot].n_blocks : 0;
+      need += ceil_div(P + e.limit, blk) - have;
+    }
+    for (int i = 0; i < n_admit; ++i) {
+      const april_request& r = new_reqs[i];
+      const int lim = r.forced_len > 0 ? std::min(r.forced_len, max_new) : max_new;
+      need += ceil_div(r.n_tokens + lim, blk);
+    }
+    if (need > c->free_pages_host)
+      return fail(c, APRIL_ENOMEM, "KV pool: step may need %lld pages, %d free", need, c->free_pages_host);
+  }
+
+  // ---- commit admission ---------------------------------------------------------------
+  struct Fl { int slot; };
+  std::vector<int> inflight;            // slots in flight this step
+  std::vector<int> prefill_slots;       // need (re-)prefill
+  std::vector<Entry> deliver;           // surplus-complete from the last step, ascending id
+  int64_t prefill_tokens = 0, reprefill_tokens = 0;
+  int n_resident = 0;
+  for (int i : deliver_idx) deliver.push_back(pend[i]);
+  for (int i : resume_idx) {
+    Entry& e = pend[i];
+    int s = e.slot;
+    if (s < 0) {                         // token-level entry: take a slot, upload its tokens
+      s = alloc_slot(c);
+      SlotH& sh = c->slots[s];
+      sh = SlotH();
+      sh.req = e.req; sh.prompt = e.prompt; sh.prompt_len = (int)e.prompt.size();
+      sh.gen = (int)e.generated.size(); sh.limit = e.limit; sh.n_resumes = e.n_resumes;
+      sh.state = SLOT_PARKED;
+      std::vector<int> all(e.prompt);
+      all.insert(all.end(), e.generated.begin(), e.generated.end());
+      HIPCHK(c, hipMemcpyAsync(c->ds.tokens + (size_t)s * c->max_ctx, all.data(), all.size() * sizeof(int), hipMemcpyHostToDevice, st));
+      HIPCHK(c, hipStreamSynchronize(st));
+    }
+    SlotH& sh = c->slots[s];
+    sh.n_resumes += 1;
+    if (sh.kv_len > 0) { sh.state = SLOT_LIVE; ++n_resident; }
+    else { sh.state = SLOT_PREFILL; prefill_slots.push_back(s); reprefill_tokens += sh.prompt_len + sh.gen; }
+    inflight.push_back(s);
+  }
+  for (int i = 0; i < n_admit; ++i) {
+    const april_request& r = new_reqs[i];
+    const int s = alloc_slot(c);
+    SlotH& sh = c->slots[s];
+    sh = SlotH();
+    sh.req = r.request_id; sh.prompt.assign(r.tokens, r.tokens + r.n_tokens); sh.prompt_len = r.n_tokens;
+    sh.limit = r.forced_len > 0 ? std::min(r.forced_len, max_new) : max_new;
+    sh.state = SLOT_PREFILL;
+    HIPCHK(c, hipMemcpyAsync(c->ds.tokens + (size_t)s * c->max_ctx, r.tokens, (size_t)r.n_tokens * sizeof(int), hipMemcpyHostToDevice, st));
+    if (c->ds.forced) {
+      std::vector<int> f(c->max_ctx, -1);
+      if (r.forced_tokens) for (int k = 0; k < r.n_forced_tokens && k < c->max_ctx; ++k) f[k] = r.forced_tokens[k];
+      HIPCHK(c, hipMemcpyAsync(c->ds.forced + (size_t)s * c->max_ctx, f.data(), (size_t)c->max_ctx * sizeof(int), hipMemcpyHostToDevice, st));
+      HIPCHK(c, hipStreamSynchronize(st));
+    }
+    prefill_slots.push_back(s);
+    prefill_tokens += r.n_tokens;
+    inflight.push_back(s);
+  }
+  HIPCHK(c, hipStreamSynchronize(st));
+  pend.clear();
+  c->have_pending = false;
+
+  // ---- run ------------------------------------------------------------------------------
+  double t_prefill = 0, t_decode = 0;
+  long long iters = 0, sum_live = 0, sum_ctx = 0, it1_live = 0, it1_ctx = 0;
+  std::vector<int> snap(7 * c->n_slots);
+  if (D < N_target) {
+    { int rc = upload_slot_tables(c); if (rc != APRIL_OK) return rc; }
+    Ctrl& hc = *c->h_ctrl;
+    hc.n_rows = 0; hc.finished = D; hc.n_target = N_target; hc.stop = 0; hc.iter = 0; hc.stop_iter = -1;
+    hc.free_top = c->free_pages_host; hc.error = 0; hc.n_slots = c->n_slots; hc.eos_token = c->cfg.eos_token;
+    hc.n_watch = c->n_watch; hc.sum_live = 0; hc.sum_ctx = 0; hc.iter_ctx = 0;
+    HIPCHK(c, hipMemcpyAsync(c->d_ctrl, &hc, sizeof(Ctrl), hipMemcpyHostToDevice, st));
+    HIPCHK(c, hipStreamSynchronize(st));
+
+    // Upper bound on the iterations of this step when only length limits end rollouts:
+    // the (N - D)-th smallest remaining length.  With an EOS token the device may stop
+    // earlier; the host then polls the control block between chunks.
+    std::vector<int> rem;
+    for (int s : inflight) rem.push_back(c->slots[s].limit - c->slots[s].gen);
+    std::sort(rem.begin(), rem.end());
+    const int T_bound = rem[N_target - D - 1];
+    const bool exact = c->cfg.eos_token < 0;
+
+    RowCtx drc{c->d_row_slot, c->d_row_pos, &c->d_ctrl->n_rows, &c->d_ctrl->stop, 0};
+    const double t0 = now_s();
+    // iteration 1: resident rollouts decode, the others are (re-)prefilled
+    launch_sched(st, c->d_ctrl, c->ds, c->d_row_slot, c->d_row_pos, c->d_free_stack, blk, 0);
+    if (n_resident > 0) {
+      drc.max_rows = n_resident;
+      forward(c, drc, drc, nullptr, n_resident, 0);
+    }
+    // prefill in chunks of whole sequences
+    size_t pi = 0;
+    while (pi < prefill_slots.size()) {
+      int rows = 0, nseq = 0;
+      int* hs = c->h_stage;
+      int* h_row_slot = hs; int* h_row_pos = hs + c->m_cap;
+      int* h_ss = hs + 2 * (size_t)c->m_cap; int* h_sp = h_ss + c->n_slots; int* h_g = h_sp + c->n_slots;
+      int* h_list = h_g + c->n_slots; int* h_need = h_list + c->n_slots; int* h_n = h_need + c->n_slots;
+      while (pi < prefill_slots.size()) {
+        const int s = prefill_slots[pi];
+        const SlotH& sh = c->slots[s];
+        const int nt = sh.prompt_len + sh.gen;
+        if (rows + nt > c->prefill_cap && nseq > 0) break;
+        for (int p = 0; p < nt; ++p) { h_row_slot[rows + p] = s; h_row_pos[rows + p] = p; }
+        h_ss[nseq] = s; h_sp[nseq] = nt - 1; h_g[nseq] = rows + nt - 1;
+        h_list[nseq] = s; h_need[nseq] = ceil_div(nt, blk);
+        rows += nt; ++nseq; ++pi;
+      }
+      h_n[0] = rows; h_n[1] = nseq;
+      HIPCHK(c, hipMemcpyAsync(c->d_pf_row_slot, h_row_slot, rows * sizeof(int), hipMemcpyHostToDevice, st));
+      HIPCHK(c, hipMemcpyAsync(c->d_pf_row_pos, h_row_pos, rows * sizeof(int), hipMemcpyHostToDevice, st));
+      HIPCHK(c, hipMemcpyAsync(c->d_pf_srow_slot, h_ss, nseq * sizeof(int), hipMemcpyHostToDevice, st));
+      HIPCHK(c, hipMemcpyAsync(c->d_pf_srow_pos, h_sp, nseq * sizeof(int), hipMemcpyHostToDevice, st));
+      HIPCHK(c, hipMemcpyAsync(c->d_pf_gather, h_g, nseq * sizeof(int), hipMemcpyHostToDevice, st));
+      HIPCHK(c, hipMemcpyAsync(c->d_list_a, h_list, nseq * sizeof(int), hipMemcpyHostToDevice, st));
+      HIPCHK(c, hipMemcpyAsync(c->d_list_b, h_need, nseq * sizeof(int), hipMemcpyHostToDevice, st));
+      HIPCHK(c, hipMemcpyAsync(c->d_pf_nrows, h_n, sizeof(int), hipMemcpyHostToDevice, st));
+      HIPCHK(c, hipMemcpyAsync(c->d_pf_nsrows, h_n + 1, sizeof(int), hipMemcpyHostToDevice, st));
+      launch_alloc_prefill(st, c->d_ctrl, c->ds, c->d_list_a, c->d_list_b, nseq, c->d_free_stack);
+      RowCtx prc{c->d_pf_row_slot, c->d_pf_row_pos, c->d_pf_nrows, nullptr, rows};
+      RowCtx src{c->d_pf_srow_slot, c->d_pf_srow_pos, c->d_pf_nsrows, nullptr, nseq};
+      forward(c, prc, src, c->d_pf_gather, rows, 0);
+      HIPCHK(c, hipStreamSynchronize(st));     // staging buffers are reused by the next chunk
+    }
+    HIPCHK(c, hipMemcpyAsync(c->h_ctrl, c->d_ctrl, sizeof(Ctrl), hipMemcpyDeviceToHost, st));
+    HIPCHK(c, hipStreamSynchronize(st));
+    if (c->h_ctrl->error) return fail(c, APRIL_ENOMEM, "KV page stack underflow on device (prefill)");
+    it1_live = c->h_ctrl->sum_live; it1_ctx = c->h_ctrl->sum_ctx;
+    t_prefill = now_s() - t0;
+
+    // iterations 2..: pure decode
+    const double t1 = now_s();
+    drc.max_rows = (int)inflight.size();
+    bool stopped = false;
+    int launched = 1;
+    const int chunk = 32;
+    while (!stopped) {
+      int todo = exact ? T_bound - launched : std::min(chunk, T_bound - launched);
+      if (todo < 0) todo = 0;
+      for (int k = 0; k < todo; ++k) {
+        const int it = launched + k + 1;
+        c->prof_now = c->prof_every > 0 && (it % c->prof_every) == 0 && c->snaps_used < c->snaps_cap;
+        {
+          ProfScope p(c, KC_SCHED, 0, 0);
+          launch_sched(st, c->d_ctrl, c->ds, c->d_row_slot, c->d_row_pos, c->d_free_stack, blk, 0);
+        }
+        double B = 0, C = 0;
+        if (c->prof_now) {
+          c->prof_snap = c->snaps_used++;
+          HIPCHK(c, hipMemcpyAsync(&c->h_snaps[c->prof_snap], c->d_ctrl, sizeof(Ctrl), hipMemcpyDeviceToHost, st));
+          HIPCHK(c, hipStreamSynchronize(st));
+          B = c->h_snaps[c->prof_snap].n_rows; C = (double)c->h_snaps[c->prof_snap].iter_ctx;
+        }
+        forward(c, drc, drc, nullptr, B, C);
+        c->prof_now = false;
+      }
+      launched += todo;
+      launch_sched(st, c->d_ctrl, c->ds, c->d_row_slot, c->d_row_pos, c->d_free_stack, blk, 1);
+      HIPCHK(c, hipMemcpyAsync(c->h_ctrl, c->d_ctrl, sizeof(Ctrl), hipMemcpyDeviceToHost, st));
+      HIPCHK(c, hipStreamSynchronize(st));
+      if (c->h_ctrl->error) return fail(c, APRIL_ENOMEM, "KV page stack underflow on device");
+      stopped = c->h_ctrl->stop != 0;
+      if (!stopped && launched >= T_bound) return fail(c, APRIL_EDEVICE, "scheduler did not stop after %d iterations", launched);
+    }
+    t_decode = now_s() - t1;
+    iters = c->h_ctrl->stop_iter;
+    sum_live = c->h_ctrl->sum_live; sum_ctx = c->h_ctrl->sum_ctx;
+    if (exact && iters != T_bound) return fail(c, APRIL_EDEVICE, "device stopped at iteration %lld, host expected %d", iters, T_bound);
+    prof_collect(c);
+
+    // ---- read back per-slot state --------------------------------------------------------
+    const int S = c->n_slots;
+    int* srcs[5] = {c->ds.gen, c->ds.state, c->ds.kv_len, c->ds.n_blocks, c->ds.finish_iter};
+    for (int k = 0; k < 5; ++k)
+      HIPCHK(c, hipMemcpyAsync(c->h_slot_arrays + k * S, srcs[k], S * sizeof(int), hipMemcpyDeviceToHost, st));
+    HIPCHK(c, hipStreamSynchronize(st));
+    memcpy(snap.data(), c->h_slot_arrays, 5 * S * sizeof(int));
+    c->free_pages_host = c->h_ctrl->free_top;
+  }
+
+  // ---- classify: newly complete (iteration, request id), surplus, partial -----------------
+  const int S = c->n_slots;
+  struct Fin { int iter; long long req; int slot; };
+  std::vector<Fin> fins;
+  int64_t tokens_generated = 0;
+  std::vector<int> partial_slots;
+  if (D < N_target) {
+    for (int s : inflight) {
+      SlotH& sh = c->slots[s];
+      const int gen = snap[0 * S + s], state = snap[1 * S + s];
+      tokens_generated += gen - sh.gen;
+      sh.gen = gen; sh.kv_len = snap[2 * S + s]; sh.n_blocks = snap[3 * S + s];
+      if (state == SLOT_DONE) { sh.state = SLOT_DONE; fins.push_back({snap[4 * S + s], sh.req, s}); }
+      else { sh.state = SLOT_PARKED; partial_slots.push_back(s); }
+    }
+  } else {
+    for (int s : inflight) { c->slots[s].state = SLOT_PARKED; partial_slots.push_back(s); }
+  }
+  std::sort(fins.begin(), fins.end(), [](const Fin& a, const Fin& b) { return a.iter != b.iter ? a.iter < b.iter : a.req < b.req; });
+
+  // delivery order: surplus of the last step (ascending id), then this step's finishers
+  c->r_req.clear(); c->r_tokens.clear(); c->r_ntok.clear(); c->r_nres.clear(); c->r_tok_ptrs.clear();
+  april_buffer* nb = new_buffer(c);
+  std::vector<int> release;             // slots whose rollout is returned now
+  int delivered = 0;
+  auto deliver_slot = [&](int s) -> int {
+    SlotH& sh = c->slots[s];
+    c->r_req.push_back(sh.req);
+    c->r_tokens.emplace_back((size_t)sh.gen);
+    if (sh.gen > 0)
+      HIPCHK(c, hipMemcpyAsync(c->r_tokens.back().data(), c->ds.tokens + (size_t)s * c->max_ctx + sh.prompt_len,
+                               (size_t)sh.gen * sizeof(int), hipMemcpyDeviceToHost, st));
+    c->r_ntok.push_back(sh.gen);
+    c->r_nres.push_back(sh.n_resumes);
+    release.push_back(s);
+    return APRIL_OK;
+  };
+  for (Entry& e : deliver) {
+    if (delivered < N_target) {
+      if (e.slot >= 0) { int rc = deliver_slot(e.slot); if (rc != APRIL_OK) return rc; }
+      else {
+        c->r_req.push_back(e.req); c->r_tokens.push_back(e.generated);
+        c->r_ntok.push_back((int)e.generated.size()); c->r_nres.push_back(e.n_resumes);
+      }
+      ++delivered;
+    } else {
+      nb->entries.push_back(e);          // still surplus (only when N' > 2N)
+    }
+  }
+  std::vector<int> surplus_slots;
+  for (const Fin& f : fins) {
+    if (delivered < N_target) { int rc = deliver_slot(f.slot); if (rc != APRIL_OK) return rc; ++delivered; }
+    else surplus_slots.push_back(f.slot);
+  }
+  HIPCHK(c, hipStreamSynchronize(st));
+  // surplus-complete rollouts keep their tokens (slot) but no KV pages
+  {
+    std::vector<int> to_free = release;
+    to_free.insert(to_free.end(), surplus_slots.begin(), surplus_slots.end());
+    int rc = free_slot_pages(c, to_free);
+    if (rc != APRIL_OK) return rc;
+  }
+  for (int s : release) c->slots[s] = SlotH();
+  for (int s : surplus_slots) {
+    Entry e; e.req = c->slots[s].req; e.slot = s; e.limit = c->slots[s].limit; e.n_resumes = c->slots[s].n_resumes; e.done = 1;
+    nb->entries.push_back(std::move(e));
+  }
+  for (int s : partial_slots) {
+    Entry e; e.req = c->slots[s].req; e.slot = s; e.limit = c->slots[s].limit; e.n_resumes = c->slots[s].n_resumes; e.done = 0;
+    nb->entries.push_back(std::move(e));
+  }
+  std::sort(nb->entries.begin(), nb->entries.end(), [](const Entry& a, const Entry& b) { return a.req < b.req; });
+
+  for (auto& v : c->r_tokens) c->r_tok_ptrs.push_back(v.data());
+  out->n_completed = delivered;
+  out->request_id = (const int64_t*)c->r_req.data();
+  out->tokens = c->r_tok_ptrs.data();
+  out->n_tokens = c->r_ntok.data();
+  out->n_resumes = c->r_nres.data();
+  out->buffer = nb;
+  out->n_new_consumed = n_admit;
+  out->decode_iters = iters;
+  out->tokens_generated = tokens_generated;
+  out->prefill_tokens = prefill_tokens;
+  out->reprefill_tokens = reprefill_tokens;
+  out->sum_live = sum_live;
+  out->sum_ctx = sum_ctx;
+  out->dec_sum_live = sum_live - it1_live;
+  out->dec_sum_ctx = sum_ctx - it1_ctx;
+  out->t_prefill_s = t_prefill;
+  out->t_decode_s = t_decode;
+  out->t_total_s = now_s() - t_begin;
+  return APRIL_OK;
+}
+
+}  // extern "C"

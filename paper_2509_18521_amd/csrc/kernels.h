@@ -1,0 +1,91 @@
+// Launcher prototypes of the HIP kernels (gfx950).  Every launcher enqueues on
+// `st` and returns immediately; none allocates.
+//
+// Row model: a forward pass runs over "rows"; row r belongs to sequence slot
+// row_slot[r] and sits at position row_pos[r].  For a decode iteration the rows are
+// the live rollouts (written by the scheduler kernel), for prefill they are all
+// prompt tokens of the admitted rollouts.  n_rows lives in device memory; kernels
+// whose block index is beyond it exit.  stop (device int, may be null) turns every
+// kernel into a no-op once the scheduler has ended the step.
+#pragma once
+#include "common.h"
+
+namespace april {
+
+struct RowCtx {
+  const int* row_slot;
+  const int* row_pos;
+  const int* n_rows;     // device
+  const int* stop;       // device, nullable
+  int max_rows;          // host-known upper bound (grid size)
+};
+
+// Early exit of a one-workgroup-per-row kernel: step stopped, or row beyond the batch.
+#define ROW_GUARD(rc, r)                               \
+  if ((rc).stop != nullptr && *(rc).stop != 0) return; \
+  if ((r) >= *(rc).n_rows) return;
+
+// --- scheduler / allocator -------------------------------------------------
+// check_only = 1: only the "N complete => stop" test (end of a chunk of iterations).
+void launch_sched(hipStream_t st, Ctrl* ctrl, Slots s, int* row_slot, int* row_pos,
+                  int* free_stack, int blk, int check_only);
+void launch_alloc_prefill(hipStream_t st, Ctrl* ctrl, Slots s, const int* slot_list,
+                          const int* n_blocks_needed, int n, int* free_stack);
+void launch_free_slots(hipStream_t st, Ctrl* ctrl, Slots s, const int* slot_list, int n,
+                       int* free_stack);
+void launch_init_free_stack(hipStream_t st, int* free_stack, int n_blocks);
+void launch_fill_i32(hipStream_t st, int* p, int v, size_t n);
+
+// --- model ------------------------------------------------------------------
+template <typename T>
+void launch_embed(hipStream_t st, RowCtx rc, Slots s, const T* emb, float* x_res, int d);
+
+// x_res += sum of partials (if any); h = rmsnorm(x_res) * gain.  gather (nullable):
+// input row index of output row r.
+template <typename T, bool XF>
+void launch_add_rmsnorm(hipStream_t st, RowCtx rc, float* x_res, const float* partials,
+                        int n_partials, size_t partial_stride, const float* gain, T* h,
+                        int d, float eps, const int* gather);
+
+template <typename T>
+void launch_rope_append(hipStream_t st, RowCtx rc, Slots s, const float* qkv, int n_partials,
+                        size_t partial_stride, const float* rope_cos, const float* rope_sin,
+                        float* q_rot, T* kv_pool, KVLayout kvl, int layer, int n_q_heads);
+
+template <typename T, bool XF>
+void launch_attn_ref(hipStream_t st, RowCtx rc, Slots s, const float* q_rot, const T* kv_pool,
+                     KVLayout kvl, int layer, int n_q_heads, T* out);
+
+template <typename T, bool XF>
+void launch_silu_mul(hipStream_t st, RowCtx rc, const float* gu, int F, T* act);
+
+// out[m][n] = sum_k x[m][k] W[n][k]; plain row-major W; reference path.
+template <typename T, bool XF>
+void launch_gemm_ref(hipStream_t st, RowCtx rc, const T* x, const T* W, float* out, int N, int K);
+
+// bf16 MFMA GEMM over fragment-tiled operands.  Wp: weights re-laid by
+// launch_shuffle_weights.  out: fp32 [ksplit][m_cap][N] partial sums.
+void launch_gemm_mfma(hipStream_t st, RowCtx rc, const bf16_t* x, const bf16_t* Wp, float* out,
+                      int N, int K, int ksplit, size_t partial_stride);
+// act[m][f] = silu(x.Wg[f]) * (x.Wu[f]) as fragment-tiled bf16.
+void launch_gemm_mfma_swiglu(hipStream_t st, RowCtx rc, const bf16_t* x, const bf16_t* Wg,
+                             const bf16_t* Wu, bf16_t* act, int F, int K);
+void launch_shuffle_weights(hipStream_t st, const bf16_t* src, bf16_t* dst, int N, int K);
+
+void launch_rope_table(hipStream_t st, float* cos_t, float* sin_t, int max_pos, int head_dim,
+                       float theta);
+
+// --- sampler + per-rollout state update ---------------------------------------
+struct SamplerCfg {
+  int kind, top_k;
+  float temperature;
+  unsigned long long seed;
+};
+// Rows here are sampling rows: sample_row_slot / sample_row_pos give the slot and the
+// position of the LAST fed token of each row.  update = 0: only write out_tokens
+// (standalone sampler; req_ids/gen_idx arrays given explicitly).
+void launch_sample(hipStream_t st, RowCtx rc, Slots s, Ctrl* ctrl, const float* logits, int vocab,
+                   SamplerCfg sc, Watch w, int update, const long long* req_ids,
+                   const int* gen_idx, int* out_tokens);
+
+}  // namespace april

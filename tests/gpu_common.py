@@ -1,0 +1,95 @@
+"""Helpers shared by the GPU parity tests: run the same seeded workload through the
+HIP library (C ABI via the ctypes binding) and through the CPU oracle."""
+import numpy as np
+
+import april_inputs as ai
+import paper_2509_18521_amd as ap
+from oracle.model import Decoder
+from oracle.rollout import OracleRollouts
+
+
+def have_gpu():
+    try:
+        import torch
+        return torch.cuda.is_available()
+    except Exception:
+        return False
+
+
+def sampler_name(w):
+    return "greedy" if w.sampler == ai.SAMPLER_GREEDY else "topk"
+
+
+def make_engine(w, weights, *, debug=False, max_inflight=None, max_ctx=None, temperature=1.0, eos=-1,
+                kv_pool_bytes=0):
+    s = w.shape
+    cfg = ap.make_cfg(s, max_inflight=max_inflight or (w.n_overprovision + 8),
+                      max_ctx=max_ctx or (w.prompt_len + w.max_new + 16),
+                      sampler=w.sampler, top_k=max(w.top_k, 1), temperature=temperature, seed=w.seed,
+                      eos_token=eos, debug_logits=debug, kv_pool_bytes=kv_pool_bytes)
+    return ap.april_init(cfg, ap.pack_weights(s, weights))
+
+
+def req_dicts(reqs, forced=None):
+    out = []
+    for r in reqs:
+        d = dict(request_id=r.request_id, tokens=r.tokens, forced_len=r.forced_len)
+        if forced is not None and r.request_id in forced:
+            d["forced_tokens"] = np.asarray(forced[r.request_id], dtype=np.int32)
+        out.append(d)
+    return out
+
+
+def run_gpu(ctx, reqs, n_target, n_over, max_new, steps, *, forced=None, between=None):
+    """-> list of per-step dicts (ids, tokens, stats, buffer view).  `between(ctx, buffer)`
+    may act on the buffer (e.g. drop its KV) before it is resumed; it returns the
+    buffer handle to resume."""
+    nxt, out = 0, []
+    for _ in range(steps):
+        res = ap.april_rollout_step(ctx, req_dicts(reqs[nxt:], forced), n_target, n_over, max_new)
+        nxt += res.n_new_consumed
+        view = ap.april_buffer_export(ctx, res.buffer)
+        out.append(dict(ids=res.request_id, tokens=[t.tolist() for t in res.tokens], n_resumes=res.n_resumes,
+                        consumed=res.n_new_consumed, iters=res.decode_iters, generated=res.tokens_generated,
+                        buffer=[(p["request_id"], len(p["generated"]), p["done"]) for p in view],
+                        buffer_tokens={p["request_id"]: p["generated"].tolist() for p in view},
+                        sum_live=res.sum_live, res=res))
+        buf = res.buffer
+        if between is not None:
+            buf = between(ctx, buf)
+        ap.april_resume(ctx, buf)
+    return out
+
+
+def run_oracle(w, weights, reqs, n_target, n_over, max_new, steps, *, keep_logits=False, temperature=1.0,
+               eos=-1, drop_kv=False):
+    eng = OracleRollouts(Decoder(w.shape, weights), sampler_name(w), top_k=max(w.top_k, 1),
+                         temperature=temperature, seed=w.seed, eos_token=eos, keep_logits=keep_logits)
+    rolls = [eng.make_rollout(r.request_id, r.tokens, r.forced_len) for r in reqs]
+    nxt, out = 0, []
+    for _ in range(steps):
+        if drop_kv:
+            eng.drop_kv()
+        o = eng.step(rolls[nxt:], n_target, n_over, max_new)
+        nxt += o.n_new_consumed
+        out.append(dict(ids=[r.request_id for r in o.completed], tokens=[list(r.tokens) for r in o.completed],
+                        n_resumes=[r.n_resumes for r in o.completed], consumed=o.n_new_consumed,
+                        iters=o.decode_iters, generated=o.tokens_generated,
+                        buffer=[(r.request_id, r.gen, int(r.done)) for r in o.buffer],
+                        buffer_tokens={r.request_id: list(r.tokens) for r in o.buffer},
+                        sum_live=sum(o.live_per_iter)))
+    return out, eng
+
+
+def assert_schedule_equal(got, want):
+    """Scheduling outputs are integers: bit-exact."""
+    assert len(got) == len(want)
+    for k, (g, o) in enumerate(zip(got, want)):
+        for key in ("ids", "consumed", "iters", "generated", "buffer", "n_resumes"):
+            assert g[key] == o[key], (k, key, g[key], o[key])
+        assert [len(t) for t in g["tokens"]] == [len(t) for t in o["tokens"]]
+
+
+def top2_margin(logits):
+    p = np.partition(np.asarray(logits, dtype=np.float64), -2)
+    return float(p[-1] - p[-2])

@@ -1,0 +1,89 @@
+"""GPU parity for the bf16 path (MFMA GEMMs, bf16 KV cache) at the real layer shapes of
+the benchmark configurations, teacher-forced with the oracle's tokens."""
+import numpy as np
+import pytest
+
+import april_inputs as ai
+from gpu_common import assert_schedule_equal, have_gpu, make_engine, run_gpu, run_oracle
+from oracle import sampler as osampler
+from oracle.philox import uniform_for
+
+pytestmark = pytest.mark.gpu
+
+BF16_LOGIT_TOL = 2e-2          # max-abs relative to the logit scale max(1, max|l_ref|)
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _need_gpu():
+    if not have_gpu():
+        pytest.skip("no GPU")
+
+
+def ap():
+    import paper_2509_18521_amd
+    return paper_2509_18521_amd
+
+
+def teacher_forced_parity(w, steps, n_requests):
+    weights = ai.make_weights(w.shape, w.seed)
+    reqs = ai.make_requests(w, n_requests)
+    want, eng = run_oracle(w, weights, reqs, w.n_target, w.n_overprovision, w.max_new, steps, keep_logits=True)
+    ref_tokens = {}
+    for o in want:
+        ref_tokens.update(dict(zip(o["ids"], o["tokens"])))
+    ref_tokens.update(want[-1]["buffer_tokens"])
+    ctx = make_engine(w, weights, debug=True)
+    try:
+        for rid in ref_tokens:
+            ap().april_debug_watch(ctx, rid, 0, w.max_new)
+        got = run_gpu(ctx, reqs, w.n_target, w.n_overprovision, w.max_new, steps, forced=ref_tokens)
+        assert_schedule_equal(got, want)
+        for g, o in zip(got, want):
+            assert g["tokens"] == o["tokens"]            # forced tokens went through
+        worst, rows, sampler_rows = 0.0, 0, 0
+        for rid, toks in ref_tokens.items():
+            for i in range(len(toks)):
+                lg, sampled = ap().april_debug_logits(ctx, rid, i, w.shape.vocab)
+                ref = eng.logits[(rid, i)]
+                scale = max(1.0, float(np.max(np.abs(ref))))
+                worst = max(worst, float(np.max(np.abs(lg - ref))) / scale)
+                rows += 1
+                # the device sampler on the device's own fp32 logits == oracle sampler on them
+                if w.sampler == ai.SAMPLER_GREEDY:
+                    assert sampled == osampler.greedy(lg)
+                else:
+                    u = uniform_for(w.seed, rid, i)
+                    idx, p = osampler.top_k_probs(lg, w.top_k, 1.0)
+                    cdf = np.cumsum(p)
+                    if np.min(np.abs(cdf - u)) > 1e-9:
+                        assert sampled == osampler.top_k_sample(lg, w.top_k, 1.0, u)
+                        sampler_rows += 1
+        assert rows >= 20
+        assert worst <= BF16_LOGIT_TOL, worst
+        return worst, rows
+    finally:
+        ap().april_destroy(ctx)
+
+
+def test_cfg2_shape_two_layers_topk_teacher_forced():
+    base = ai.WORKLOADS["cfg2_small_bf16"]
+    w = ai.Workload("cfg2_L2", ai.reduced(base, n_layers=2).shape, 8, 256, 3, 5, 16, 2.2, 0.5, 4, 16,
+                    ai.SAMPLER_TOPK, 50, 2, base.seed)
+    teacher_forced_parity(w, 2, 12)
+
+
+def test_cfg2_full_depth_sampled_positions():
+    """All 24 layers of configuration 2 on a few rollouts and positions."""
+    base = ai.WORKLOADS["cfg2_small_bf16"]
+    w = ai.Workload("cfg2_full", base.shape, 4, 256, 2, 3, 6, 1.5, 0.3, 3, 6, ai.SAMPLER_TOPK, 50, 1, base.seed)
+    teacher_forced_parity(w, 1, 4)
+
+
+@pytest.mark.parametrize("name", ["cfg3_mid_bf16", "cfg4_8b_bf16"])
+def test_wide_shapes_head_dim_128_gqa4(name):
+    """Layer shapes of configurations 3 and 4 (head_dim 128, 4 query heads per KV head),
+    one layer, reduced vocabulary, greedy, ragged prompt lengths via re-prefill."""
+    base = ai.WORKLOADS[name]
+    shape = ai.reduced(base, n_layers=1, vocab=8192).shape
+    w = ai.Workload(name + "_L1", shape, 4, 70, 2, 4, 12, 2.0, 0.5, 3, 12, ai.SAMPLER_GREEDY, 0, 2, base.seed)
+    teacher_forced_parity(w, 2, 8)

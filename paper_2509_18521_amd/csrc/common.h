@@ -87,14 +87,22 @@ __host__ __device__ inline size_t act_index(int row, int k, int K) {
   }
 }
 
-// KV cache addressing: pool[layer][k|v][page][kv_head][token_in_page][dim]
+// KV cache addressing: pool[layer][k|v][page][kv_head][blk * head_dim elements].
+// Inside one (page, head) block, mode 0 keeps [token][dim] for both K and V; mode 1
+// (bf16 MFMA attention) keeps K in the A-operand order of v_mfma_f32_16x16x32_bf16
+// ([dim/32][lane = token + 16*((dim%32)/8)][dim%8]) and V transposed ([dim][token]).
 struct KVLayout {
   size_t layer_stride;   // elements between layers (covers k and v)
   size_t kv_stride;      // elements between the k part and the v part
-  int n_kv_heads, head_dim, blk;
+  int n_kv_heads, head_dim, blk, mode;
   __host__ __device__ inline size_t at(int layer, int kv, int page, int head, int tok, int d) const {
-    return (size_t)layer * layer_stride + (size_t)kv * kv_stride +
-           (((size_t)page * n_kv_heads + head) * blk + tok) * head_dim + d;
+    const size_t base = (size_t)layer * layer_stride + (size_t)kv * kv_stride +
+                        ((size_t)page * n_kv_heads + head) * (size_t)(blk * head_dim);
+    int inner;
+    if (mode == 0) inner = tok * head_dim + d;
+    else if (kv == 0) inner = ((((d >> 5) << 6) + tok + (((d & 31) >> 3) << 4)) << 3) + (d & 7);
+    else inner = d * blk + tok;
+    return base + inner;
   }
 };
 

@@ -113,10 +113,21 @@ struct april_ctx {
   // workspaces
   int m_cap = 0;
   float *x_res = nullptr, *qkv = nullptr, *q_rot = nullptr, *proj = nullptr, *gu = nullptr, *logits = nullptr;
+  float* group_max = nullptr;  // per row, maxima of groups of lmhead_group_cols() logits (MFMA LM head)
   void *h_act = nullptr, *attn_out = nullptr, *act = nullptr, *hf = nullptr;
   float *rope_cos = nullptr, *rope_sin = nullptr;
   int s_qkv = 1, s_o = 1, s_down = 1;
   size_t qkv_stride = 0, proj_stride = 0;
+  // bf16 MFMA attention: split-KV workspace
+  bool attn_mfma = false;
+  int attn_chunk = 256, attn_max_splits = 1, attn_ws_rows = 0;
+  float* attn_ws = nullptr;
+  int* attn_counters = nullptr;
+  int step_max_ctx = 0;        // bound on the context length of any row in the current pass
+  // one decode iteration (scheduler + forward + sample) captured as a HIP graph, keyed by
+  // the launch geometry (row bound, attention split bound)
+  bool use_graph = true;
+  std::map<std::pair<int, int>, hipGraphExec_t> iter_graphs;
 
   // pending resume
   std::vector<Entry> pending;
@@ -204,9 +215,9 @@ int fetch_tensor(april_ctx* c, const april_tensor* w, int n, const std::string& 
 int pick_ksplit(int N, int K) {
   const int n_tiles = N / 32, KT = K / 16;
   if (n_tiles >= 512) return 1;
-  int s = KT / 8;
+  int s = KT / 12;
   if (s < 1) s = 1;
-  if (s > 16) s = 16;
+  if (s > 8) s = 8;
   return s;
 }
 
@@ -285,7 +296,15 @@ void forward(april_ctx* c, RowCtx rows, RowCtx srows, const int* gather, double 
     }
     {
       ProfScope p(c, KC_ATTN, C * 2.0 * nkv * e + B * nq * (4.0 + e), 4.0 * C * nq);
-      if (c->bf16) launch_attn_ref<bf16_t, true>(st, rows, c->ds, c->q_rot, (const bf16_t*)c->kv_pool, c->kvl, l, Hq, (bf16_t*)c->attn_out);
+      if (c->attn_mfma) {
+        const int gs = std::min(c->attn_max_splits, std::max(1, ceil_div(c->step_max_ctx, c->attn_chunk)));
+        for (int base = 0; base < rows.max_rows; base += c->attn_ws_rows) {
+          RowCtx sub = rows;
+          sub.max_rows = std::min(c->attn_ws_rows, rows.max_rows - base);
+          launch_attn_decode(st, sub, base, c->ds, c->q_rot, (const bf16_t*)c->kv_pool, c->kvl, l, Hq,
+                             (bf16_t*)c->attn_out, c->attn_ws, c->attn_counters, c->attn_max_splits, gs);
+        }
+      } else if (c->bf16) launch_attn_ref<bf16_t, true>(st, rows, c->ds, c->q_rot, (const bf16_t*)c->kv_pool, c->kvl, l, Hq, (bf16_t*)c->attn_out);
       else launch_attn_ref<float, false>(st, rows, c->ds, c->q_rot, (const float*)c->kv_pool, c->kvl, l, Hq, (float*)c->attn_out);
     }
     gemm(KC_GEMM_O, rows, c->attn_out, L.wo, L.wo_s, c->proj, d, nq, c->s_o, c->proj_stride, B);
@@ -305,7 +324,8 @@ void forward(april_ctx* c, RowCtx rows, RowCtx srows, const int* gather, double 
   norm(srows, c->s_down, c->final_norm, c->hf, gather, SB);
   {
     ProfScope p(c, KC_GEMM_LMHEAD, (double)V * d * e + SB * d * e, 2.0 * SB * V * d);
-    if (c->use_mfma) launch_gemm_mfma(st, srows, (const bf16_t*)c->hf, c->lm_head_s, c->logits, V, d, 1, 0);
+    if (c->use_mfma && c->group_max) launch_gemm_mfma_logits(st, srows, (const bf16_t*)c->hf, c->lm_head_s, c->logits, c->group_max, V, d);
+    else if (c->use_mfma) launch_gemm_mfma(st, srows, (const bf16_t*)c->hf, c->lm_head_s, c->logits, V, d, 1, 0);
     else if (c->bf16) launch_gemm_ref<bf16_t, true>(st, srows, (const bf16_t*)c->hf, (const bf16_t*)c->lm_head, c->logits, V, d);
     else launch_gemm_ref<float, false>(st, srows, (const float*)c->hf, (const float*)c->lm_head, c->logits, V, d);
   }
@@ -313,7 +333,8 @@ void forward(april_ctx* c, RowCtx rows, RowCtx srows, const int* gather, double 
     ProfScope p(c, KC_SAMPLE, SB * V * 4.0, 0);
     SamplerCfg sc{c->cfg.sampler, c->cfg.top_k, c->cfg.temperature, (unsigned long long)c->cfg.seed};
     Watch w = c->cfg.debug_logits ? c->dwatch : Watch{};
-    launch_sample(st, srows, c->ds, c->d_ctrl, c->logits, V, sc, w, 1, nullptr, nullptr, nullptr);
+    launch_sample(st, srows, c->ds, c->d_ctrl, c->logits, V, sc, w, 1, nullptr, nullptr, nullptr, c->group_max,
+                  lmhead_group_cols());
   }
 }
 
@@ -361,11 +382,12 @@ int april_init(const april_model_cfg* cfg, const april_tensor* weights, int32_t 
   if (g.n_layers <= 0 || g.d_model <= 0 || g.n_q_heads <= 0 || g.n_kv_heads <= 0 || g.vocab <= 0 || g.d_ffn <= 0)
     return fail(nullptr, APRIL_EINVAL, "non-positive model dimension");
   if (g.n_q_heads % g.n_kv_heads) return fail(nullptr, APRIL_EINVAL, "n_q_heads must be a multiple of n_kv_heads");
+  if (g.n_q_heads / g.n_kv_heads > 16) return fail(nullptr, APRIL_EINVAL, "at most 16 query heads per KV head");
   if (g.head_dim != 32 && g.head_dim != 64 && g.head_dim != 128) return fail(nullptr, APRIL_EINVAL, "head_dim must be 32, 64 or 128");
   if (g.d_model % 8 || g.d_model > 8192) return fail(nullptr, APRIL_EINVAL, "d_model must be a multiple of 8, at most 8192");
   if (g.dtype != APRIL_DTYPE_FP32 && g.dtype != APRIL_DTYPE_BF16) return fail(nullptr, APRIL_EINVAL, "bad dtype");
   if (g.max_inflight <= 0 || g.max_inflight > 2048) return fail(nullptr, APRIL_EINVAL, "max_inflight must be in 1..2048");
-  if (g.max_ctx <= 1) return fail(nullptr, APRIL_EINVAL, "max_ctx too small");
+  if (g.max_ctx <= 1 || g.max_ctx > 32768) return fail(nullptr, APRIL_EINVAL, "max_ctx must be in 2..32768");
   if (g.sampler == APRIL_SAMPLER_TOPK && (g.top_k < 1 || g.top_k > 64 || !(g.temperature > 0.f)))
     return fail(nullptr, APRIL_EINVAL, "top_k must be in 1..64 and temperature > 0");
   const int nq = g.n_q_heads * g.head_dim, nkv = g.n_kv_heads * g.head_dim, nqkv = nq + 2 * nkv;
@@ -380,6 +402,10 @@ int april_init(const april_model_cfg* cfg, const april_tensor* weights, int32_t 
   c->esz = c->bf16 ? 2 : 4;
   const char* gm = getenv("APRIL_GEMM");
   c->use_mfma = c->bf16 && !(gm && !strcmp(gm, "ref"));
+  const char* am = getenv("APRIL_ATTN");
+  c->attn_mfma = c->bf16 && !(am && !strcmp(am, "ref"));
+  const char* gr = getenv("APRIL_GRAPH");
+  c->use_graph = !(gr && !strcmp(gr, "0"));
   for (int i = 0; i < KC_COUNT; ++i) c->stats[i] = april_kernel_stat{kKernelNames[i], 0, 0, 0, 0};
   auto bail = [&](int rc) { g_init_error = c->err; april_destroy(c); return rc; };
 #define TRY(x) do { int rc_ = (x); if (rc_ != APRIL_OK) return bail(rc_); } while (0)
@@ -495,8 +521,9 @@ int april_init(const april_model_cfg* cfg, const april_tensor* weights, int32_t 
   c->n_pages = (int)std::min<int64_t>(pool / page_bytes, (int64_t)1 << 30);
   if (c->n_pages < 1) { fail(c, APRIL_ENOMEM, "KV pool smaller than one page"); return bail(APRIL_ENOMEM); }
   c->kv_pool_bytes = (int64_t)c->n_pages * page_bytes;
-  TRY(dev_alloc_bytes(c, &c->kv_pool, (size_t)c->kv_pool_bytes, false));
+  TRY(dev_alloc_bytes(c, &c->kv_pool, (size_t)c->kv_pool_bytes, true));   // zeroed: masked lanes must stay finite
   c->kvl.n_kv_heads = g.n_kv_heads; c->kvl.head_dim = g.head_dim; c->kvl.blk = 16;
+  c->kvl.mode = c->attn_mfma ? 1 : 0;
   c->kvl.kv_stride = (size_t)c->n_pages * nkv * 16;
   c->kvl.layer_stride = 2 * c->kvl.kv_stride;
   TRY(dev_alloc(c, &c->d_free_stack, c->n_pages, false));
@@ -524,10 +551,19 @@ int april_init(const april_model_cfg* cfg, const april_tensor* weights, int32_t 
   if (!c->use_mfma) TRY(dev_alloc(c, &c->gu, M * 2 * F));
   const size_t SR = ((size_t)S + 31) / 32 * 32;
   TRY(dev_alloc(c, &c->logits, SR * V));
+  if (c->use_mfma && V % lmhead_group_cols() == 0) TRY(dev_alloc(c, &c->group_max, SR * (V / lmhead_group_cols())));
   TRY(dev_alloc_bytes(c, &c->h_act, M * d * e));
   TRY(dev_alloc_bytes(c, &c->attn_out, M * nq * e));
   TRY(dev_alloc_bytes(c, &c->act, M * F * e));
   TRY(dev_alloc_bytes(c, &c->hf, SR * d * e));
+  if (c->attn_mfma) {
+    c->attn_chunk = attn_split_tokens();
+    c->attn_max_splits = ceil_div(g.max_ctx, c->attn_chunk);
+    c->attn_ws_rows = std::min<int>(c->m_cap, std::max(512, (S + 31) / 32 * 32));
+    const size_t rec = 32 + (size_t)16 * g.head_dim;
+    TRY(dev_alloc(c, &c->attn_ws, (size_t)c->attn_ws_rows * g.n_kv_heads * c->attn_max_splits * rec, false));
+    TRY(dev_alloc(c, &c->attn_counters, (size_t)c->attn_ws_rows * g.n_kv_heads, true));
+  }
   TRY(dev_alloc(c, &c->rope_cos, (size_t)g.max_ctx * g.head_dim / 2, false));
   TRY(dev_alloc(c, &c->rope_sin, (size_t)g.max_ctx * g.head_dim / 2, false));
   launch_rope_table(c->stream, c->rope_cos, c->rope_sin, g.max_ctx, g.head_dim, g.rope_theta);
@@ -563,6 +599,7 @@ void april_destroy(april_ctx* c) {
   if (c->h_stage) hipHostFree(c->h_stage);
   if (c->h_snaps) hipHostFree(c->h_snaps);
   for (auto& ev : c->ev_pool) { hipEventDestroy(ev.first); hipEventDestroy(ev.second); }
+  for (auto& kv : c->iter_graphs) hipGraphExecDestroy(kv.second);
   for (april_buffer* b : c->buffers) delete b;
   if (c->own_stream && c->stream) hipStreamDestroy(c->stream);
   delete c;
@@ -755,10 +792,18 @@ int april_sample_rows(april_ctx* c, const float* logits, int32_t n_rows, const i
   HIPCHK(c, hipMemcpy(d_n, &n_rows, sizeof(int), hipMemcpyHostToDevice));
   RowCtx rc{nullptr, nullptr, d_n, nullptr, n_rows};
   SamplerCfg sc{c->cfg.sampler, c->cfg.top_k, c->cfg.temperature, (unsigned long long)c->cfg.seed};
-  launch_sample(c->stream, rc, c->ds, nullptr, logits, c->dm.vocab, sc, Watch{}, 0, d_req, d_gen, d_out);
+  // same candidate search as the rollout path: group maxima first when the vocabulary allows
+  const int grp = lmhead_group_cols();
+  float* d_gm = nullptr;
+  if (c->dm.vocab % grp == 0) {
+    HIPCHK(c, hipMalloc((void**)&d_gm, (size_t)n_rows * (c->dm.vocab / grp) * sizeof(float)));
+    launch_group_max(c->stream, logits, n_rows, c->dm.vocab, grp, d_gm);
+  }
+  launch_sample(c->stream, rc, c->ds, nullptr, logits, c->dm.vocab, sc, Watch{}, 0, d_req, d_gen, d_out, d_gm, grp);
   HIPCHK(c, hipStreamSynchronize(c->stream));
   HIPCHK(c, hipMemcpy(out_tokens, d_out, n_rows * sizeof(int), hipMemcpyDeviceToHost));
   hipFree(d_req); hipFree(d_gen); hipFree(d_out); hipFree(d_n);
+  if (d_gm) hipFree(d_gm);
   return APRIL_OK;
 }
 
@@ -820,6 +865,9 @@ int april_rollout_step(april_ctx* c, const april_request* new_reqs, int32_t n_ne
     for (int k = 0; k < r.n_tokens; ++k)
       if (r.tokens[k] < 0 || r.tokens[k] >= c->dm.vocab) return fail(c, APRIL_EINVAL, "request %d: token out of range", i);
     if (r.forced_tokens && !c->cfg.debug_logits) return fail(c, APRIL_EINVAL, "forced_tokens need a debug_logits context");
+    if (r.forced_tokens)
+      for (int k = 0; k < r.n_forced_tokens; ++k)
+        if (r.forced_tokens[k] < 0 || r.forced_tokens[k] >= c->dm.vocab) return fail(c, APRIL_EINVAL, "request %d: forced token out of range", i);
   }
   // worst-case page demand of the step (no preemption: refuse up front)
   {
@@ -913,6 +961,9 @@ int april_rollout_step(april_ctx* c, const april_request* new_reqs, int32_t n_ne
     const int T_bound = rem[N_target - D - 1];
     const bool exact = c->cfg.eos_token < 0;
 
+    int decode_max_ctx = 1;
+    for (int s : inflight) decode_max_ctx = std::max(decode_max_ctx, c->slots[s].prompt_len + c->slots[s].limit);
+    c->step_max_ctx = decode_max_ctx;
     RowCtx drc{c->d_row_slot, c->d_row_pos, &c->d_ctrl->n_rows, &c->d_ctrl->stop, 0};
     const double t0 = now_s();
     // iteration 1: resident rollouts decode, the others are (re-)prefilled
@@ -924,7 +975,7 @@ int april_rollout_step(april_ctx* c, const april_request* new_reqs, int32_t n_ne
     // prefill in chunks of whole sequences
     size_t pi = 0;
     while (pi < prefill_slots.size()) {
-      int rows = 0, nseq = 0;
+      int rows = 0, nseq = 0, chunk_max_ctx = 1;
       int* hs = c->h_stage;
       int* h_row_slot = hs; int* h_row_pos = hs + c->m_cap;
       int* h_ss = hs + 2 * (size_t)c->m_cap; int* h_sp = h_ss + c->n_slots; int* h_g = h_sp + c->n_slots;
@@ -938,7 +989,9 @@ int april_rollout_step(april_ctx* c, const april_request* new_reqs, int32_t n_ne
         h_ss[nseq] = s; h_sp[nseq] = nt - 1; h_g[nseq] = rows + nt - 1;
         h_list[nseq] = s; h_need[nseq] = ceil_div(nt, blk);
         rows += nt; ++nseq; ++pi;
+        chunk_max_ctx = std::max(chunk_max_ctx, nt);
       }
+      c->step_max_ctx = chunk_max_ctx;
       h_n[0] = rows; h_n[1] = nseq;
       HIPCHK(c, hipMemcpyAsync(c->d_pf_row_slot, h_row_slot, rows * sizeof(int), hipMemcpyHostToDevice, st));
       HIPCHK(c, hipMemcpyAsync(c->d_pf_row_pos, h_row_pos, rows * sizeof(int), hipMemcpyHostToDevice, st));
@@ -962,8 +1015,31 @@ int april_rollout_step(april_ctx* c, const april_request* new_reqs, int32_t n_ne
     t_prefill = now_s() - t0;
 
     // iterations 2..: pure decode
+    c->step_max_ctx = decode_max_ctx;
     const double t1 = now_s();
-    drc.max_rows = (int)inflight.size();
+    drc.max_rows = ((int)inflight.size() + 31) / 32 * 32;
+    if (drc.max_rows > c->n_slots) drc.max_rows = c->n_slots;
+    // the iteration graph for this geometry (captured once, replayed every iteration)
+    hipGraphExec_t iter_exec = nullptr;
+    if (c->use_graph) {
+      const int gs_key = c->attn_mfma ? std::min(c->attn_max_splits, std::max(1, ceil_div(c->step_max_ctx, c->attn_chunk))) : 0;
+      // round the split bound up so that steps with slightly different limits share a graph
+      const std::pair<int, int> key{drc.max_rows, gs_key};
+      auto it = c->iter_graphs.find(key);
+      if (it == c->iter_graphs.end()) {
+        hipGraph_t graph = nullptr;
+        c->prof_now = false;
+        HIPCHK(c, hipStreamBeginCapture(st, hipStreamCaptureModeThreadLocal));
+        launch_sched(st, c->d_ctrl, c->ds, c->d_row_slot, c->d_row_pos, c->d_free_stack, blk, 0);
+        forward(c, drc, drc, nullptr, 0, 0);
+        HIPCHK(c, hipStreamEndCapture(st, &graph));
+        hipGraphExec_t exec = nullptr;
+        HIPCHK(c, hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0));
+        HIPCHK(c, hipGraphDestroy(graph));
+        it = c->iter_graphs.emplace(key, exec).first;
+      }
+      iter_exec = it->second;
+    }
     bool stopped = false;
     int launched = 1;
     const int chunk = 32;
@@ -973,6 +1049,10 @@ int april_rollout_step(april_ctx* c, const april_request* new_reqs, int32_t n_ne
       for (int k = 0; k < todo; ++k) {
         const int it = launched + k + 1;
         c->prof_now = c->prof_every > 0 && (it % c->prof_every) == 0 && c->snaps_used < c->snaps_cap;
+        if (iter_exec && !c->prof_now) {
+          HIPCHK(c, hipGraphLaunch(iter_exec, st));
+          continue;
+        }
         {
           ProfScope p(c, KC_SCHED, 0, 0);
           launch_sched(st, c->d_ctrl, c->ds, c->d_row_slot, c->d_row_pos, c->d_free_stack, blk, 0);

@@ -56,6 +56,16 @@ template <typename T, bool XF>
 void launch_attn_ref(hipStream_t st, RowCtx rc, Slots s, const float* q_rot, const T* kv_pool,
                      KVLayout kvl, int layer, int n_q_heads, T* out);
 
+// bf16 MFMA paged attention (KV layout mode 1).  Rows [row_base, row_base + rc.max_rows)
+// of the row arrays.  A context longer than attn_split_tokens() is cut in KV splits of
+// that fixed size, so a row's reduction order depends on its own length only; ws /
+// counters: split workspace for rc.max_rows rows (counters zero on entry and on exit);
+// max_splits <= 32.
+int attn_split_tokens();
+void launch_attn_decode(hipStream_t st, RowCtx rc, int row_base, Slots s, const float* q_rot,
+                        const bf16_t* kv_pool, KVLayout kvl, int layer, int n_q_heads, bf16_t* out,
+                        float* ws, int* counters, int max_splits, int grid_splits);
+
 template <typename T, bool XF>
 void launch_silu_mul(hipStream_t st, RowCtx rc, const float* gu, int F, T* act);
 
@@ -70,6 +80,11 @@ void launch_gemm_mfma(hipStream_t st, RowCtx rc, const bf16_t* x, const bf16_t* 
 // act[m][f] = silu(x.Wg[f]) * (x.Wu[f]) as fragment-tiled bf16.
 void launch_gemm_mfma_swiglu(hipStream_t st, RowCtx rc, const bf16_t* x, const bf16_t* Wg,
                              const bf16_t* Wu, bf16_t* act, int F, int K);
+// LM head: logits fp32 [rows][V] plus, per row, the maximum of every group of
+// lmhead_group_cols() consecutive logits (group_max [rows][V / group]); V % 64 == 0.
+int lmhead_group_cols();
+void launch_gemm_mfma_logits(hipStream_t st, RowCtx rc, const bf16_t* x, const bf16_t* Wp, float* logits,
+                             float* group_max, int V, int K);
 void launch_shuffle_weights(hipStream_t st, const bf16_t* src, bf16_t* dst, int N, int K);
 
 void launch_rope_table(hipStream_t st, float* cos_t, float* sin_t, int max_pos, int head_dim,
@@ -84,8 +99,12 @@ struct SamplerCfg {
 // Rows here are sampling rows: sample_row_slot / sample_row_pos give the slot and the
 // position of the LAST fed token of each row.  update = 0: only write out_tokens
 // (standalone sampler; req_ids/gen_idx arrays given explicitly).
+// group_max (nullable): per row the maxima of groups of `group` consecutive logits, as
+// written by launch_gemm_mfma_logits; lets the sampler look at a few groups only.
 void launch_sample(hipStream_t st, RowCtx rc, Slots s, Ctrl* ctrl, const float* logits, int vocab,
                    SamplerCfg sc, Watch w, int update, const long long* req_ids,
-                   const int* gen_idx, int* out_tokens);
+                   const int* gen_idx, int* out_tokens, const float* group_max, int group);
+
+void launch_group_max(hipStream_t st, const float* logits, int n_rows, int V, int group, float* out);
 
 }  // namespace april

@@ -1,0 +1,290 @@
+// Paged-attention decode for bf16 KV, gfx950.
+//
+// One workgroup (4 wavefronts) per (row, KV head, KV split of ATT_SPLIT tokens).  The
+// wavefronts take the split's 32-token tiles round-robin, each keeps an online softmax
+// in registers, the four partial results are merged through LDS in wavefront order;
+// when a context spans several splits the merged partials go to a workspace and the
+// last workgroup to finish merges them in split order (deterministic: the order of
+// every floating-point sum depends on the row's own length only).
+//
+// Both products run on v_mfma_f32_16x16x32_bf16, computed transposed so that no
+// operand has to be re-laid between them:
+//   S^T[token, head] = K[token, :] . Q[head, :]      A = K fragment, B = Q^T fragment
+//   O^T[dim,  head]  = V^T[dim, token] . P^T[token, head]
+// The accumulator of the first product (lane l: head l%16, tokens 4*(l/16)+i of a
+// 16-token page) is, after exp(), directly the B operand of the second product: its
+// k index runs over (page A tokens 4g..4g+3, page B tokens 4g..4g+3), and the V^T
+// fragment is loaded with the same token order.
+//
+// KV page layout (written by rope_append_kernel, mode 1), per (page, KV head):
+//   K: MFMA A-fragment order  [d/32][lane = t + 16*((d%32)/8)][d%8]   -> 1 KiB coalesced loads
+//   V: transposed             [d][t]                                 -> 8-byte loads, 512 B/wave coalesced
+#include "kernels.h"
+
+namespace april {
+
+constexpr int ATT_SPLIT = 1024;          // tokens per KV split = 64 pages = one page id per lane
+constexpr int ATT_WAVES = 4;
+
+template <int DH>
+__global__ __launch_bounds__(64 * ATT_WAVES) void attn_decode_kernel(
+    RowCtx rc, int row_base, Slots s, const float* __restrict__ q_rot, const bf16_t* __restrict__ kv_pool,
+    KVLayout L, int layer, int Hq, bf16_t* __restrict__ out, float* ws, int* counters, int max_splits) {
+  constexpr int KC = DH / 32;      // k-chunks of the QK product
+  constexpr int DT = DH / 16;      // dim tiles of the PV product
+  constexpr int REC = 32 + 16 * DH;   // floats of one partial result: m[16], l[16], o[16][DH]
+  __shared__ float lds[ATT_WAVES * REC];
+  __shared__ int s_last;
+  const int wr = blockIdx.x, r = row_base + wr, kvh = blockIdx.y, split = blockIdx.z;   // wr: workspace row
+  ROW_GUARD(rc, r);
+  const int slot = rc.row_slot[r], pos = rc.row_pos[r];
+  const int ctx = pos + 1;
+  const int n_splits = (ctx + ATT_SPLIT - 1) / ATT_SPLIT;
+  if (split >= n_splits) return;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, hh = lane & 15, g = lane >> 4;
+  const int Hkv = L.n_kv_heads, G = Hq / Hkv;
+  const int t_begin = split * ATT_SPLIT, t_end = min(ctx, t_begin + ATT_SPLIT);
+  const int n_tiles = (t_end - t_begin + 31) >> 5;
+  const int n_pages = (t_end - t_begin + 15) >> 4;
+  const size_t blk_elems = (size_t)16 * DH;
+  const bf16_t* kbase = kv_pool + (size_t)layer * L.layer_stride;
+  const bf16_t* vbase = kbase + L.kv_stride;
+
+  // page ids of this split: lane i holds page i (one vector load instead of a scalar
+  // load per tile inside the loop)
+  const int* bt = s.block_table + (size_t)slot * s.max_blocks + (t_begin >> 4);
+  const int my_page = bt[lane < n_pages ? lane : n_pages - 1];
+
+  // Q^T fragments: lane holds q[head hh][32c + 8g .. +7]; heads beyond the group read
+  // the group's last head and are zeroed.
+  bf16x8 qf[KC];
+  {
+    const int hq = hh < G ? hh : G - 1;
+    const float* q = q_rot + (size_t)r * Hq * DH + (size_t)(kvh * G + hq) * DH + 8 * g;
+    f32x4 qa[KC][2];
+#pragma unroll
+    for (int c = 0; c < KC; ++c) {
+      qa[c][0] = *reinterpret_cast<const f32x4*>(q + 32 * c);
+      qa[c][1] = *reinterpret_cast<const f32x4*>(q + 32 * c + 4);
+    }
+#pragma unroll
+    for (int c = 0; c < KC; ++c)
+#pragma unroll
+      for (int j = 0; j < 8; ++j) qf[c][j] = hh < G ? (bf16_t)qa[c][j >> 2][j & 3] : (bf16_t)0.f;
+  }
+  const float scale = 1.0f / sqrtf((float)DH);
+  float m_run = -INFINITY, l_run = 0.f;
+  f32x4 oacc[DT];
+#pragma unroll
+  for (int d = 0; d < DT; ++d) oacc[d] = f32x4{};
+
+  // tiles wave, wave + 4, ... of the split; the fetch of tile i+1 is always issued (clamped
+  // to the last tile) so that the wait counts are static
+  auto load_tile = [&](int tile, bf16x8 (&kk)[2][KC], bf16x4 (&vv)[2][DT]) {
+#pragma unroll
+    for (int p = 0; p < 2; ++p) {
+      int pl = 2 * tile + p;                                   // page within the split
+      pl = pl < n_pages ? pl : n_pages - 1;                    // a missing second page re-reads the last one
+      const int page = __builtin_amdgcn_readlane(my_page, __builtin_amdgcn_readfirstlane(pl));
+      const size_t off = ((size_t)page * Hkv + kvh) * blk_elems;
+      const bf16x8* kp = reinterpret_cast<const bf16x8*>(kbase + off);
+      const bf16x4* vp = reinterpret_cast<const bf16x4*>(vbase + off);
+#pragma unroll
+      for (int c = 0; c < KC; ++c) kk[p][c] = kp[c * 64 + lane];
+#pragma unroll
+      for (int d = 0; d < DT; ++d) vv[p][d] = vp[(d * 16 + hh) * 4 + g];
+    }
+  };
+
+  if (wave < n_tiles) {
+    bf16x8 kf[2][KC];
+    bf16x4 vf[2][DT];
+    load_tile(wave, kf, vf);
+    for (int tile = wave; tile < n_tiles; tile += ATT_WAVES) {
+      bf16x8 kn[2][KC];
+      bf16x4 vn[2][DT];
+      const int nxt = tile + ATT_WAVES < n_tiles ? tile + ATT_WAVES : tile;
+      load_tile(nxt, kn, vn);
+      __builtin_amdgcn_sched_barrier(0);
+
+      const int t0 = t_begin + tile * 32;
+      f32x4 sacc[2];
+#pragma unroll
+      for (int p = 0; p < 2; ++p) {
+        sacc[p] = f32x4{};
+#pragma unroll
+        for (int c = 0; c < KC; ++c)
+          sacc[p] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[p][c], qf[c], sacc[p], 0, 0, 0);
+      }
+      float sv[8];
+      float mx = -INFINITY;
+#pragma unroll
+      for (int p = 0; p < 2; ++p)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int tok = t0 + p * 16 + 4 * g + i;
+          const float v = tok < t_end ? sacc[p][i] * scale : -INFINITY;
+          sv[p * 4 + i] = v;
+          mx = fmaxf(mx, v);
+        }
+      mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      const float m_new = fmaxf(m_run, mx);
+      const float corr = __expf(m_run - m_new);
+      float rs = 0.f;
+      bf16x8 pf;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const float pe = __expf(sv[e] - m_new);
+        rs += pe;
+        pf[e] = (bf16_t)pe;
+      }
+      rs += __shfl_xor(rs, 16, 64);
+      rs += __shfl_xor(rs, 32, 64);
+      l_run = l_run * corr + rs;
+      m_run = m_new;
+#pragma unroll
+      for (int d = 0; d < DT; ++d) {
+        oacc[d] *= corr;
+        bf16x8 af;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) { af[j] = vf[0][d][j]; af[4 + j] = vf[1][d][j]; }
+        oacc[d] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af, pf, oacc[d], 0, 0, 0);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int p = 0; p < 2; ++p) {
+#pragma unroll
+        for (int c = 0; c < KC; ++c) kf[p][c] = kn[p][c];
+#pragma unroll
+        for (int d = 0; d < DT; ++d) vf[p][d] = vn[p][d];
+      }
+    }
+  }
+
+  // ---- merge the wavefronts of this workgroup through LDS, in wavefront order -----------
+  {
+    float* my = lds + wave * REC;
+    if (g == 0) { my[hh] = m_run; my[16 + hh] = l_run; }
+#pragma unroll
+    for (int d = 0; d < DT; ++d) *reinterpret_cast<f32x4*>(my + 32 + hh * DH + d * 16 + 4 * g) = oacc[d];
+  }
+  __syncthreads();
+  if (wave != 0) {
+    if (n_splits == 1) return;
+  } else {
+    float M = lds[hh];
+#pragma unroll
+    for (int w = 1; w < ATT_WAVES; ++w) M = fmaxf(M, lds[w * REC + hh]);
+    float lsum = 0.f;
+#pragma unroll
+    for (int d = 0; d < DT; ++d) oacc[d] = f32x4{};
+#pragma unroll
+    for (int w = 0; w < ATT_WAVES; ++w) {
+      const float* p = lds + w * REC;
+      const float wgt = __expf(p[hh] - M);
+      lsum += wgt * p[16 + hh];
+#pragma unroll
+      for (int d = 0; d < DT; ++d) oacc[d] += *reinterpret_cast<const f32x4*>(p + 32 + hh * DH + d * 16 + 4 * g) * wgt;
+    }
+    m_run = M;
+    l_run = lsum;
+  }
+
+  const int K = Hq * DH;
+  if (n_splits == 1) {
+    if (hh < G) {
+      const float inv = 1.0f / l_run;
+#pragma unroll
+      for (int d = 0; d < DT; ++d) {
+        bf16x4 o;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) o[i] = (bf16_t)(oacc[d][i] * inv);
+        *reinterpret_cast<bf16x4*>(out + act_index<true>(r, (kvh * G + hh) * DH + d * 16 + 4 * g, K)) = o;
+      }
+    }
+    return;
+  }
+
+  // ---- several splits: publish (m, l, O); the last workgroup to arrive merges --------------
+  if (wave == 0) {
+    float* my = ws + (((size_t)wr * Hkv + kvh) * max_splits + split) * REC;
+    if (g == 0) { my[hh] = m_run; my[16 + hh] = l_run; }
+#pragma unroll
+    for (int d = 0; d < DT; ++d) *reinterpret_cast<f32x4*>(my + 32 + hh * DH + d * 16 + 4 * g) = oacc[d];
+    __threadfence();
+    if (lane == 0) s_last = atomicAdd(&counters[wr * Hkv + kvh], 1) == n_splits - 1;
+  }
+  __syncthreads();
+  if (!s_last || wave != 0) return;
+  __threadfence();
+  const float* base = ws + ((size_t)wr * Hkv + kvh) * max_splits * REC;
+  // every load of the merge is independent of the others: issue them in batches
+  float M = -INFINITY;
+#pragma unroll
+  for (int k = 0; k < 8; ++k) {                      // max_splits <= 32: lane group g takes splits g, g+4, ...
+    const int si = g + 4 * k;
+    M = fmaxf(M, base[(size_t)(si < n_splits ? si : n_splits - 1) * REC + hh]);
+  }
+  M = fmaxf(M, __shfl_xor(M, 16, 64));
+  M = fmaxf(M, __shfl_xor(M, 32, 64));
+  float lsum = 0.f;
+  f32x4 acc[DT];
+#pragma unroll
+  for (int d = 0; d < DT; ++d) acc[d] = f32x4{};
+  for (int i0 = 0; i0 < n_splits; i0 += 2) {
+    float mi[2], li[2];
+    f32x4 o[2][DT];
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      const float* p = base + (size_t)(i0 + u < n_splits ? i0 + u : n_splits - 1) * REC;
+      mi[u] = p[hh];
+      li[u] = p[16 + hh];
+#pragma unroll
+      for (int d = 0; d < DT; ++d) o[u][d] = *reinterpret_cast<const f32x4*>(p + 32 + hh * DH + d * 16 + 4 * g);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      const float wgt = i0 + u < n_splits ? __expf(mi[u] - M) : 0.f;
+      lsum += wgt * li[u];
+#pragma unroll
+      for (int d = 0; d < DT; ++d) acc[d] += o[u][d] * wgt;
+    }
+  }
+  if (hh < G) {
+    const float inv = 1.0f / lsum;
+#pragma unroll
+    for (int d = 0; d < DT; ++d) {
+      bf16x4 o;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) o[i] = (bf16_t)(acc[d][i] * inv);
+      *reinterpret_cast<bf16x4*>(out + act_index<true>(r, (kvh * G + hh) * DH + d * 16 + 4 * g, K)) = o;
+    }
+  }
+  if (lane == 0) counters[wr * Hkv + kvh] = 0;
+}
+
+int attn_split_tokens() { return ATT_SPLIT; }
+
+void launch_attn_decode(hipStream_t st, RowCtx rc, int row_base, Slots s, const float* q_rot, const bf16_t* kv_pool,
+                        KVLayout kvl, int layer, int n_q_heads, bf16_t* out, float* ws, int* counters,
+                        int max_splits, int grid_splits) {
+  dim3 grid(rc.max_rows, kvl.n_kv_heads, grid_splits), block(64 * ATT_WAVES);
+  switch (kvl.head_dim) {
+    case 32:
+      hipLaunchKernelGGL(attn_decode_kernel<32>, grid, block, 0, st, rc, row_base, s, q_rot, kv_pool, kvl, layer,
+                         n_q_heads, out, ws, counters, max_splits);
+      break;
+    case 64:
+      hipLaunchKernelGGL(attn_decode_kernel<64>, grid, block, 0, st, rc, row_base, s, q_rot, kv_pool, kvl, layer,
+                         n_q_heads, out, ws, counters, max_splits);
+      break;
+    default:
+      hipLaunchKernelGGL(attn_decode_kernel<128>, grid, block, 0, st, rc, row_base, s, q_rot, kv_pool, kvl, layer,
+                         n_q_heads, out, ws, counters, max_splits);
+      break;
+  }
+}
+
+}  // namespace april

@@ -208,9 +208,9 @@ template void launch_embed<bf16_t>(hipStream_t, RowCtx, Slots, const bf16_t*, fl
 // Residual add (deterministic sum of split-K partials) + RMSNorm.
 // One workgroup per output row; each thread owns up to 4 chunks of 8 columns.
 // ---------------------------------------------------------------------------
-template <typename T, bool XF>
+template <typename T, bool XF, int NP>
 __global__ __launch_bounds__(256) void add_rmsnorm_kernel(RowCtx rc, float* x_res, const float* partials,
-                                                          int n_partials, size_t partial_stride,
+                                                          int n_partials_rt, size_t partial_stride,
                                                           const float* gain, T* h, int d, float eps,
                                                           const int* gather) {
   const int r = blockIdx.x;
@@ -225,13 +225,28 @@ __global__ __launch_bounds__(256) void add_rmsnorm_kernel(RowCtx rc, float* x_re
     const int ch = threadIdx.x + c * 256;
     if (ch < nchunk) {
       float* xp = x_res + (size_t)rin * d + ch * 8;
+      // NP >= 0: compile-time partial count, every load issued before the first add
+      const int n_partials = NP >= 0 ? NP : n_partials_rt;
+      f32x4 xv[2] = {*reinterpret_cast<const f32x4*>(xp), *reinterpret_cast<const f32x4*>(xp + 4)};
+      if (NP >= 0) {
+        f32x4 pv[NP > 0 ? NP : 1][2];
 #pragma unroll
-      for (int j = 0; j < 8; ++j) v[c][j] = xp[j];
-      for (int p = 0; p < n_partials; ++p) {
-        const float* pp = partials + p * partial_stride + (size_t)rin * d + ch * 8;
+        for (int p = 0; p < NP; ++p) {
+          const float* pp = partials + p * partial_stride + (size_t)rin * d + ch * 8;
+          pv[p][0] = *reinterpret_cast<const f32x4*>(pp);
+          pv[p][1] = *reinterpret_cast<const f32x4*>(pp + 4);
+        }
 #pragma unroll
-        for (int j = 0; j < 8; ++j) v[c][j] += pp[j];
+        for (int p = 0; p < NP; ++p) { xv[0] += pv[p][0]; xv[1] += pv[p][1]; }
+      } else {
+        for (int p = 0; p < n_partials; ++p) {
+          const float* pp = partials + p * partial_stride + (size_t)rin * d + ch * 8;
+          xv[0] += *reinterpret_cast<const f32x4*>(pp);
+          xv[1] += *reinterpret_cast<const f32x4*>(pp + 4);
+        }
       }
+#pragma unroll
+      for (int j = 0; j < 8; ++j) v[c][j] = xv[j >> 2][j & 3];
       if (n_partials > 0) {
 #pragma unroll
         for (int j = 0; j < 8; ++j) xp[j] = v[c][j];
@@ -258,8 +273,22 @@ __global__ __launch_bounds__(256) void add_rmsnorm_kernel(RowCtx rc, float* x_re
 template <typename T, bool XF>
 void launch_add_rmsnorm(hipStream_t st, RowCtx rc, float* x_res, const float* partials, int n_partials,
                         size_t partial_stride, const float* gain, T* h, int d, float eps, const int* gather) {
-  hipLaunchKernelGGL((add_rmsnorm_kernel<T, XF>), dim3(rc.max_rows), dim3(256), 0, st, rc, x_res, partials,
-                     n_partials, partial_stride, gain, h, d, eps, gather);
+#define ARN_CASE(NP)                                                                                          \
+  hipLaunchKernelGGL((add_rmsnorm_kernel<T, XF, NP>), dim3(rc.max_rows), dim3(256), 0, st, rc, x_res, partials, \
+                     n_partials, partial_stride, gain, h, d, eps, gather)
+  switch (n_partials) {
+    case 0: ARN_CASE(0); break;
+    case 1: ARN_CASE(1); break;
+    case 2: ARN_CASE(2); break;
+    case 3: ARN_CASE(3); break;
+    case 4: ARN_CASE(4); break;
+    case 5: ARN_CASE(5); break;
+    case 6: ARN_CASE(6); break;
+    case 7: ARN_CASE(7); break;
+    case 8: ARN_CASE(8); break;
+    default: ARN_CASE(-1); break;
+  }
+#undef ARN_CASE
 }
 template void launch_add_rmsnorm<float, false>(hipStream_t, RowCtx, float*, const float*, int, size_t, const float*, float*, int, float, const int*);
 template void launch_add_rmsnorm<bf16_t, true>(hipStream_t, RowCtx, float*, const float*, int, size_t, const float*, bf16_t*, int, float, const int*);
@@ -356,16 +385,15 @@ __global__ __launch_bounds__(64) void attn_ref_kernel(RowCtx rc, Slots s, const 
   float m = -INFINITY, l = 0.f, o0 = 0.f, o1 = 0.f;
   for (int j = 0; j < ctx; ++j) {
     const int page = bt[j / L.blk], t = j % L.blk;
-    const size_t kb = L.at(layer, 0, page, kvh, t, 0), vb = L.at(layer, 1, page, kvh, t, 0);
     float part = 0.f;
-    if (has0) part += q0 * to_f32(kv_pool[kb + lane]);
-    if (has1) part += q1 * to_f32(kv_pool[kb + lane + 64]);
+    if (has0) part += q0 * to_f32(kv_pool[L.at(layer, 0, page, kvh, t, lane)]);
+    if (has1) part += q1 * to_f32(kv_pool[L.at(layer, 0, page, kvh, t, lane + 64)]);
     const float sc = wave_sum(part) * scale;
     const float m_new = fmaxf(m, sc);
     const float corr = expf(m - m_new), p = expf(sc - m_new);
     l = l * corr + p;
-    if (has0) o0 = o0 * corr + p * to_f32(kv_pool[vb + lane]);
-    if (has1) o1 = o1 * corr + p * to_f32(kv_pool[vb + lane + 64]);
+    if (has0) o0 = o0 * corr + p * to_f32(kv_pool[L.at(layer, 1, page, kvh, t, lane)]);
+    if (has1) o1 = o1 * corr + p * to_f32(kv_pool[L.at(layer, 1, page, kvh, t, lane + 64)]);
     m = m_new;
   }
   const int K = Hq * dh;

@@ -29,14 +29,20 @@ void launch_shuffle_weights(hipStream_t st, const bf16_t* src, bf16_t* dst, int 
                      reinterpret_cast<bf16x8*>(dst), N, K);
 }
 
-enum { EPI_F32 = 0, EPI_SWIGLU = 1 };
+enum { EPI_F32 = 0, EPI_SWIGLU = 1, EPI_LOGITS = 2 };
 
-// One wavefront: NT weight tiles x MTC activation tiles over k-tiles [kt0, kt1).
-template <int NT, int MTC, int EPI>
-__device__ inline void gemm_wave(const bf16x8* __restrict__ w0, const bf16x8* __restrict__ w1,
-                                 const bf16x8* __restrict__ x, int KT, int kt0, int kt1, int nt0, int mt0,
-                                 int rows, int N, float* __restrict__ out, bf16_t* __restrict__ act) {
-  const int lane = threadIdx.x & 63;
+constexpr int KW = 4;        // wavefronts of a workgroup; they split the k range among themselves
+constexpr int KU = 8;        // k-tiles fetched per loop trip
+
+// One workgroup: NT weight tiles x MTC activation tiles over k-tiles [k0, k1).  Each of
+// the KW wavefronts accumulates a quarter of the k range, the partial accumulators are
+// summed through LDS in a fixed tree order, wavefront 0 runs the epilogue.
+template <int NT, int MTC, int EPI, bool INTRA>
+__device__ inline void gemm_group(const bf16x8* __restrict__ w0, const bf16x8* __restrict__ w1,
+                                  const bf16x8* __restrict__ x, int KT, int k0, int k1, int nt0, int mt0,
+                                  int rows, int N, float* __restrict__ out, bf16_t* __restrict__ act,
+                                  float* red) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   f32x16 acc[NT][MTC];
 #pragma unroll
   for (int i = 0; i < NT; ++i)
@@ -55,22 +61,79 @@ __device__ inline void gemm_wave(const bf16x8* __restrict__ w0, const bf16x8* __
 #pragma unroll
   for (int j = 0; j < MTC; ++j) xp[j] = x + (size_t)(mt0 + j) * KT * 64 + lane;
 
-#pragma unroll 4
-  for (int kt = kt0; kt < kt1; ++kt) {
-    bf16x8 a[NT], b[MTC];
+  const int len = k1 - k0;
+  const int kb = INTRA ? k0 + (int)((long long)len * wave / KW) : k0;
+  const int ke = INTRA ? k0 + (int)((long long)len * (wave + 1) / KW) : k1;
+  // KU k-tiles per trip; the last trip re-reads the final tile for the missing ones
+  // (loads stay unconditional and in flight together) and skips their MFMAs.
+  for (int kt = kb; kt < ke; kt += KU) {
+    bf16x8 a[KU][NT], b[KU][MTC];
 #pragma unroll
-    for (int i = 0; i < NT; ++i) a[i] = wp[i][(size_t)kt * 64];
+    for (int u = 0; u < KU; ++u) {
+      const size_t k = (size_t)(kt + u < ke ? kt + u : ke - 1) * 64;
 #pragma unroll
-    for (int j = 0; j < MTC; ++j) b[j] = xp[j][(size_t)kt * 64];
+      for (int i = 0; i < NT; ++i) a[u][i] = wp[i][k];
 #pragma unroll
-    for (int i = 0; i < NT; ++i)
+      for (int j = 0; j < MTC; ++j) b[u][j] = xp[j][k];
+    }
+    // keep every load of this trip in flight before the first MFMA waits on one
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int j = 0; j < MTC; ++j)
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+    for (int u = 0; u < KU; ++u) {
+      if (kt + u < ke) {
+#pragma unroll
+        for (int i = 0; i < NT; ++i)
+#pragma unroll
+          for (int j = 0; j < MTC; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[u][i], b[u][j], acc[i][j], 0, 0, 0);
+      }
+    }
   }
 
+  // tree reduction over the KW wavefronts: (2,3) -> (0,1), then 1 -> 0
+  constexpr int NREG = NT * MTC * 16;
+#pragma unroll
+  for (int stride = INTRA ? KW / 2 : 0; stride >= 1; stride >>= 1) {
+    if (wave >= stride && wave < 2 * stride) {
+      float* dst = red + (size_t)(wave - stride) * NREG * 64 + lane;
+#pragma unroll
+      for (int i = 0; i < NT; ++i)
+#pragma unroll
+        for (int j = 0; j < MTC; ++j)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) dst[((i * MTC + j) * 16 + e) * 64] = acc[i][j][e];
+    }
+    __syncthreads();
+    if (wave < stride) {
+      const float* src = red + (size_t)wave * NREG * 64 + lane;
+#pragma unroll
+      for (int i = 0; i < NT; ++i)
+#pragma unroll
+        for (int j = 0; j < MTC; ++j)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) acc[i][j][e] += src[((i * MTC + j) * 16 + e) * 64];
+    }
+    __syncthreads();
+  }
+  if (INTRA && wave != 0) return;
+
   const int mloc = lane & 31, nhalf = (lane >> 5) << 2;
-  if (EPI == EPI_F32) {
+  if (EPI == EPI_LOGITS) {
+    // per row: the maximum over this wavefront's NT*32 output columns (a group of the
+    // sampler's candidate search), in the order-preserving integer key of the sampler
+#pragma unroll
+    for (int j = 0; j < MTC; ++j) {
+      float mxv = acc[0][j][0];
+#pragma unroll
+      for (int i = 0; i < NT; ++i)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) mxv = fmaxf(mxv, acc[i][j][e]);
+      mxv = fmaxf(mxv, __shfl_xor(mxv, 32, 64));
+      const int m = (mt0 + j) * 32 + mloc;
+      if (m < rows && lane < 32) reinterpret_cast<float*>(act)[(size_t)m * (N / (32 * NT)) + nt0 / NT] = mxv;
+    }
+  }
+  if (EPI == EPI_F32 || EPI == EPI_LOGITS) {
 #pragma unroll
     for (int i = 0; i < NT; ++i)
 #pragma unroll
@@ -107,60 +170,74 @@ __device__ inline void gemm_wave(const bf16x8* __restrict__ w0, const bf16x8* __
   }
 }
 
-// grid: x = groups of 4 wavefronts over n-tile groups, y = k-split, z = group of MT m-tiles.
-template <int NT, int MT, int EPI>
-__global__ __launch_bounds__(256) void gemm_mfma_kernel(RowCtx rc, const bf16x8* __restrict__ x,
-                                                        const bf16x8* __restrict__ w0,
-                                                        const bf16x8* __restrict__ w1, float* __restrict__ out,
-                                                        bf16_t* __restrict__ act, int N, int K, int ksplit,
-                                                        size_t partial_stride) {
+// grid: x = n-tile group, y = k-split across workgroups, z = group of MT m-tiles.
+// INTRA: the 4 wavefronts of a workgroup split the k range of one n-tile group (few
+// n-tiles, or fused SwiGLU); otherwise each wavefront owns its own n-tile group.
+template <int NT, int MT, int EPI, bool INTRA>
+__global__ __launch_bounds__(64 * KW) void gemm_mfma_kernel(RowCtx rc, const bf16x8* __restrict__ x,
+                                                           const bf16x8* __restrict__ w0,
+                                                           const bf16x8* __restrict__ w1, float* __restrict__ out,
+                                                           bf16_t* __restrict__ act, int N, int K, int ksplit,
+                                                           size_t partial_stride) {
+  __shared__ float red[INTRA ? (KW / 2) * NT * MT * 16 * 64 : 1];
   if (rc.stop != nullptr && *rc.stop != 0) return;
   const int rows = *rc.n_rows;
   const int mt0 = blockIdx.z * MT;
   if (mt0 * 32 >= rows) return;
-  const int n_tiles = N >> 5, KT = K >> 4;
-  const int gw = blockIdx.x * 4 + (threadIdx.x >> 6);
-  const int nt0 = (EPI == EPI_SWIGLU) ? gw : gw * NT;
-  if (nt0 >= n_tiles) return;
+  const int KT = K >> 4;
+  const int grp = INTRA ? blockIdx.x : blockIdx.x * KW + (threadIdx.x >> 6);
+  const int nt0 = (EPI == EPI_SWIGLU) ? grp : grp * NT;
+  if (!INTRA && nt0 >= (N >> 5)) return;
   const int sidx = blockIdx.y;
-  const int kt0 = (int)((long long)KT * sidx / ksplit), kt1 = (int)((long long)KT * (sidx + 1) / ksplit);
+  const int k0 = (int)((long long)KT * sidx / ksplit), k1 = (int)((long long)KT * (sidx + 1) / ksplit);
   float* o = out ? out + sidx * partial_stride : nullptr;
   int mtc = ceil_div(rows, 32) - mt0;
   if (mtc > MT) mtc = MT;
   switch (mtc) {
-    case 1: gemm_wave<NT, 1, EPI>(w0, w1, x, KT, kt0, kt1, nt0, mt0, rows, N, o, act); break;
-    case 2: gemm_wave<NT, (MT >= 2 ? 2 : 1), EPI>(w0, w1, x, KT, kt0, kt1, nt0, mt0, rows, N, o, act); break;
-    case 3: gemm_wave<NT, (MT >= 3 ? 3 : 1), EPI>(w0, w1, x, KT, kt0, kt1, nt0, mt0, rows, N, o, act); break;
-    default: gemm_wave<NT, MT, EPI>(w0, w1, x, KT, kt0, kt1, nt0, mt0, rows, N, o, act); break;
+    case 1: gemm_group<NT, 1, EPI, INTRA>(w0, w1, x, KT, k0, k1, nt0, mt0, rows, N, o, act, red); break;
+    case 2: gemm_group<NT, (MT >= 2 ? 2 : 1), EPI, INTRA>(w0, w1, x, KT, k0, k1, nt0, mt0, rows, N, o, act, red); break;
+    case 3: gemm_group<NT, (MT >= 3 ? 3 : 1), EPI, INTRA>(w0, w1, x, KT, k0, k1, nt0, mt0, rows, N, o, act, red); break;
+    default: gemm_group<NT, MT, EPI, INTRA>(w0, w1, x, KT, k0, k1, nt0, mt0, rows, N, o, act, red); break;
   }
 }
 
 void launch_gemm_mfma(hipStream_t st, RowCtx rc, const bf16_t* x, const bf16_t* Wp, float* out, int N, int K,
                       int ksplit, size_t partial_stride) {
-  constexpr int NT = 2, MT = 4;
+  constexpr int MT = 4;
   const int n_tiles = N >> 5;
-  // N/32 may be odd: the kernel's last wavefront would read one tile past the end, so
-  // fall back to NT = 1 in that case.
   const int m_groups = ceil_div(ceil_div(rc.max_rows, 32), MT);
-  if (n_tiles % NT == 0) {
-    dim3 grid(ceil_div(n_tiles / NT, 4), ksplit, m_groups);
-    hipLaunchKernelGGL((gemm_mfma_kernel<NT, MT, EPI_F32>), grid, dim3(256), 0, st, rc,
-                       reinterpret_cast<const bf16x8*>(x), reinterpret_cast<const bf16x8*>(Wp), nullptr, out,
-                       nullptr, N, K, ksplit, partial_stride);
+  const bf16x8* xv = reinterpret_cast<const bf16x8*>(x);
+  const bf16x8* wv = reinterpret_cast<const bf16x8*>(Wp);
+  if (n_tiles >= 2048 && n_tiles % 2 == 0) {
+    // plenty of n-tiles (LM head): one wavefront per pair of tiles, whole k range
+    dim3 grid(ceil_div(n_tiles / 2, KW), ksplit, m_groups);
+    hipLaunchKernelGGL((gemm_mfma_kernel<2, MT, EPI_F32, false>), grid, dim3(64 * KW), 0, st, rc, xv, wv, nullptr,
+                       out, nullptr, N, K, ksplit, partial_stride);
   } else {
-    dim3 grid(ceil_div(n_tiles, 4), ksplit, m_groups);
-    hipLaunchKernelGGL((gemm_mfma_kernel<1, MT, EPI_F32>), grid, dim3(256), 0, st, rc,
-                       reinterpret_cast<const bf16x8*>(x), reinterpret_cast<const bf16x8*>(Wp), nullptr, out,
-                       nullptr, N, K, ksplit, partial_stride);
+    dim3 grid(n_tiles, ksplit, m_groups);
+    hipLaunchKernelGGL((gemm_mfma_kernel<1, MT, EPI_F32, true>), grid, dim3(64 * KW), 0, st, rc, xv, wv, nullptr,
+                       out, nullptr, N, K, ksplit, partial_stride);
   }
+}
+
+int lmhead_group_cols() { return 64; }
+
+void launch_gemm_mfma_logits(hipStream_t st, RowCtx rc, const bf16_t* x, const bf16_t* Wp, float* logits,
+                             float* group_max, int V, int K) {
+  constexpr int MT = 4;
+  const int n_tiles = V >> 5;
+  dim3 grid(ceil_div(n_tiles / 2, KW), 1, ceil_div(ceil_div(rc.max_rows, 32), MT));
+  hipLaunchKernelGGL((gemm_mfma_kernel<2, MT, EPI_LOGITS, false>), grid, dim3(64 * KW), 0, st, rc,
+                     reinterpret_cast<const bf16x8*>(x), reinterpret_cast<const bf16x8*>(Wp), nullptr, logits,
+                     reinterpret_cast<bf16_t*>(group_max), V, K, 1, (size_t)0);
 }
 
 void launch_gemm_mfma_swiglu(hipStream_t st, RowCtx rc, const bf16_t* x, const bf16_t* Wg, const bf16_t* Wu,
                              bf16_t* act, int F, int K) {
   constexpr int MT = 4;
   const int n_tiles = F >> 5;
-  dim3 grid(ceil_div(n_tiles, 4), 1, ceil_div(ceil_div(rc.max_rows, 32), MT));
-  hipLaunchKernelGGL((gemm_mfma_kernel<2, MT, EPI_SWIGLU>), grid, dim3(256), 0, st, rc,
+  dim3 grid(n_tiles, 1, ceil_div(ceil_div(rc.max_rows, 32), MT));
+  hipLaunchKernelGGL((gemm_mfma_kernel<2, MT, EPI_SWIGLU, true>), grid, dim3(64 * KW), 0, st, rc,
                      reinterpret_cast<const bf16x8*>(x), reinterpret_cast<const bf16x8*>(Wg),
                      reinterpret_cast<const bf16x8*>(Wu), nullptr, act, F, K, 1, (size_t)0);
 }

@@ -2,12 +2,21 @@
 // state update: append the token, advance the generated length, detect completion
 // and count it for the early-termination scheduler (Section 2.2).  One workgroup
 // per sampling row.  gfx950.
+//
+// Top-k is exact: the k largest logits, ties broken by lower index, in descending
+// order.  When the LM-head GEMM has left the maximum of every group of 64 logits, the
+// k-th largest group maximum is a lower bound of the k-th largest logit (each group
+// maximum is a logit), so only the groups whose maximum reaches it are read again.
+// Without group maxima (or if a candidate list overflows) a 4-pass radix select over
+// the whole row is used.
 #include "kernels.h"
 
 namespace april {
 
 #define SAMPLE_THREADS 1024
 #define MAX_TOPK 64
+#define MAX_HOT 1024
+#define MAX_CAND 2048
 
 // Order-preserving map float -> unsigned (larger float <=> larger key); -0 == +0.
 __device__ inline unsigned f2key(float f) {
@@ -31,24 +40,90 @@ __device__ inline unsigned philox4x32_10_word0(unsigned c0, unsigned c1, unsigne
   return c0;
 }
 
+struct SampleShared {
+  unsigned hist[256];
+  unsigned prefix, krem, ntie;
+  int cnt, choice, watch_row, n_hot, overflow;
+  unsigned cand_key[MAX_CAND];
+  int cand_idx[MAX_CAND];
+  int hot[MAX_HOT];
+  float sort_logit[MAX_TOPK];
+  int sort_idx[MAX_TOPK];
+  unsigned red_key[16];
+  int red_idx[16];
+};
+
+// Key of the k-th largest of vals[0..n) (k <= n): 4 radix passes of 8 bits.  On return
+// sh.prefix = that key, sh.krem = how many entries equal to it belong to the top k,
+// sh.ntie = how many entries equal it.  All threads must call.
+__device__ inline void block_kth_largest(const float* vals, int n, int k, SampleShared& sh) {
+  const int tid = threadIdx.x;
+  if (tid == 0) { sh.prefix = 0u; sh.krem = (unsigned)k; }
+  for (int pass = 0; pass < 4; ++pass) {
+    const int shift = 24 - 8 * pass;
+    const unsigned mask_hi = pass == 0 ? 0u : (0xFFFFFFFFu << (shift + 8));
+    if (tid < 256) sh.hist[tid] = 0u;
+    __syncthreads();
+    const unsigned prefix = sh.prefix;
+    for (int i = tid; i < n; i += SAMPLE_THREADS) {
+      const unsigned key = f2key(vals[i]);
+      if ((key & mask_hi) == prefix) atomicAdd(&sh.hist[(key >> shift) & 255u], 1u);
+    }
+    __syncthreads();
+    if (tid == 0) {
+      unsigned cum = 0u;
+      const unsigned krem = sh.krem;
+      for (int b = 255; b >= 0; --b) {
+        if (cum + sh.hist[b] >= krem) {
+          sh.prefix = prefix | ((unsigned)b << shift);
+          sh.krem = krem - cum;
+          sh.ntie = sh.hist[b];
+          break;
+        }
+        cum += sh.hist[b];
+      }
+    }
+    __syncthreads();
+  }
+}
+
+// Block arg-max with lowest index on ties over vals[idx0 + i*stride...]: generic helper.
+__device__ inline int block_argmax(const float* vals, int n, SampleShared& sh) {
+  const int tid = threadIdx.x, lane = tid & 63, wid = tid >> 6;
+  unsigned bk = 0u;
+  int bi = 0x7fffffff;
+  for (int i = tid; i < n; i += SAMPLE_THREADS) {
+    const unsigned k = f2key(vals[i]);
+    if (bi == 0x7fffffff || k > bk) { bk = k; bi = i; }     // ascending i: first maximum stays
+  }
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) {
+    const unsigned ok = __shfl_xor(bk, off, 64);
+    const int oi = __shfl_xor(bi, off, 64);
+    if (ok > bk || (ok == bk && oi < bi)) { bk = ok; bi = oi; }
+  }
+  __syncthreads();
+  if (lane == 0) { sh.red_key[wid] = bk; sh.red_idx[wid] = bi; }
+  __syncthreads();
+  if (tid == 0) {
+    for (int x = 1; x < SAMPLE_THREADS / 64; ++x)
+      if (sh.red_key[x] > bk || (sh.red_key[x] == bk && sh.red_idx[x] < bi)) { bk = sh.red_key[x]; bi = sh.red_idx[x]; }
+    sh.choice = bi;
+  }
+  __syncthreads();
+  return sh.choice;
+}
+
 __global__ __launch_bounds__(SAMPLE_THREADS) void sample_kernel(RowCtx rc, Slots s, Ctrl* ctrl,
                                                                 const float* logits, int V, SamplerCfg sc,
                                                                 Watch w, int update, const long long* req_ids,
-                                                                const int* gen_idx, int* out_tokens) {
+                                                                const int* gen_idx, int* out_tokens,
+                                                                const float* group_max, int group) {
   const int r = blockIdx.x;
   ROW_GUARD(rc, r);
   const int tid = threadIdx.x, lane = tid & 63, wid = tid >> 6;
   const float* lg = logits + (size_t)r * V;
-
-  __shared__ unsigned hist[256];
-  __shared__ unsigned s_prefix, s_krem, s_ntie;
-  __shared__ int s_cnt, s_choice, s_watch_row;
-  __shared__ unsigned cand_key[MAX_TOPK];
-  __shared__ int cand_idx[MAX_TOPK];
-  __shared__ float sort_logit[MAX_TOPK];
-  __shared__ int sort_idx[MAX_TOPK];
-  __shared__ unsigned red_key[16];
-  __shared__ int red_idx[16];
+  __shared__ SampleShared sh;
 
   int slot = -1, pos = 0, g = 0;
   long long req = 0;
@@ -61,135 +136,133 @@ __global__ __launch_bounds__(SAMPLE_THREADS) void sample_kernel(RowCtx rc, Slots
     req = req_ids[r];
     g = gen_idx[r];
   }
+  const int n_groups = group_max ? V / group : 0;
+  const float* gm = group_max ? group_max + (size_t)r * n_groups : nullptr;
 
   if (sc.kind == 0 || sc.top_k <= 1) {
-    // ---- greedy: maximum, lowest index on ties --------------------------------
-    unsigned bk = 0u; int bi = 0x7fffffff;
-    for (int i = tid; i < V; i += SAMPLE_THREADS) {
-      const unsigned k = f2key(lg[i]);
-      if (bi == 0x7fffffff || k > bk) { bk = k; bi = i; }     // ascending i: first maximum stays
-    }
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) {
-      const unsigned ok = __shfl_xor(bk, off, 64);
-      const int oi = __shfl_xor(bi, off, 64);
-      if (ok > bk || (ok == bk && oi < bi)) { bk = ok; bi = oi; }
-    }
-    if (lane == 0) { red_key[wid] = bk; red_idx[wid] = bi; }
-    __syncthreads();
-    if (tid == 0) {
-      for (int x = 1; x < SAMPLE_THREADS / 64; ++x)
-        if (red_key[x] > bk || (red_key[x] == bk && red_idx[x] < bi)) { bk = red_key[x]; bi = red_idx[x]; }
-      s_choice = bi;
-    }
-    __syncthreads();
-  } else {
-    // ---- top-k: radix select of the k-th largest key, gather, sort, sample ---
-    const int k = sc.top_k < V ? (sc.top_k < MAX_TOPK ? sc.top_k : MAX_TOPK) : (V < MAX_TOPK ? V : MAX_TOPK);
-    if (tid == 0) { s_prefix = 0u; s_krem = (unsigned)k; }
-    for (int pass = 0; pass < 4; ++pass) {
-      const int shift = 24 - 8 * pass;
-      const unsigned mask_hi = pass == 0 ? 0u : (0xFFFFFFFFu << (shift + 8));
-      if (tid < 256) hist[tid] = 0u;
+    // ---- greedy: maximum, lowest index on ties --------------------------------------
+    if (gm) {
+      const int gi = block_argmax(gm, n_groups, sh);               // lowest group holding the maximum
+      const int li = block_argmax(lg + (size_t)gi * group, group, sh);
+      if (tid == 0) sh.choice = gi * group + li;
       __syncthreads();
-      const unsigned prefix = s_prefix;
+    } else {
+      block_argmax(lg, V, sh);
+    }
+  } else {
+    const int k = sc.top_k < V ? (sc.top_k < MAX_TOPK ? sc.top_k : MAX_TOPK) : (V < MAX_TOPK ? V : MAX_TOPK);
+    bool have = false;
+    if (gm && n_groups >= k) {
+      // ---- candidates from the groups whose maximum reaches the k-th largest maximum ---
+      block_kth_largest(gm, n_groups, k, sh);
+      const unsigned tau = sh.prefix;
+      if (tid == 0) { sh.n_hot = 0; sh.cnt = 0; sh.overflow = 0; }
+      __syncthreads();
+      for (int i = tid; i < n_groups; i += SAMPLE_THREADS)
+        if (f2key(gm[i]) >= tau) {
+          const int p = atomicAdd(&sh.n_hot, 1);
+          if (p < MAX_HOT) sh.hot[p] = i; else sh.overflow = 1;
+        }
+      __syncthreads();
+      if (!sh.overflow) {
+        const int n_hot = sh.n_hot;
+        for (int e = tid; e < n_hot * group; e += SAMPLE_THREADS) {
+          const int idx = sh.hot[e / group] * group + e % group;
+          const unsigned key = f2key(lg[idx]);
+          if (key >= tau) {
+            const int p = atomicAdd(&sh.cnt, 1);
+            if (p < MAX_CAND) { sh.cand_key[p] = key; sh.cand_idx[p] = idx; } else sh.overflow = 1;
+          }
+        }
+        __syncthreads();
+        have = !sh.overflow;
+      }
+      __syncthreads();
+    }
+    if (!have) {
+      // ---- radix select over the whole row ---------------------------------------------
+      block_kth_largest(lg, V, k, sh);
+      const unsigned thr = sh.prefix;
+      const int krem = (int)sh.krem, ntie = (int)sh.ntie;
+      if (tid == 0) sh.cnt = 0;
+      __syncthreads();
+      // everything above the threshold, plus the threshold ties with the lowest indices
       for (int i = tid; i < V; i += SAMPLE_THREADS) {
         const unsigned key = f2key(lg[i]);
-        if ((key & mask_hi) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1u);
-      }
-      __syncthreads();
-      if (tid == 0) {
-        unsigned cum = 0u, krem = s_krem;
-        for (int b = 255; b >= 0; --b) {
-          if (cum + hist[b] >= krem) {
-            s_prefix = prefix | ((unsigned)b << shift);
-            s_krem = krem - cum;
-            s_ntie = hist[b];
-            break;
-          }
-          cum += hist[b];
+        if (key > thr || (key == thr && ntie == krem)) {
+          const int p = atomicAdd(&sh.cnt, 1);
+          if (p < MAX_CAND) { sh.cand_key[p] = key; sh.cand_idx[p] = i; }
         }
       }
       __syncthreads();
-    }
-    const unsigned thr = s_prefix;            // key of the k-th largest logit
-    const int krem = (int)s_krem;             // how many entries equal to it are kept
-    const int ntie = (int)s_ntie;
-    if (tid == 0) s_cnt = 0;
-    __syncthreads();
-    for (int i = tid; i < V; i += SAMPLE_THREADS) {
-      const unsigned key = f2key(lg[i]);
-      if (key > thr || (key == thr && ntie == krem)) {
-        const int p = atomicAdd(&s_cnt, 1);
-        if (p < MAX_TOPK) { cand_key[p] = key; cand_idx[p] = i; }
-      }
-    }
-    __syncthreads();
-    if (ntie != krem) {
-      // more ties at the threshold than places left: keep the lowest indices
-      int last = -1;
-      for (int t = 0; t < krem; ++t) {
-        int best = 0x7fffffff;
-        for (int i = tid; i < V; i += SAMPLE_THREADS)
-          if (i > last && f2key(lg[i]) == thr) { best = i; break; }
+      if (ntie != krem) {
+        int last = -1;
+        for (int t = 0; t < krem; ++t) {
+          int best = 0x7fffffff;
+          for (int i = tid; i < V; i += SAMPLE_THREADS)
+            if (i > last && f2key(lg[i]) == thr) { best = i; break; }
 #pragma unroll
-        for (int off = 32; off > 0; off >>= 1) { const int o = __shfl_xor(best, off, 64); best = o < best ? o : best; }
-        if (lane == 0) red_idx[wid] = best;
-        __syncthreads();
-        if (tid == 0) {
-          for (int x = 1; x < SAMPLE_THREADS / 64; ++x) best = red_idx[x] < best ? red_idx[x] : best;
-          const int p = s_cnt++;
-          if (p < MAX_TOPK) { cand_key[p] = thr; cand_idx[p] = best; }
-          red_idx[0] = best;
+          for (int off = 32; off > 0; off >>= 1) { const int o = __shfl_xor(best, off, 64); best = o < best ? o : best; }
+          if (lane == 0) sh.red_idx[wid] = best;
+          __syncthreads();
+          if (tid == 0) {
+            for (int x = 1; x < SAMPLE_THREADS / 64; ++x) best = sh.red_idx[x] < best ? sh.red_idx[x] : best;
+            const int p = sh.cnt++;
+            if (p < MAX_CAND) { sh.cand_key[p] = thr; sh.cand_idx[p] = best; }
+            sh.red_idx[0] = best;
+          }
+          __syncthreads();
+          last = sh.red_idx[0];
+          __syncthreads();
         }
-        __syncthreads();
-        last = red_idx[0];
-        __syncthreads();
       }
     }
-    const int n = s_cnt < MAX_TOPK ? s_cnt : MAX_TOPK;      // == k
-    if (tid < n) {
-      const unsigned mk = cand_key[tid]; const int mi = cand_idx[tid];
+    // ---- exact top-k of the candidates: the rank of a candidate is its place in the
+    // descending order (ties: lower index first) ------------------------------------------
+    const int n_cand = sh.cnt < MAX_CAND ? sh.cnt : MAX_CAND;
+    for (int c = tid; c < n_cand; c += SAMPLE_THREADS) {
+      const unsigned mk = sh.cand_key[c];
+      const int mi = sh.cand_idx[c];
       int rank = 0;
-      for (int j = 0; j < n; ++j) rank += (cand_key[j] > mk) || (cand_key[j] == mk && cand_idx[j] < mi);
-      sort_logit[rank] = lg[mi];
-      sort_idx[rank] = mi;
+      for (int j = 0; j < n_cand; ++j) rank += (sh.cand_key[j] > mk) || (sh.cand_key[j] == mk && sh.cand_idx[j] < mi);
+      if (rank < k) { sh.sort_logit[rank] = lg[mi]; sh.sort_idx[rank] = mi; }
     }
     __syncthreads();
     if (tid == 0) {
+      const int n = n_cand < k ? n_cand : k;
       const unsigned long long rid = (unsigned long long)req;
       const unsigned w0 = philox4x32_10_word0((unsigned)(rid & 0xFFFFFFFFull), (unsigned)(rid >> 32),
                                               (unsigned)g, 0u, (unsigned)(sc.seed & 0xFFFFFFFFull),
                                               (unsigned)(sc.seed >> 32));
       const double u = (double)(w0 >> 8) * (1.0 / 16777216.0);
       const double T = (double)sc.temperature;
-      const double z0 = (double)sort_logit[0] / T;
+      const double z0 = (double)sh.sort_logit[0] / T;
       double sum = 0.0;
-      for (int j = 0; j < n; ++j) sum += exp((double)sort_logit[j] / T - z0);
+      for (int j = 0; j < n; ++j) sum += exp((double)sh.sort_logit[j] / T - z0);
       double c = 0.0;
-      int choice = sort_idx[n - 1];
+      int choice = sh.sort_idx[n - 1];
       for (int j = 0; j < n; ++j) {
-        c += exp((double)sort_logit[j] / T - z0) / sum;
-        if (c > u) { choice = sort_idx[j]; break; }
+        c += exp((double)sh.sort_logit[j] / T - z0) / sum;
+        if (c > u) { choice = sh.sort_idx[j]; break; }
       }
-      s_choice = choice;
+      sh.choice = choice;
     }
     __syncthreads();
   }
 
-  const int sampled = s_choice;
+  const int sampled = sh.choice;
 
-  // ---- parity-mode capture ----------------------------------------------------
+  // ---- parity-mode capture --------------------------------------------------------------
   if (w.req != nullptr && ctrl != nullptr) {
     if (tid == 0) {
       int row = -1;
       const int nw = ctrl->n_watch;
       for (int i = 0; i < nw; ++i)
         if (w.req[i] == req && g >= w.first[i] && g < w.first[i] + w.count[i]) row = w.row0[i] + (g - w.first[i]);
-      s_watch_row = row;
+      sh.watch_row = row;
     }
     __syncthreads();
-    const int row = s_watch_row;
+    const int row = sh.watch_row;
     if (row >= 0) {
       for (int i = tid; i < V; i += SAMPLE_THREADS) w.logits[(size_t)row * V + i] = lg[i];
       if (tid == 0) { w.sampled[row] = sampled; w.filled[row] = 1; }
@@ -220,10 +293,28 @@ __global__ __launch_bounds__(SAMPLE_THREADS) void sample_kernel(RowCtx rc, Slots
   }
 }
 
+// Maxima of groups of `group` consecutive logits (what the LM-head GEMM epilogue leaves),
+// for callers that bring their own logits.
+__global__ __launch_bounds__(256) void group_max_kernel(const float* logits, int n_rows, int V, int group, float* out) {
+  const int n_groups = V / group;
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= (size_t)n_rows * n_groups) return;
+  const size_t r = i / n_groups, gi = i % n_groups;
+  const float* p = logits + r * V + gi * group;
+  float m = p[0];
+  for (int j = 1; j < group; ++j) m = fmaxf(m, p[j]);
+  out[i] = m;
+}
+void launch_group_max(hipStream_t st, const float* logits, int n_rows, int V, int group, float* out) {
+  const size_t n = (size_t)n_rows * (V / group);
+  hipLaunchKernelGGL(group_max_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, logits, n_rows, V, group, out);
+}
+
 void launch_sample(hipStream_t st, RowCtx rc, Slots s, Ctrl* ctrl, const float* logits, int vocab, SamplerCfg sc,
-                   Watch w, int update, const long long* req_ids, const int* gen_idx, int* out_tokens) {
+                   Watch w, int update, const long long* req_ids, const int* gen_idx, int* out_tokens,
+                   const float* group_max, int group) {
   hipLaunchKernelGGL(sample_kernel, dim3(rc.max_rows), dim3(SAMPLE_THREADS), 0, st, rc, s, ctrl, logits, vocab,
-                     sc, w, update, req_ids, gen_idx, out_tokens);
+                     sc, w, update, req_ids, gen_idx, out_tokens, group_max, group);
 }
 
 }  // namespace april

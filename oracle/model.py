@@ -64,12 +64,18 @@ def swiglu(h, w_gate, w_up, w_down):
     return (silu(h @ w_gate.T) * (h @ w_up.T)) @ w_down.T
 
 
-def moe_mlp(h, router, e_gate, e_up, e_down, top_k):
+def moe_mlp(h, router, e_gate, e_up, e_down, top_k, margins=None):
     """Routed mixture for ONE token h [d]: r = softmax over all experts of the
     router logits; the top_k largest r (ties: lower expert index) are kept and
-    renormalised to sum 1; output = sum of weight * expert SwiGLU."""
+    renormalised to sum 1; output = sum of weight * expert SwiGLU.
+    margins (optional list): receives the relative gap between the last kept and the
+    first dropped router probability (how robust the routing decision is)."""
     r = softmax(router @ h)
-    order = sorted(range(r.shape[0]), key=lambda e: (-r[e], e))[:top_k]
+    ranked = sorted(range(r.shape[0]), key=lambda e: (-r[e], e))
+    order = ranked[:top_k]
+    if margins is not None:
+        margins.append((r[ranked[top_k - 1]] - r[ranked[top_k]]) / r[ranked[top_k - 1]]
+                       if top_k < r.shape[0] else 1.0)
     z = sum(r[e] for e in order)
     out = np.zeros_like(h)
     for e in order:
@@ -103,6 +109,7 @@ class Decoder:
         vocab, n_experts, experts_per_tok, rope_theta, rms_eps.  weights: name -> array."""
         self.s = shape
         self.w = {k: np.asarray(v, dtype=F64) for k, v in weights.items()}
+        self.route_margins = None     # set to a list to collect (position, layer, margin) of routed layers
 
     def new_cache(self, capacity=0):
         s = self.s
@@ -142,8 +149,14 @@ class Decoder:
             x = x + o.reshape(T, -1) @ w[f"wo.{l}"].T
             h = rmsnorm(x, w[f"mlp_norm.{l}"], s.rms_eps)
             if s.n_experts > 0:
-                y = np.stack([moe_mlp(h[t], w[f"router.{l}"], w[f"e_gate.{l}"], w[f"e_up.{l}"],
-                                      w[f"e_down.{l}"], s.experts_per_tok) for t in range(T)])
+                ys = []
+                for t in range(T):
+                    mg = [] if self.route_margins is not None else None
+                    ys.append(moe_mlp(h[t], w[f"router.{l}"], w[f"e_gate.{l}"], w[f"e_up.{l}"],
+                                      w[f"e_down.{l}"], s.experts_per_tok, mg))
+                    if mg is not None:
+                        self.route_margins.append((int(pos[t]), l, float(mg[0])))
+                y = np.stack(ys)
             else:
                 y = swiglu(h, w[f"w_gate.{l}"], w[f"w_up.{l}"], w[f"w_down.{l}"])
             x = x + y

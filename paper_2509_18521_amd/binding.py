@@ -63,7 +63,7 @@ class april_step_result(C.Structure):
         ("n_resumes", C.POINTER(C.c_int32)), ("buffer", C.c_void_p), ("n_new_consumed", C.c_int32),
         ("decode_iters", C.c_int64), ("tokens_generated", C.c_int64), ("prefill_tokens", C.c_int64),
         ("reprefill_tokens", C.c_int64), ("sum_live", C.c_int64), ("sum_ctx", C.c_int64),
-        ("dec_sum_live", C.c_int64), ("dec_sum_ctx", C.c_int64),
+        ("dec_sum_live", C.c_int64), ("dec_sum_ctx", C.c_int64), ("dec_sum_experts", C.c_int64),
         ("t_prefill_s", C.c_double), ("t_decode_s", C.c_double), ("t_total_s", C.c_double),
     ]
 
@@ -82,7 +82,7 @@ class april_kernel_stat(C.Structure):
 class april_info(C.Structure):
     _fields_ = [(n, C.c_int64) for n in ("hbm_total", "hbm_free", "kv_pool_bytes", "kv_blocks_total",
                                          "kv_blocks_free", "weight_bytes", "decode_weight_bytes",
-                                         "kv_bytes_per_token")]
+                                         "kv_bytes_per_token", "expert_bytes")]
 
 
 _lib = None
@@ -181,6 +181,7 @@ class StepResult:
     sum_ctx: int
     dec_sum_live: int
     dec_sum_ctx: int
+    dec_sum_experts: int
     t_prefill_s: float
     t_decode_s: float
     t_total_s: float
@@ -210,7 +211,7 @@ def april_rollout_step(ctx, requests: Sequence[dict], n_target: int, n_overprovi
         toks.append(np.ctypeslib.as_array(res.tokens[i], shape=(nt,)).copy() if nt > 0 else np.zeros(0, np.int32))
         nres.append(int(res.n_resumes[i]))
     return StepResult(ids, toks, nres, C.c_void_p(res.buffer), res.n_new_consumed, res.decode_iters,
-                      res.tokens_generated, res.prefill_tokens, res.reprefill_tokens, res.sum_live, res.sum_ctx, res.dec_sum_live, res.dec_sum_ctx,
+                      res.tokens_generated, res.prefill_tokens, res.reprefill_tokens, res.sum_live, res.sum_ctx, res.dec_sum_live, res.dec_sum_ctx, res.dec_sum_experts,
                       res.t_prefill_s, res.t_decode_s, res.t_total_s)
 
 

@@ -33,6 +33,7 @@ struct Ctrl {
   long long sum_live;   // sum over iterations of n_rows
   long long sum_ctx;    // sum over (iteration, row) of context length
   long long iter_ctx;   // context-length sum of the current iteration alone
+  long long sum_experts;  // sum over (iteration, layer) of the experts that received a token
 };
 
 // Per-slot state, structure of arrays in device memory.

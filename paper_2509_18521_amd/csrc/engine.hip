@@ -27,15 +27,17 @@ double now_s() {
 
 enum KernelClass {
   KC_SCHED = 0, KC_EMBED, KC_NORM, KC_GEMM_QKV, KC_ROPE, KC_ATTN, KC_GEMM_O, KC_GEMM_GATEUP, KC_SILU,
-  KC_GEMM_DOWN, KC_GEMM_LMHEAD, KC_SAMPLE, KC_COUNT
+  KC_GEMM_DOWN, KC_GEMM_LMHEAD, KC_SAMPLE, KC_MOE_ROUTE, KC_MOE_GATEUP, KC_MOE_DOWN, KC_COUNT
 };
 const char* kKernelNames[KC_COUNT] = {"sched", "embed", "add_rmsnorm", "gemm_qkv", "rope_append", "attn_decode",
-                                      "gemm_o", "gemm_gateup", "silu_mul", "gemm_down", "gemm_lmhead", "sample"};
+                                      "gemm_o", "gemm_gateup", "silu_mul", "gemm_down", "gemm_lmhead", "sample",
+                                      "moe_route", "moe_gateup", "moe_down"};
 
 struct LayerW {
   float *attn_norm = nullptr, *mlp_norm = nullptr;
   void *wqkv = nullptr, *wo = nullptr, *wgu = nullptr, *wd = nullptr;            // plain [N][K]
   bf16_t *wqkv_s = nullptr, *wo_s = nullptr, *wg_s = nullptr, *wu_s = nullptr, *wd_s = nullptr;  // fragment-tiled
+  bf16_t *router_s = nullptr, *eg_s = nullptr, *eu_s = nullptr, *ed_s = nullptr;  // routed experts, [E*rows][K] tiled
 };
 
 struct SlotH {
@@ -124,6 +126,14 @@ struct april_ctx {
   float* attn_ws = nullptr;
   int* attn_counters = nullptr;
   int step_max_ctx = 0;        // bound on the context length of any row in the current pass
+  // routed experts
+  bool moe = false;
+  int n_experts = 0, top_k_experts = 0, d_expert = 0, s_router = 1, moe_p_cap = 0;
+  size_t router_stride = 0;
+  float *router_out = nullptr, *moe_wts = nullptr, *moe_out = nullptr;
+  int *moe_ids = nullptr, *moe_pos = nullptr, *moe_cnt = nullptr, *moe_base = nullptr, *moe_src = nullptr;
+  bf16_t* moe_act = nullptr;
+  int64_t expert_bytes = 0;    // bytes of one expert's three matrices
   // one decode iteration (scheduler + forward + sample) captured as a HIP graph, keyed by
   // the launch geometry (row bound, attention split bound)
   bool use_graph = true;
@@ -273,9 +283,13 @@ void forward(april_ctx* c, RowCtx rows, RowCtx srows, const int* gather, double 
     if (c->bf16) launch_embed<bf16_t>(st, rows, c->ds, (const bf16_t*)c->tok_emb, c->x_res, d);
     else launch_embed<float>(st, rows, c->ds, (const float*)c->tok_emb, c->x_res, d);
   }
-  auto norm = [&](RowCtx rc, int n_part, const float* gain, void* out, const int* gth, double rowsB) {
+  // mlp_in = true: the partials are the previous layer's MLP output (for routed experts: the
+  // top-k expert outputs of each row, gathered and weighted)
+  auto norm = [&](RowCtx rc, int n_part, const float* gain, void* out, const int* gth, double rowsB, bool mlp_in) {
     ProfScope p(c, KC_NORM, rowsB * d * (4.0 * (2 + (n_part > 0 ? 1 : 0)) + e), 0);
-    if (c->bf16) launch_add_rmsnorm<bf16_t, true>(st, rc, c->x_res, c->proj, n_part, c->proj_stride, gain, (bf16_t*)out, d, m.rms_eps, gth);
+    if (c->moe && mlp_in && n_part > 0)
+      launch_add_rmsnorm<bf16_t, true>(st, rc, c->x_res, c->moe_out, c->top_k_experts, 0, gain, (bf16_t*)out, d, m.rms_eps, gth, c->moe_pos, c->moe_wts);
+    else if (c->bf16) launch_add_rmsnorm<bf16_t, true>(st, rc, c->x_res, c->proj, n_part, c->proj_stride, gain, (bf16_t*)out, d, m.rms_eps, gth);
     else launch_add_rmsnorm<float, false>(st, rc, c->x_res, c->proj, n_part, c->proj_stride, gain, (float*)out, d, m.rms_eps, gth);
   };
   auto gemm = [&](int kc, RowCtx rc, const void* x, const void* w_plain, const bf16_t* w_s, float* out, int N, int K,
@@ -287,7 +301,7 @@ void forward(april_ctx* c, RowCtx rows, RowCtx srows, const int* gather, double 
   };
   for (int l = 0; l < m.n_layers; ++l) {
     const LayerW& L = c->layers[l];
-    norm(rows, l == 0 ? 0 : c->s_down, L.attn_norm, c->h_act, nullptr, B);
+    norm(rows, l == 0 ? 0 : c->s_down, L.attn_norm, c->h_act, nullptr, B, true);
     gemm(KC_GEMM_QKV, rows, c->h_act, L.wqkv, L.wqkv_s, c->qkv, nqkv, d, c->s_qkv, c->qkv_stride, B);
     {
       ProfScope p(c, KC_ROPE, B * (nqkv * 4.0 + nq * 4.0 + 2 * nkv * e), 0);
@@ -308,7 +322,24 @@ void forward(april_ctx* c, RowCtx rows, RowCtx srows, const int* gather, double 
       else launch_attn_ref<float, false>(st, rows, c->ds, c->q_rot, (const float*)c->kv_pool, c->kvl, l, Hq, (float*)c->attn_out);
     }
     gemm(KC_GEMM_O, rows, c->attn_out, L.wo, L.wo_s, c->proj, d, nq, c->s_o, c->proj_stride, B);
-    norm(rows, c->s_o, L.mlp_norm, c->h_act, nullptr, B);
+    norm(rows, c->s_o, L.mlp_norm, c->h_act, nullptr, B, false);
+    if (c->moe) {
+      const int E = c->n_experts, Fe = c->d_expert, tk = c->top_k_experts;
+      gemm(KC_MOE_ROUTE, rows, c->h_act, nullptr, L.router_s, c->router_out, E, d, c->s_router, c->router_stride, B);
+      launch_moe_route(st, rows, c->router_out, c->s_router, c->router_stride, E, tk, c->moe_ids, c->moe_wts);
+      launch_moe_dispatch(st, rows, c->moe_ids, E, tk, c->moe_cnt, c->moe_base, c->moe_pos, c->moe_src, c->moe_p_cap,
+                          rows.stop ? c->d_ctrl : nullptr);
+      const double hit = std::min<double>(E, B * tk);   // bookkeeping estimate: experts that receive a token
+      {
+        ProfScope p(c, KC_MOE_GATEUP, hit * 2.0 * Fe * d * e + B * tk * (d + Fe) * e, 4.0 * B * tk * Fe * d);
+        launch_moe_gateup(st, rows, c->moe_cnt, c->moe_base, c->moe_src, (const bf16_t*)c->h_act, L.eg_s, L.eu_s, c->moe_act, E, Fe, d);
+      }
+      {
+        ProfScope p(c, KC_MOE_DOWN, hit * 1.0 * Fe * d * e + B * tk * (Fe * e + d * 4.0), 2.0 * B * tk * Fe * d);
+        launch_moe_down(st, rows, c->moe_cnt, c->moe_base, c->moe_act, L.ed_s, c->moe_out, E, Fe, d);
+      }
+      continue;
+    }
     if (c->use_mfma) {
       ProfScope p(c, KC_GEMM_GATEUP, 2.0 * F * d * e + B * d * e + B * F * e, 4.0 * B * F * d);
       launch_gemm_mfma_swiglu(st, rows, (const bf16_t*)c->h_act, L.wg_s, L.wu_s, (bf16_t*)c->act, F, d);
@@ -321,7 +352,7 @@ void forward(april_ctx* c, RowCtx rows, RowCtx srows, const int* gather, double 
     gemm(KC_GEMM_DOWN, rows, c->act, L.wd, L.wd_s, c->proj, d, F, c->s_down, c->proj_stride, B);
   }
   const double SB = gather ? (double)srows.max_rows : B;
-  norm(srows, c->s_down, c->final_norm, c->hf, gather, SB);
+  norm(srows, c->s_down, c->final_norm, c->hf, gather, SB, true);
   {
     ProfScope p(c, KC_GEMM_LMHEAD, (double)V * d * e + SB * d * e, 2.0 * SB * V * d);
     if (c->use_mfma && c->group_max) launch_gemm_mfma_logits(st, srows, (const bf16_t*)c->hf, c->lm_head_s, c->logits, c->group_max, V, d);
@@ -377,9 +408,13 @@ int april_init(const april_model_cfg* cfg, const april_tensor* weights, int32_t 
   int ndev = 0;
   if (hipGetDeviceCount(&ndev) != hipSuccess || ndev <= 0) return fail(nullptr, APRIL_EDEVICE, "no HIP device");
   const april_model_cfg& g = *cfg;
-  if (g.n_experts != 0) return fail(nullptr, APRIL_EINVAL, "routed experts are not built yet");
+  const bool moe = g.n_experts != 0;
+  if (moe && (g.dtype != APRIL_DTYPE_BF16 || g.n_experts < 1 || g.n_experts > 256 || g.experts_per_tok < 1 ||
+              g.experts_per_tok > 8 || g.experts_per_tok > g.n_experts || g.d_expert_ffn <= 0 ||
+              g.d_expert_ffn % 32 || g.d_model % 64 || g.n_experts % 32))
+    return fail(nullptr, APRIL_EINVAL, "routed experts need bf16, 32 | n_experts <= 256, experts_per_tok <= 8, 32 | d_expert_ffn, 64 | d_model");
   if (g.kv_block_tokens != 16) return fail(nullptr, APRIL_EINVAL, "kv_block_tokens must be 16");
-  if (g.n_layers <= 0 || g.d_model <= 0 || g.n_q_heads <= 0 || g.n_kv_heads <= 0 || g.vocab <= 0 || g.d_ffn <= 0)
+  if (g.n_layers <= 0 || g.d_model <= 0 || g.n_q_heads <= 0 || g.n_kv_heads <= 0 || g.vocab <= 0 || (!moe && g.d_ffn <= 0))
     return fail(nullptr, APRIL_EINVAL, "non-positive model dimension");
   if (g.n_q_heads % g.n_kv_heads) return fail(nullptr, APRIL_EINVAL, "n_q_heads must be a multiple of n_kv_heads");
   if (g.n_q_heads / g.n_kv_heads > 16) return fail(nullptr, APRIL_EINVAL, "at most 16 query heads per KV head");
@@ -392,18 +427,21 @@ int april_init(const april_model_cfg* cfg, const april_tensor* weights, int32_t 
     return fail(nullptr, APRIL_EINVAL, "top_k must be in 1..64 and temperature > 0");
   const int nq = g.n_q_heads * g.head_dim, nkv = g.n_kv_heads * g.head_dim, nqkv = nq + 2 * nkv;
   const int d = g.d_model, F = g.d_ffn, V = g.vocab;
-  if (g.dtype == APRIL_DTYPE_BF16 && (d % 32 || F % 32 || V % 32 || nq % 32 || nqkv % 32))
+  if (g.dtype == APRIL_DTYPE_BF16 && (d % 32 || (!moe && F % 32) || V % 32 || nq % 32 || nqkv % 32))
     return fail(nullptr, APRIL_EINVAL, "bf16 path needs d_model, d_ffn, vocab, head widths multiple of 32");
 
   april_ctx* c = new april_ctx();
   c->cfg = g;
-  c->dm = ModelDims{g.n_layers, d, g.n_q_heads, g.n_kv_heads, g.head_dim, F, V, 0, 0, 0, g.rope_theta, g.rms_eps, 16};
+  c->dm = ModelDims{g.n_layers, d, g.n_q_heads, g.n_kv_heads, g.head_dim, F, V, g.n_experts, g.experts_per_tok,
+                    g.d_expert_ffn, g.rope_theta, g.rms_eps, 16};
+  c->moe = moe; c->n_experts = g.n_experts; c->top_k_experts = g.experts_per_tok; c->d_expert = g.d_expert_ffn;
   c->bf16 = g.dtype == APRIL_DTYPE_BF16;
   c->esz = c->bf16 ? 2 : 4;
   const char* gm = getenv("APRIL_GEMM");
   c->use_mfma = c->bf16 && !(gm && !strcmp(gm, "ref"));
   const char* am = getenv("APRIL_ATTN");
   c->attn_mfma = c->bf16 && !(am && !strcmp(am, "ref"));
+  if (moe && !(c->use_mfma && c->attn_mfma)) { delete c; return fail(nullptr, APRIL_EINVAL, "routed experts run on the MFMA path only"); }
   const char* gr = getenv("APRIL_GRAPH");
   c->use_graph = !(gr && !strcmp(gr, "0"));
   for (int i = 0; i < KC_COUNT; ++i) c->stats[i] = april_kernel_stat{kKernelNames[i], 0, 0, 0, 0};
@@ -417,6 +455,7 @@ int april_init(const april_model_cfg* cfg, const april_tensor* weights, int32_t 
   // ---- weights ------------------------------------------------------------------
   const size_t e = c->esz;
   size_t stage_bytes = std::max<size_t>((size_t)V * d, (size_t)2 * F * d) * e;
+  if (moe) stage_bytes = std::max<size_t>(stage_bytes, (size_t)g.n_experts * g.d_expert_ffn * d * e);
   void* stage = nullptr;
   if (c->use_mfma) HIPTRY(hipMalloc(&stage, stage_bytes));
   auto free_stage = [&]() { if (stage) { hipFree(stage); stage = nullptr; } };
@@ -460,6 +499,17 @@ int april_init(const april_model_cfg* cfg, const april_tensor* weights, int32_t 
       TRYW(dev_alloc(c, &L.wqkv_s, (size_t)nqkv * d, false));
       launch_shuffle_weights(c->stream, (const bf16_t*)qkv_dst, L.wqkv_s, nqkv, d);
       HIPTRY(hipStreamSynchronize(c->stream));
+    }
+    if (moe) {
+      const int E = g.n_experts, Fe = g.d_expert_ffn;
+      TRYW(load_matrix("wo" + sl, d, nq, nullptr, &L.wo_s));
+      TRYW(load_matrix("router" + sl, E, d, nullptr, &L.router_s));
+      TRYW(load_matrix("e_gate" + sl, E * Fe, d, nullptr, &L.eg_s));
+      TRYW(load_matrix("e_up" + sl, E * Fe, d, nullptr, &L.eu_s));
+      TRYW(load_matrix("e_down" + sl, E * d, Fe, nullptr, &L.ed_s));
+      c->decode_weight_bytes += ((int64_t)nqkv * d + (int64_t)d * nq + (int64_t)E * d) * e + 2 * d * 4;
+      c->weight_bytes += (int64_t)3 * E * Fe * d * e;
+      continue;
     }
     if (keep_plain) {
       TRYW(dev_alloc_bytes(c, &L.wo, (size_t)d * nq * e, false));
@@ -549,12 +599,24 @@ int april_init(const april_model_cfg* cfg, const april_tensor* weights, int32_t 
   TRY(dev_alloc(c, &c->q_rot, M * nq));
   TRY(dev_alloc(c, &c->proj, (size_t)std::max(c->s_o, c->s_down) * c->proj_stride));
   if (!c->use_mfma) TRY(dev_alloc(c, &c->gu, M * 2 * F));
+  if (moe) {
+    const int E = g.n_experts, Fe = g.d_expert_ffn, tk = g.experts_per_tok;
+    c->expert_bytes = (int64_t)3 * Fe * d * e;
+    c->s_router = pick_ksplit(E, d);
+    c->router_stride = M * E;
+    c->moe_p_cap = (int)((M * tk + (size_t)E * 31 + 31) / 32 * 32);
+    TRY(dev_alloc(c, &c->router_out, (size_t)c->s_router * c->router_stride));
+    TRY(dev_alloc(c, &c->moe_ids, M * tk)); TRY(dev_alloc(c, &c->moe_wts, M * tk)); TRY(dev_alloc(c, &c->moe_pos, M * tk));
+    TRY(dev_alloc(c, &c->moe_cnt, E)); TRY(dev_alloc(c, &c->moe_base, E + 1)); TRY(dev_alloc(c, &c->moe_src, c->moe_p_cap));
+    TRY(dev_alloc(c, &c->moe_act, (size_t)c->moe_p_cap * Fe));
+    TRY(dev_alloc(c, &c->moe_out, (size_t)c->moe_p_cap * d));
+  }
   const size_t SR = ((size_t)S + 31) / 32 * 32;
   TRY(dev_alloc(c, &c->logits, SR * V));
   if (c->use_mfma && V % lmhead_group_cols() == 0) TRY(dev_alloc(c, &c->group_max, SR * (V / lmhead_group_cols())));
   TRY(dev_alloc_bytes(c, &c->h_act, M * d * e));
   TRY(dev_alloc_bytes(c, &c->attn_out, M * nq * e));
-  TRY(dev_alloc_bytes(c, &c->act, M * F * e));
+  TRY(dev_alloc_bytes(c, &c->act, M * std::max(F, 1) * e));
   TRY(dev_alloc_bytes(c, &c->hf, SR * d * e));
   if (c->attn_mfma) {
     c->attn_chunk = attn_split_tokens();
@@ -613,6 +675,7 @@ int april_get_info(april_ctx* c, april_info* out) {
   out->kv_pool_bytes = c->kv_pool_bytes; out->kv_blocks_total = c->n_pages; out->kv_blocks_free = c->free_pages_host;
   out->weight_bytes = c->weight_bytes; out->decode_weight_bytes = c->decode_weight_bytes;
   out->kv_bytes_per_token = c->kv_bytes_per_token;
+  out->expert_bytes = c->expert_bytes;
   return APRIL_OK;
 }
 
@@ -941,14 +1004,14 @@ int april_rollout_step(april_ctx* c, const april_request* new_reqs, int32_t n_ne
 
   // ---- run ------------------------------------------------------------------------------
   double t_prefill = 0, t_decode = 0;
-  long long iters = 0, sum_live = 0, sum_ctx = 0, it1_live = 0, it1_ctx = 0;
+  long long iters = 0, sum_live = 0, sum_ctx = 0, it1_live = 0, it1_ctx = 0, sum_experts = 0, it1_experts = 0;
   std::vector<int> snap(7 * c->n_slots);
   if (D < N_target) {
     { int rc = upload_slot_tables(c); if (rc != APRIL_OK) return rc; }
     Ctrl& hc = *c->h_ctrl;
     hc.n_rows = 0; hc.finished = D; hc.n_target = N_target; hc.stop = 0; hc.iter = 0; hc.stop_iter = -1;
     hc.free_top = c->free_pages_host; hc.error = 0; hc.n_slots = c->n_slots; hc.eos_token = c->cfg.eos_token;
-    hc.n_watch = c->n_watch; hc.sum_live = 0; hc.sum_ctx = 0; hc.iter_ctx = 0;
+    hc.n_watch = c->n_watch; hc.sum_live = 0; hc.sum_ctx = 0; hc.iter_ctx = 0; hc.sum_experts = 0;
     HIPCHK(c, hipMemcpyAsync(c->d_ctrl, &hc, sizeof(Ctrl), hipMemcpyHostToDevice, st));
     HIPCHK(c, hipStreamSynchronize(st));
 
@@ -1011,7 +1074,7 @@ int april_rollout_step(april_ctx* c, const april_request* new_reqs, int32_t n_ne
     HIPCHK(c, hipMemcpyAsync(c->h_ctrl, c->d_ctrl, sizeof(Ctrl), hipMemcpyDeviceToHost, st));
     HIPCHK(c, hipStreamSynchronize(st));
     if (c->h_ctrl->error) return fail(c, APRIL_ENOMEM, "KV page stack underflow on device (prefill)");
-    it1_live = c->h_ctrl->sum_live; it1_ctx = c->h_ctrl->sum_ctx;
+    it1_live = c->h_ctrl->sum_live; it1_ctx = c->h_ctrl->sum_ctx; it1_experts = c->h_ctrl->sum_experts;
     t_prefill = now_s() - t0;
 
     // iterations 2..: pure decode
@@ -1077,7 +1140,7 @@ int april_rollout_step(april_ctx* c, const april_request* new_reqs, int32_t n_ne
     }
     t_decode = now_s() - t1;
     iters = c->h_ctrl->stop_iter;
-    sum_live = c->h_ctrl->sum_live; sum_ctx = c->h_ctrl->sum_ctx;
+    sum_live = c->h_ctrl->sum_live; sum_ctx = c->h_ctrl->sum_ctx; sum_experts = c->h_ctrl->sum_experts;
     if (exact && iters != T_bound) return fail(c, APRIL_EDEVICE, "device stopped at iteration %lld, host expected %d", iters, T_bound);
     prof_collect(c);
 
@@ -1180,6 +1243,7 @@ int april_rollout_step(april_ctx* c, const april_request* new_reqs, int32_t n_ne
   out->sum_ctx = sum_ctx;
   out->dec_sum_live = sum_live - it1_live;
   out->dec_sum_ctx = sum_ctx - it1_ctx;
+  out->dec_sum_experts = sum_experts - it1_experts;
   out->t_prefill_s = t_prefill;
   out->t_decode_s = t_decode;
   out->t_total_s = now_s() - t_begin;

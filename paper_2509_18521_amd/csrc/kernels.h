@@ -42,10 +42,23 @@ void launch_embed(hipStream_t st, RowCtx rc, Slots s, const T* emb, float* x_res
 
 // x_res += sum of partials (if any); h = rmsnorm(x_res) * gain.  gather (nullable):
 // input row index of output row r.
+// pos_of / wts (nullable, mixture-of-experts combine): partial p of row r is then the row
+// pos_of[r * n_partials + p] of `partials` ([packed rows][d]) weighted by wts[r * n_partials + p].
 template <typename T, bool XF>
 void launch_add_rmsnorm(hipStream_t st, RowCtx rc, float* x_res, const float* partials,
                         int n_partials, size_t partial_stride, const float* gain, T* h,
-                        int d, float eps, const int* gather);
+                        int d, float eps, const int* gather, const int* pos_of = nullptr,
+                        const float* wts = nullptr);
+
+// --- routed experts (bf16) ---------------------------------------------------------
+void launch_moe_route(hipStream_t st, RowCtx rc, const float* logits, int n_partials, size_t partial_stride,
+                      int E, int top_k, int* ids, float* wts);
+void launch_moe_dispatch(hipStream_t st, RowCtx rc, const int* ids, int E, int top_k, int* cnt, int* base,
+                         int* pos_of, int* src_row, int p_cap, Ctrl* ctrl);
+void launch_moe_gateup(hipStream_t st, RowCtx rc, const int* cnt, const int* base, const int* src_row,
+                       const bf16_t* h, const bf16_t* Wg, const bf16_t* Wu, bf16_t* act, int E, int Fe, int d);
+void launch_moe_down(hipStream_t st, RowCtx rc, const int* cnt, const int* base, const bf16_t* act,
+                     const bf16_t* Wd, float* out, int E, int Fe, int d);
 
 template <typename T>
 void launch_rope_append(hipStream_t st, RowCtx rc, Slots s, const float* qkv, int n_partials,

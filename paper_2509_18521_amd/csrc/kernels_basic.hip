@@ -212,7 +212,8 @@ template <typename T, bool XF, int NP>
 __global__ __launch_bounds__(256) void add_rmsnorm_kernel(RowCtx rc, float* x_res, const float* partials,
                                                           int n_partials_rt, size_t partial_stride,
                                                           const float* gain, T* h, int d, float eps,
-                                                          const int* gather) {
+                                                          const int* gather, const int* pos_of,
+                                                          const float* wts) {
   const int r = blockIdx.x;
   ROW_GUARD(rc, r);
   const int rin = gather ? gather[r] : r;
@@ -230,14 +231,17 @@ __global__ __launch_bounds__(256) void add_rmsnorm_kernel(RowCtx rc, float* x_re
       f32x4 xv[2] = {*reinterpret_cast<const f32x4*>(xp), *reinterpret_cast<const f32x4*>(xp + 4)};
       if (NP >= 0) {
         f32x4 pv[NP > 0 ? NP : 1][2];
+        float pw[NP > 0 ? NP : 1];
 #pragma unroll
         for (int p = 0; p < NP; ++p) {
-          const float* pp = partials + p * partial_stride + (size_t)rin * d + ch * 8;
+          const float* pp = pos_of ? partials + (size_t)pos_of[(size_t)rin * NP + p] * d + ch * 8
+                                   : partials + p * partial_stride + (size_t)rin * d + ch * 8;
+          pw[p] = wts ? wts[(size_t)rin * NP + p] : 1.0f;
           pv[p][0] = *reinterpret_cast<const f32x4*>(pp);
           pv[p][1] = *reinterpret_cast<const f32x4*>(pp + 4);
         }
 #pragma unroll
-        for (int p = 0; p < NP; ++p) { xv[0] += pv[p][0]; xv[1] += pv[p][1]; }
+        for (int p = 0; p < NP; ++p) { xv[0] += pv[p][0] * pw[p]; xv[1] += pv[p][1] * pw[p]; }
       } else {
         for (int p = 0; p < n_partials; ++p) {
           const float* pp = partials + p * partial_stride + (size_t)rin * d + ch * 8;
@@ -272,10 +276,11 @@ __global__ __launch_bounds__(256) void add_rmsnorm_kernel(RowCtx rc, float* x_re
 }
 template <typename T, bool XF>
 void launch_add_rmsnorm(hipStream_t st, RowCtx rc, float* x_res, const float* partials, int n_partials,
-                        size_t partial_stride, const float* gain, T* h, int d, float eps, const int* gather) {
+                        size_t partial_stride, const float* gain, T* h, int d, float eps, const int* gather,
+                        const int* pos_of, const float* wts) {
 #define ARN_CASE(NP)                                                                                          \
   hipLaunchKernelGGL((add_rmsnorm_kernel<T, XF, NP>), dim3(rc.max_rows), dim3(256), 0, st, rc, x_res, partials, \
-                     n_partials, partial_stride, gain, h, d, eps, gather)
+                     n_partials, partial_stride, gain, h, d, eps, gather, pos_of, wts)
   switch (n_partials) {
     case 0: ARN_CASE(0); break;
     case 1: ARN_CASE(1); break;
@@ -290,8 +295,8 @@ void launch_add_rmsnorm(hipStream_t st, RowCtx rc, float* x_res, const float* pa
   }
 #undef ARN_CASE
 }
-template void launch_add_rmsnorm<float, false>(hipStream_t, RowCtx, float*, const float*, int, size_t, const float*, float*, int, float, const int*);
-template void launch_add_rmsnorm<bf16_t, true>(hipStream_t, RowCtx, float*, const float*, int, size_t, const float*, bf16_t*, int, float, const int*);
+template void launch_add_rmsnorm<float, false>(hipStream_t, RowCtx, float*, const float*, int, size_t, const float*, float*, int, float, const int*, const int*, const float*);
+template void launch_add_rmsnorm<bf16_t, true>(hipStream_t, RowCtx, float*, const float*, int, size_t, const float*, bf16_t*, int, float, const int*, const int*, const float*);
 
 // ---------------------------------------------------------------------------
 // Rotary tables, computed once in double precision: cos/sin[pos][i], i < head_dim/2,

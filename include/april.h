@@ -116,6 +116,7 @@ typedef struct {
   int64_t  tokens_generated;      /* over all in-flight rollouts, partial ones included    */
   int64_t  prefill_tokens;        /* prompt tokens of newly admitted rollouts              */
   int64_t  reprefill_tokens;      /* tokens recomputed for rollouts resumed without KV     */
+  int64_t  n_preempted;           /* rollouts preempted in this step (KV pool exhausted)   */
   int64_t  sum_live;              /* sum over decode-path iterations of the live batch     */
   int64_t  sum_ctx;               /* sum over decode-path (iteration, seq) of context len  */
   int64_t  dec_sum_live, dec_sum_ctx;  /* the same sums over iterations 2.. only: the ones
@@ -149,6 +150,12 @@ int april_init(const april_model_cfg* cfg, const april_tensor* weights, int32_t 
  * iterations - one token per live rollout per iteration - until N_target rollouts
  * are complete, then returns exactly N_target of them and a buffer with the rest.
  * N_overprovision == N_target is the wait-for-all baseline.
+ * KV pool exhausted: a rollout that needs prefill is admitted only while the pages of its
+ * tokens fit (the first that does not fit closes admission for the step); before an
+ * iteration, if the rollouts that open a new page need more pages than are free, the
+ * youngest decoding rollout (largest request id) is preempted - pages freed, tokens kept,
+ * no progress this step, re-prefilled when resumed; if nothing is left in flight the step
+ * returns fewer than N_target (n_completed says how many).
  * new_reqs: host array [n_new_avail]; out: host struct filled by the call. */
 int april_rollout_step(april_ctx* ctx, const april_request* new_reqs, int32_t n_new_avail,
                        int32_t N_target, int32_t N_overprovision, int32_t max_new,

@@ -50,13 +50,22 @@ class OracleRollouts:
         return Rollout(request_id=request_id, prompt_len=len(prompt), forced_len=forced_len,
                        user={"prompt": np.asarray(prompt), "cache": None})
 
-    def drop_kv(self):
+    def drop_kv(self, pool=None):
         for r in self.buffer:
             r.user["cache"] = None
+            if pool is not None:
+                pool.free += r.pages
+            r.pages = 0
+            r.kv = 0
 
-    def step(self, new_rollouts, n_target, n_overprovision, max_new):
+    @staticmethod
+    def _forget_cache(r):
+        r.user["cache"] = None
+
+    def step(self, new_rollouts, n_target, n_overprovision, max_new, pool=None):
         out = rollout_step(self.buffer, new_rollouts, n_target, n_overprovision, max_new,
-                           next_token=self._next_token, eos_token=self.eos_token)
+                           next_token=self._next_token, eos_token=self.eos_token, pool=pool,
+                           on_preempt=self._forget_cache)
         self.buffer = out.buffer
         for r in out.completed:
             r.user["cache"] = None                    # finished: its KV is released

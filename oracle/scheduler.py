@@ -20,12 +20,15 @@ Readings where the paper is silent (each listed in the build's design notes):
   - exactly N rollouts are returned per step, lowest request id first among
     those that are complete; rollouts completing in the same iteration beyond
     N stay in the buffer flagged done and are returned first at the next step;
-  - buffered rollouts are resumed in ascending request id.
+  - buffered rollouts are resumed in ascending request id;
+  - an exhausted KV pool (optional PagePool): see rollout_step.
 
 Pins (tests/test_oracle_scheduler.py): an order-statistics closed form derived
 independently, the method's invariants (exactly N returned, nothing discarded,
-N' = N never buffers, buffer size N' - N), and the paper's worked sizes
-(N = 256, N' = 512 leaves 256 carried, Section 3.1).
+N' = N never buffers, buffer size N' - N), the paper's worked sizes
+(N = 256, N' = 512 leaves 256 carried, Section 3.1); for the page pool: an ample
+pool changes nothing, pages are conserved, only the youngest are preempted, and
+a brute-force replay of the page demand.
 """
 from dataclasses import dataclass, field
 from typing import Callable, List, Optional
@@ -42,6 +45,22 @@ class Rollout:
     done: bool = False
     tokens: List[int] = field(default_factory=list)
     user: object = None            # opaque per-rollout state of the sampler (e.g. a KV cache)
+    kv: int = 0                    # positions whose K/V are cached (0: token-level only)
+    pages: int = 0                 # KV pages held (only tracked with a PagePool)
+
+
+@dataclass
+class PagePool:
+    """KV page accounting (integers only).  A rollout with K/V for c positions holds
+    ceil(c / page_tokens) pages; completed rollouts give their pages back at the END of
+    the step in which they complete."""
+    total: int
+    page_tokens: int = 16
+    free: int = -1
+
+    def __post_init__(self):
+        if self.free < 0:
+            self.free = self.total
 
 
 @dataclass
@@ -52,44 +71,120 @@ class StepOutcome:
     tokens_generated: int
     n_new_consumed: int
     live_per_iter: List[int]
+    preempted: List[int] = field(default_factory=list)   # request ids preempted in this step, in order
+
+
+def _pages(n_tokens, page_tokens):
+    return -(-n_tokens // page_tokens)
 
 
 def rollout_step(buffer: List[Rollout], new_requests: List[Rollout], n_target: int,
                  n_overprovision: int, max_new: int,
                  next_token: Optional[Callable[[Rollout], int]] = None,
-                 eos_token: int = -1) -> StepOutcome:
+                 eos_token: int = -1, pool: Optional[PagePool] = None,
+                 on_preempt: Optional[Callable[[Rollout], None]] = None) -> StepOutcome:
     """Run one step.  `buffer` is the previous step's buffer (may be empty);
     `new_requests` are admitted in order as needed.  `next_token(r)` produces the
-    next token of rollout r (None: token value 0, scheduling only)."""
+    next token of rollout r (None: token value 0, scheduling only).
+
+    With a PagePool (the build's reading for an exhausted KV pool, integers only):
+      * a rollout that needs prefill (new, or resumed without K/V) is admitted only
+        if the pages of its tokens fit; the first one that does not fit closes
+        admission for the step (it stays buffered / unconsumed);
+      * before an iteration, the in-flight rollouts that decode and whose next position
+        opens a page each need one page; while they need more than are free, the
+        youngest decoding rollout (largest request id) is preempted: its pages are
+        freed, it keeps its tokens, stops progressing this step and is re-prefilled
+        when resumed;
+      * if nothing is left in flight before N rollouts are complete, the step ends
+        with fewer than N."""
     resumed = sorted(buffer, key=lambda r: r.request_id)
     deliver = [r for r in resumed if r.done]
-    inflight = [r for r in resumed if not r.done]
-    for r in inflight:
+    inflight: List[Rollout] = []
+    stay: List[Rollout] = []
+    prefill_ids = set()
+    admission_open = True
+    for r in resumed:
+        if r.done:
+            continue
+        if pool is not None and r.kv == 0:
+            need = _pages(r.prompt_len + r.gen, pool.page_tokens)
+            if admission_open and need <= pool.free:
+                pool.free -= need
+                r.pages = need
+            else:
+                admission_open = False
+                stay.append(r)
+                continue
+        if r.kv == 0:
+            prefill_ids.add(r.request_id)
         r.n_resumes += 1
+        inflight.append(r)
     consumed = 0
-    while len(inflight) < n_overprovision - len(deliver) and consumed < len(new_requests):
+    while (len(inflight) < n_overprovision - len(deliver) and consumed < len(new_requests)
+           and admission_open):
         r = new_requests[consumed]
+        if pool is not None:
+            need = _pages(r.prompt_len, pool.page_tokens)
+            if need > pool.free:
+                admission_open = False
+                break
+            pool.free -= need
+            r.pages = need
         consumed += 1
         r.limit = min(r.forced_len, max_new) if r.forced_len > 0 else max_new
+        r.kv = 0
+        prefill_ids.add(r.request_id)
         inflight.append(r)
-    if len(deliver) + len(inflight) < n_target:
+    if pool is None and len(deliver) + len(inflight) < n_target:
         raise RuntimeError("starved: fewer than N rollouts can ever complete")
     iters = 0
     generated = 0
     live_hist = []
+    preempted: List[Rollout] = []
+    finished_now: List[Rollout] = []
     while len(deliver) < n_target:
+        if pool is not None:
+            decoders = [r for r in inflight if r.request_id not in prefill_ids]
+            need = [r for r in decoders if r.kv % pool.page_tokens == 0 and r.kv // pool.page_tokens >= r.pages]
+            while len(need) > pool.free:
+                victim = max(decoders, key=lambda r: r.request_id)
+                decoders.remove(victim)
+                inflight.remove(victim)
+                if victim in need:
+                    need.remove(victim)
+                pool.free += victim.pages
+                victim.pages = 0
+                victim.kv = 0
+                if on_preempt is not None:
+                    on_preempt(victim)
+                preempted.append(victim)
+            for r in need:
+                pool.free -= 1
+                r.pages += 1
+        if not inflight:
+            break
         iters += 1
         live_hist.append(len(inflight))
         for r in inflight:
             tok = next_token(r) if next_token is not None else 0
             r.tokens.append(int(tok))
             r.gen += 1
+            r.kv = r.prompt_len + r.gen - 1
             generated += 1
             if r.gen >= r.limit or (eos_token >= 0 and tok == eos_token):
                 r.done = True
+        prefill_ids.clear()
         newly = sorted((r for r in inflight if r.done), key=lambda r: r.request_id)
         inflight = [r for r in inflight if not r.done]
         deliver.extend(newly)
+        finished_now.extend(newly)
+    if pool is not None:
+        for r in finished_now:                         # pages of completed rollouts: back at step end
+            pool.free += r.pages
+            r.pages = 0
+            r.kv = 0
     completed = deliver[:n_target]
-    new_buffer = sorted(deliver[n_target:] + inflight, key=lambda r: r.request_id)
-    return StepOutcome(completed, new_buffer, iters, generated, consumed, live_hist)
+    new_buffer = sorted(deliver[n_target:] + inflight + preempted + stay, key=lambda r: r.request_id)
+    return StepOutcome(completed, new_buffer, iters, generated, consumed, live_hist,
+                       [r.request_id for r in preempted])

@@ -62,7 +62,7 @@ class april_step_result(C.Structure):
         ("tokens", C.POINTER(C.POINTER(C.c_int32))), ("n_tokens", C.POINTER(C.c_int32)),
         ("n_resumes", C.POINTER(C.c_int32)), ("buffer", C.c_void_p), ("n_new_consumed", C.c_int32),
         ("decode_iters", C.c_int64), ("tokens_generated", C.c_int64), ("prefill_tokens", C.c_int64),
-        ("reprefill_tokens", C.c_int64), ("sum_live", C.c_int64), ("sum_ctx", C.c_int64),
+        ("reprefill_tokens", C.c_int64), ("n_preempted", C.c_int64), ("sum_live", C.c_int64), ("sum_ctx", C.c_int64),
         ("dec_sum_live", C.c_int64), ("dec_sum_ctx", C.c_int64), ("dec_sum_experts", C.c_int64),
         ("t_prefill_s", C.c_double), ("t_decode_s", C.c_double), ("t_total_s", C.c_double),
     ]
@@ -177,6 +177,7 @@ class StepResult:
     tokens_generated: int
     prefill_tokens: int
     reprefill_tokens: int
+    n_preempted: int
     sum_live: int
     sum_ctx: int
     dec_sum_live: int
@@ -211,7 +212,7 @@ def april_rollout_step(ctx, requests: Sequence[dict], n_target: int, n_overprovi
         toks.append(np.ctypeslib.as_array(res.tokens[i], shape=(nt,)).copy() if nt > 0 else np.zeros(0, np.int32))
         nres.append(int(res.n_resumes[i]))
     return StepResult(ids, toks, nres, C.c_void_p(res.buffer), res.n_new_consumed, res.decode_iters,
-                      res.tokens_generated, res.prefill_tokens, res.reprefill_tokens, res.sum_live, res.sum_ctx, res.dec_sum_live, res.dec_sum_ctx, res.dec_sum_experts,
+                      res.tokens_generated, res.prefill_tokens, res.reprefill_tokens, res.n_preempted, res.sum_live, res.sum_ctx, res.dec_sum_live, res.dec_sum_ctx, res.dec_sum_experts,
                       res.t_prefill_s, res.t_decode_s, res.t_total_s)
 
 

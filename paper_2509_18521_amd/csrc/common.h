@@ -13,7 +13,7 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 // Sequence slot states.
-enum : int { SLOT_FREE = 0, SLOT_LIVE = 1, SLOT_DONE = 2, SLOT_PARKED = 3, SLOT_PREFILL = 4 };
+enum : int { SLOT_FREE = 0, SLOT_LIVE = 1, SLOT_DONE = 2, SLOT_PARKED = 3, SLOT_PREFILL = 4, SLOT_PREEMPTED = 5 };
 
 // Device-resident control block of the early-termination scheduler (Section 2.2:
 // "stop generation once N rollouts are completed" is decided here, on device).
@@ -29,7 +29,9 @@ struct Ctrl {
   int n_slots;
   int eos_token;
   int n_watch;
-  int pad0;
+  int inflight;     // rollouts in flight at the start of the step (bound on the page demand of an iteration)
+  int n_preempted;  // rollouts preempted in this step because the KV pool ran out
+  int pad1;
   long long sum_live;   // sum over iterations of n_rows
   long long sum_ctx;    // sum over (iteration, row) of context length
   long long iter_ctx;   // context-length sum of the current iteration alone

@@ -904,27 +904,39 @@ int april_rollout_step(april_ctx* c, const april_request* new_reqs, int32_t n_ne
   const int blk = 16;
 
   // ---- admission plan (nothing is modified until every check has passed) -------------
+  // Resumed rollouts first (ascending id): KV-resident ones are in flight as they are; a
+  // rollout that needs prefill (resumed without KV, or new) is admitted only while the pages of
+  // its tokens fit in the free pool - the first that does not fit closes admission for the step.
   std::vector<Entry>& pend = c->pending;
   std::sort(pend.begin(), pend.end(), [](const Entry& a, const Entry& b) { return a.req < b.req; });
-  std::vector<int> deliver_idx, resume_idx;          // indices into pend
-  for (int i = 0; i < (int)pend.size(); ++i) (pend[i].done ? deliver_idx : resume_idx).push_back(i);
+  std::vector<int> deliver_idx, resume_idx, stay_idx;          // indices into pend
+  int64_t pages_left = c->free_pages_host;
+  bool admission_open = true;
+  for (int i = 0; i < (int)pend.size(); ++i) {
+    const Entry& e = pend[i];
+    if (e.done) { deliver_idx.push_back(i); continue; }
+    const bool resident = e.slot >= 0 && c->slots[e.slot].kv_len > 0;
+    if (!resident) {
+      const int ntok = e.slot >= 0 ? c->slots[e.slot].prompt_len + c->slots[e.slot].gen
+                                   : (int)(e.prompt.size() + e.generated.size());
+      const int need = ceil_div(ntok, blk);
+      if (admission_open && need <= pages_left) pages_left -= need;
+      else { admission_open = false; stay_idx.push_back(i); continue; }
+    }
+    resume_idx.push_back(i);
+  }
   const int D = (int)deliver_idx.size();
   int n_inflight = (int)resume_idx.size();
-  int n_admit = 0;
-  while (n_inflight + n_admit < N_over - D && n_admit < n_new_avail) ++n_admit;
-  n_inflight += n_admit;
-  if (D + n_inflight < N_target)
-    return fail(c, APRIL_ESTARVED, "only %d rollouts available, %d needed", D + n_inflight, N_target);
-  int slots_needed = n_admit;
-  for (int i : resume_idx) if (pend[i].slot < 0) ++slots_needed;
-  int slots_free = 0;
-  for (auto& s : c->slots) if (s.state == SLOT_FREE) ++slots_free;
-  if (slots_needed > slots_free) return fail(c, APRIL_ENOMEM, "%d sequence slots needed, %d free (max_inflight)", slots_needed, slots_free);
-  for (int i = 0; i < n_admit; ++i) {
+  int n_admit = 0, n_avail_for_n = 0;
+  while (n_inflight + n_avail_for_n < N_over - D && n_avail_for_n < n_new_avail) ++n_avail_for_n;
+  if (D + (int)stay_idx.size() + n_inflight + n_avail_for_n < N_target)
+    return fail(c, APRIL_ESTARVED, "only %d rollouts available, %d needed", D + (int)stay_idx.size() + n_inflight + n_avail_for_n, N_target);
+  for (int i = 0; i < n_avail_for_n; ++i) {
     const april_request& r = new_reqs[i];
     if (r.n_tokens <= 0 || !r.tokens) return fail(c, APRIL_EINVAL, "request %d: empty prompt", i);
     const int lim = r.forced_len > 0 ? std::min(r.forced_len, max_new) : max_new;
     if (r.n_tokens + lim > c->max_ctx) return fail(c, APRIL_EINVAL, "request %d: prompt %d + limit %d exceeds max_ctx %d", i, r.n_tokens, lim, c->max_ctx);
+    if (ceil_div(r.n_tokens + lim, blk) > c->n_pages) return fail(c, APRIL_ENOMEM, "request %d: the KV pool (%d pages) cannot hold even this one rollout", i, c->n_pages);
     for (int k = 0; k < r.n_tokens; ++k)
       if (r.tokens[k] < 0 || r.tokens[k] >= c->dm.vocab) return fail(c, APRIL_EINVAL, "request %d: token out of range", i);
     if (r.forced_tokens && !c->cfg.debug_logits) return fail(c, APRIL_EINVAL, "forced_tokens need a debug_logits context");
@@ -932,7 +944,21 @@ int april_rollout_step(april_ctx* c, const april_request* new_reqs, int32_t n_ne
       for (int k = 0; k < r.n_forced_tokens; ++k)
         if (r.forced_tokens[k] < 0 || r.forced_tokens[k] >= c->dm.vocab) return fail(c, APRIL_EINVAL, "request %d: forced token out of range", i);
   }
-  // worst-case page demand of the step (no preemption: refuse up front)
+  while (n_admit < n_avail_for_n && admission_open) {
+    const int need = ceil_div(new_reqs[n_admit].n_tokens, blk);
+    if (need > pages_left) { admission_open = false; break; }
+    pages_left -= need;
+    ++n_admit;
+  }
+  n_inflight += n_admit;
+  int slots_needed = n_admit;
+  for (int i : resume_idx) if (pend[i].slot < 0) ++slots_needed;
+  int slots_free = 0;
+  for (auto& s : c->slots) if (s.state == SLOT_FREE) ++slots_free;
+  if (slots_needed > slots_free) return fail(c, APRIL_ENOMEM, "%d sequence slots needed, %d free (max_inflight)", slots_needed, slots_free);
+  // does the worst case (every rollout runs to its limit) fit?  If it does, no rollout can be
+  // preempted and the iteration count of the step is known in advance.
+  bool pool_ample = true;
   {
     long long need = 0;
     for (int i : resume_idx) {
@@ -946,8 +972,7 @@ int april_rollout_step(april_ctx* c, const april_request* new_reqs, int32_t n_ne
       const int lim = r.forced_len > 0 ? std::min(r.forced_len, max_new) : max_new;
       need += ceil_div(r.n_tokens + lim, blk);
     }
-    if (need > c->free_pages_host)
-      return fail(c, APRIL_ENOMEM, "KV pool: step may need %lld pages, %d free", need, c->free_pages_host);
+    pool_ample = need <= c->free_pages_host;
   }
 
   // ---- commit admission ---------------------------------------------------------------
@@ -957,6 +982,8 @@ int april_rollout_step(april_ctx* c, const april_request* new_reqs, int32_t n_ne
   std::vector<Entry> deliver;           // surplus-complete from the last step, ascending id
   int64_t prefill_tokens = 0, reprefill_tokens = 0;
   int n_resident = 0;
+  std::vector<Entry> stay;              // buffered rollouts that could not be admitted (KV pool)
+  for (int i : stay_idx) stay.push_back(pend[i]);
   for (int i : deliver_idx) deliver.push_back(pend[i]);
   for (int i : resume_idx) {
     Entry& e = pend[i];
@@ -1004,6 +1031,7 @@ int april_rollout_step(april_ctx* c, const april_request* new_reqs, int32_t n_ne
 
   // ---- run ------------------------------------------------------------------------------
   double t_prefill = 0, t_decode = 0;
+  int n_preempted = 0;
   long long iters = 0, sum_live = 0, sum_ctx = 0, it1_live = 0, it1_ctx = 0, sum_experts = 0, it1_experts = 0;
   std::vector<int> snap(7 * c->n_slots);
   if (D < N_target) {
@@ -1011,7 +1039,7 @@ int april_rollout_step(april_ctx* c, const april_request* new_reqs, int32_t n_ne
     Ctrl& hc = *c->h_ctrl;
     hc.n_rows = 0; hc.finished = D; hc.n_target = N_target; hc.stop = 0; hc.iter = 0; hc.stop_iter = -1;
     hc.free_top = c->free_pages_host; hc.error = 0; hc.n_slots = c->n_slots; hc.eos_token = c->cfg.eos_token;
-    hc.n_watch = c->n_watch; hc.sum_live = 0; hc.sum_ctx = 0; hc.iter_ctx = 0; hc.sum_experts = 0;
+    hc.n_watch = c->n_watch; hc.inflight = (int)inflight.size(); hc.n_preempted = 0; hc.sum_live = 0; hc.sum_ctx = 0; hc.iter_ctx = 0; hc.sum_experts = 0;
     HIPCHK(c, hipMemcpyAsync(c->d_ctrl, &hc, sizeof(Ctrl), hipMemcpyHostToDevice, st));
     HIPCHK(c, hipStreamSynchronize(st));
 
@@ -1021,14 +1049,28 @@ int april_rollout_step(april_ctx* c, const april_request* new_reqs, int32_t n_ne
     std::vector<int> rem;
     for (int s : inflight) rem.push_back(c->slots[s].limit - c->slots[s].gen);
     std::sort(rem.begin(), rem.end());
-    const int T_bound = rem[N_target - D - 1];
-    const bool exact = c->cfg.eos_token < 0;
+    const bool exact = c->cfg.eos_token < 0 && pool_ample && (int)rem.size() >= N_target - D;
+    const int T_bound = exact ? rem[N_target - D - 1] : (rem.empty() ? 0 : rem.back());
 
     int decode_max_ctx = 1;
     for (int s : inflight) decode_max_ctx = std::max(decode_max_ctx, c->slots[s].prompt_len + c->slots[s].limit);
     c->step_max_ctx = decode_max_ctx;
     RowCtx drc{c->d_row_slot, c->d_row_pos, &c->d_ctrl->n_rows, &c->d_ctrl->stop, 0};
     const double t0 = now_s();
+    // pages of every rollout that is (re-)prefilled this step, in admission order, before
+    // the first scheduler pass hands out decode pages
+    if (!prefill_slots.empty()) {
+      int* h_list = c->h_stage; int* h_need = c->h_stage + c->n_slots;
+      for (size_t i = 0; i < prefill_slots.size(); ++i) {
+        const SlotH& sh = c->slots[prefill_slots[i]];
+        h_list[i] = prefill_slots[i];
+        h_need[i] = ceil_div(sh.prompt_len + sh.gen, blk);
+      }
+      HIPCHK(c, hipMemcpyAsync(c->d_list_a, h_list, prefill_slots.size() * sizeof(int), hipMemcpyHostToDevice, st));
+      HIPCHK(c, hipMemcpyAsync(c->d_list_b, h_need, prefill_slots.size() * sizeof(int), hipMemcpyHostToDevice, st));
+      launch_alloc_prefill(st, c->d_ctrl, c->ds, c->d_list_a, c->d_list_b, (int)prefill_slots.size(), c->d_free_stack);
+      HIPCHK(c, hipStreamSynchronize(st));
+    }
     // iteration 1: resident rollouts decode, the others are (re-)prefilled
     launch_sched(st, c->d_ctrl, c->ds, c->d_row_slot, c->d_row_pos, c->d_free_stack, blk, 0);
     if (n_resident > 0) {
@@ -1061,11 +1103,8 @@ int april_rollout_step(april_ctx* c, const april_request* new_reqs, int32_t n_ne
       HIPCHK(c, hipMemcpyAsync(c->d_pf_srow_slot, h_ss, nseq * sizeof(int), hipMemcpyHostToDevice, st));
       HIPCHK(c, hipMemcpyAsync(c->d_pf_srow_pos, h_sp, nseq * sizeof(int), hipMemcpyHostToDevice, st));
       HIPCHK(c, hipMemcpyAsync(c->d_pf_gather, h_g, nseq * sizeof(int), hipMemcpyHostToDevice, st));
-      HIPCHK(c, hipMemcpyAsync(c->d_list_a, h_list, nseq * sizeof(int), hipMemcpyHostToDevice, st));
-      HIPCHK(c, hipMemcpyAsync(c->d_list_b, h_need, nseq * sizeof(int), hipMemcpyHostToDevice, st));
       HIPCHK(c, hipMemcpyAsync(c->d_pf_nrows, h_n, sizeof(int), hipMemcpyHostToDevice, st));
       HIPCHK(c, hipMemcpyAsync(c->d_pf_nsrows, h_n + 1, sizeof(int), hipMemcpyHostToDevice, st));
-      launch_alloc_prefill(st, c->d_ctrl, c->ds, c->d_list_a, c->d_list_b, nseq, c->d_free_stack);
       RowCtx prc{c->d_pf_row_slot, c->d_pf_row_pos, c->d_pf_nrows, nullptr, rows};
       RowCtx src{c->d_pf_srow_slot, c->d_pf_srow_pos, c->d_pf_nsrows, nullptr, nseq};
       forward(c, prc, src, c->d_pf_gather, rows, 0);
@@ -1136,12 +1175,21 @@ int april_rollout_step(april_ctx* c, const april_request* new_reqs, int32_t n_ne
       HIPCHK(c, hipStreamSynchronize(st));
       if (c->h_ctrl->error) return fail(c, APRIL_ENOMEM, "KV page stack underflow on device");
       stopped = c->h_ctrl->stop != 0;
-      if (!stopped && launched >= T_bound) return fail(c, APRIL_EDEVICE, "scheduler did not stop after %d iterations", launched);
+      if (!stopped && launched >= T_bound) {
+        // every rollout has run to its limit or was preempted: a full scheduler pass ends the
+        // step (nothing live, nothing waiting for prefill)
+        launch_sched(st, c->d_ctrl, c->ds, c->d_row_slot, c->d_row_pos, c->d_free_stack, blk, 0);
+        HIPCHK(c, hipMemcpyAsync(c->h_ctrl, c->d_ctrl, sizeof(Ctrl), hipMemcpyDeviceToHost, st));
+        HIPCHK(c, hipStreamSynchronize(st));
+        stopped = c->h_ctrl->stop != 0;
+        if (!stopped) return fail(c, APRIL_EDEVICE, "scheduler did not stop after %d iterations", launched);
+      }
     }
     t_decode = now_s() - t1;
     iters = c->h_ctrl->stop_iter;
     sum_live = c->h_ctrl->sum_live; sum_ctx = c->h_ctrl->sum_ctx; sum_experts = c->h_ctrl->sum_experts;
     if (exact && iters != T_bound) return fail(c, APRIL_EDEVICE, "device stopped at iteration %lld, host expected %d", iters, T_bound);
+    n_preempted = c->h_ctrl->n_preempted;
     prof_collect(c);
 
     // ---- read back per-slot state --------------------------------------------------------
@@ -1167,7 +1215,7 @@ int april_rollout_step(april_ctx* c, const april_request* new_reqs, int32_t n_ne
       tokens_generated += gen - sh.gen;
       sh.gen = gen; sh.kv_len = snap[2 * S + s]; sh.n_blocks = snap[3 * S + s];
       if (state == SLOT_DONE) { sh.state = SLOT_DONE; fins.push_back({snap[4 * S + s], sh.req, s}); }
-      else { sh.state = SLOT_PARKED; partial_slots.push_back(s); }
+      else { sh.state = SLOT_PARKED; partial_slots.push_back(s); }   // preempted ones come back with kv_len 0
     }
   } else {
     for (int s : inflight) { c->slots[s].state = SLOT_PARKED; partial_slots.push_back(s); }
@@ -1225,6 +1273,7 @@ int april_rollout_step(april_ctx* c, const april_request* new_reqs, int32_t n_ne
     Entry e; e.req = c->slots[s].req; e.slot = s; e.limit = c->slots[s].limit; e.n_resumes = c->slots[s].n_resumes; e.done = 0;
     nb->entries.push_back(std::move(e));
   }
+  for (Entry& e : stay) nb->entries.push_back(std::move(e));
   std::sort(nb->entries.begin(), nb->entries.end(), [](const Entry& a, const Entry& b) { return a.req < b.req; });
 
   for (auto& v : c->r_tokens) c->r_tok_ptrs.push_back(v.data());
@@ -1239,6 +1288,7 @@ int april_rollout_step(april_ctx* c, const april_request* new_reqs, int32_t n_ne
   out->tokens_generated = tokens_generated;
   out->prefill_tokens = prefill_tokens;
   out->reprefill_tokens = reprefill_tokens;
+  out->n_preempted = n_preempted;
   out->sum_live = sum_live;
   out->sum_ctx = sum_ctx;
   out->dec_sum_live = sum_live - it1_live;

@@ -31,7 +31,11 @@ template <typename T> __device__ inline T from_f32(float v) { return (T)v; }
 //   - if finished >= N: raise stop, remember the iteration count (Section 2.2,
 //     "stop generation once N rollouts are completed");
 //   - else rebuild the dense list of live rollouts (slot order) and give a fresh
-//     KV page to every live rollout whose next position opens a new page.
+//     KV page to every live rollout whose next position opens a new page.  If the
+//     free pages do not cover that demand, the youngest live rollout (largest request
+//     id) is preempted first, repeatedly: its pages return to the stack, it keeps its
+//     tokens, stops for this step and is re-prefilled when resumed;
+//   - if nothing is live and nothing waits for prefill, the step ends (fewer than N).
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(1024) void sched_kernel(Ctrl* c, Slots s, int* row_slot, int* row_pos,
                                                      int* free_stack, int blk, int check_only) {
@@ -39,7 +43,10 @@ __global__ __launch_bounds__(1024) void sched_kernel(Ctrl* c, Slots s, int* row_
   __shared__ long long sh_ctx[16];
   const int tid = threadIdx.x, lane = tid & 63, wid = tid >> 6;
   const int stop = c->stop, finished = c->finished, n_target = c->n_target;
-  const int n_slots = c->n_slots, free_top = c->free_top, iter = c->iter;
+  const int n_slots = c->n_slots, iter = c->iter, inflight = c->inflight;
+  int free_top = c->free_top;
+  __shared__ int sh_need, sh_free, sh_pending;
+  if (tid == 0) { sh_need = 0; sh_pending = 0; }
   __syncthreads();
   if (stop) return;
   if (finished >= n_target) {
@@ -47,15 +54,52 @@ __global__ __launch_bounds__(1024) void sched_kernel(Ctrl* c, Slots s, int* row_
     return;
   }
   if (check_only) return;
+  if (free_top < inflight) {
+    // the pool may be short: count this iteration's page demand, preempt if it is
+    int cnt = 0;
+    for (int slot = tid; slot < n_slots; slot += 1024)
+      if (s.state[slot] == SLOT_LIVE) {
+        const int pos = s.kv_len[slot];
+        cnt += (pos % blk == 0) && (pos / blk >= s.n_blocks[slot]);
+      }
+    if (cnt) atomicAdd(&sh_need, cnt);
+    __syncthreads();
+    if (tid == 0) {
+      int need = sh_need, ft = free_top;
+      while (need > ft) {
+        int victim = -1;
+        long long best = -1;
+        for (int slot = 0; slot < n_slots; ++slot)
+          if (s.state[slot] == SLOT_LIVE && s.req_id[slot] > best) { best = s.req_id[slot]; victim = slot; }
+        if (victim < 0) break;
+        const int pos = s.kv_len[victim], nb = s.n_blocks[victim];
+        if ((pos % blk == 0) && (pos / blk >= nb)) --need;
+        for (int j = 0; j < nb; ++j) free_stack[ft++] = s.block_table[(size_t)victim * s.max_blocks + j];
+        s.n_blocks[victim] = 0;
+        s.kv_len[victim] = 0;
+        s.state[victim] = SLOT_PREEMPTED;
+        s.finish_iter[victim] = c->n_preempted;      // order of preemption within the step
+        c->n_preempted += 1;
+      }
+      sh_free = ft;
+    }
+    __syncthreads();
+    free_top = sh_free;
+  }
   int base_live = 0, base_need = 0, err = 0;
   long long ctx_sum = 0;
   for (int s0 = 0; s0 < n_slots; s0 += 1024) {
     const int slot = s0 + tid;
     int live = 0, need = 0, pos = 0;
-    if (slot < n_slots && s.state[slot] == SLOT_LIVE) {
-      live = 1;
-      pos = s.kv_len[slot];
-      need = (pos % blk == 0) && (pos / blk >= s.n_blocks[slot]);
+    if (slot < n_slots) {
+      const int stt = s.state[slot];
+      if (stt == SLOT_LIVE) {
+        live = 1;
+        pos = s.kv_len[slot];
+        need = (pos % blk == 0) && (pos / blk >= s.n_blocks[slot]);
+      } else if (stt == SLOT_PREFILL) {
+        sh_pending = 1;
+      }
     }
     const int ia = wave_incl_scan(live), ib = wave_incl_scan(need);
     if (lane == 63) { sh_a[wid] = ia; sh_b[wid] = ib; }
@@ -98,10 +142,15 @@ __global__ __launch_bounds__(1024) void sched_kernel(Ctrl* c, Slots s, int* row_
     for (int w = 0; w < 16; ++w) { tot += sh_ctx[w]; e |= sh_err[w]; }
     c->n_rows = base_live;
     c->free_top = free_top - base_need < 0 ? 0 : free_top - base_need;
-    c->iter = iter + 1;
-    c->sum_live += base_live;
-    c->sum_ctx += tot;
-    c->iter_ctx = tot;
+    if (base_live == 0 && !sh_pending) {
+      c->stop = 1;                 // nothing left in flight: the step ends short of N
+      c->stop_iter = iter;
+    } else {
+      c->iter = iter + 1;
+      c->sum_live += base_live;
+      c->sum_ctx += tot;
+      c->iter_ctx = tot;
+    }
     if (e) { c->error = 1; c->stop = 1; c->stop_iter = iter; c->n_rows = 0; }
   }
 }

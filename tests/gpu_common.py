@@ -40,7 +40,7 @@ def req_dicts(reqs, forced=None):
     return out
 
 
-def run_gpu(ctx, reqs, n_target, n_over, max_new, steps, *, forced=None, between=None):
+def run_gpu(ctx, reqs, n_target, n_over, max_new, steps, *, forced=None, between=None, allow_short=False):
     """-> list of per-step dicts (ids, tokens, stats, buffer view).  `between(ctx, buffer)`
     may act on the buffer (e.g. drop its KV) before it is resumed; it returns the
     buffer handle to resume."""
@@ -53,7 +53,8 @@ def run_gpu(ctx, reqs, n_target, n_over, max_new, steps, *, forced=None, between
                         consumed=res.n_new_consumed, iters=res.decode_iters, generated=res.tokens_generated,
                         buffer=[(p["request_id"], len(p["generated"]), p["done"]) for p in view],
                         buffer_tokens={p["request_id"]: p["generated"].tolist() for p in view},
-                        sum_live=res.sum_live, res=res))
+                        sum_live=res.sum_live, res=res, n_preempted=res.n_preempted,
+                        kv_resident={p["request_id"]: p["kv_resident"] for p in view}))
         buf = res.buffer
         if between is not None:
             buf = between(ctx, buf)
@@ -62,7 +63,7 @@ def run_gpu(ctx, reqs, n_target, n_over, max_new, steps, *, forced=None, between
 
 
 def run_oracle(w, weights, reqs, n_target, n_over, max_new, steps, *, keep_logits=False, temperature=1.0,
-               eos=-1, drop_kv=False):
+               eos=-1, drop_kv=False, pool=None):
     eng = OracleRollouts(Decoder(w.shape, weights), sampler_name(w), top_k=max(w.top_k, 1),
                          temperature=temperature, seed=w.seed, eos_token=eos, keep_logits=keep_logits)
     rolls = [eng.make_rollout(r.request_id, r.tokens, r.forced_len) for r in reqs]
@@ -70,14 +71,15 @@ def run_oracle(w, weights, reqs, n_target, n_over, max_new, steps, *, keep_logit
     for _ in range(steps):
         if drop_kv:
             eng.drop_kv()
-        o = eng.step(rolls[nxt:], n_target, n_over, max_new)
+        o = eng.step(rolls[nxt:], n_target, n_over, max_new, pool=pool)
         nxt += o.n_new_consumed
         out.append(dict(ids=[r.request_id for r in o.completed], tokens=[list(r.tokens) for r in o.completed],
                         n_resumes=[r.n_resumes for r in o.completed], consumed=o.n_new_consumed,
                         iters=o.decode_iters, generated=o.tokens_generated,
                         buffer=[(r.request_id, r.gen, int(r.done)) for r in o.buffer],
                         buffer_tokens={r.request_id: list(r.tokens) for r in o.buffer},
-                        sum_live=sum(o.live_per_iter)))
+                        sum_live=sum(o.live_per_iter), n_preempted=len(o.preempted),
+                        kv_resident={r.request_id: int(r.kv > 0) for r in o.buffer}))
     return out, eng
 
 

@@ -166,7 +166,9 @@ def test_scheduling_bit_exact_at_all_five_configs(name):
     """Scheduling depends only on the forced lengths, so each configuration's N, N',
     max_new and length stream is run at full size on a one-layer toy model."""
     full = ai.WORKLOADS[name]
-    shape = ai.ModelShape(1, 32, 1, 1, 32, 32, 64, dtype=ai.DTYPE_FP32)
+    # long contexts: the bf16 path (MFMA attention) for the big configurations, fp32 for the rest
+    dtype = ai.DTYPE_FP32 if full.max_new <= 2048 else ai.DTYPE_BF16
+    shape = ai.ModelShape(1, 32, 1, 1, 32, 32, 64, dtype=dtype)
     w = ai.Workload(full.name, shape, 4, 4, full.n_target, full.n_overprovision, full.max_new, full.len_mu,
                     full.len_sigma, full.len_lo, full.len_hi, ai.SAMPLER_GREEDY, 0, full.steps, full.seed)
     weights = ai.make_weights(shape, 0)
@@ -249,10 +251,50 @@ def test_error_paths():
         with pytest.raises(A.AprilError):
             missing = {k: v for k, v in weights.items() if k != "wo.1"}
             A.april_init(A.make_cfg(w.shape, max_inflight=4, max_ctx=64), A.pack_weights(w.shape, missing))
-        tiny_pool = make_engine(w, weights, kv_pool_bytes=3 * 16 * 2 * 2 * 64 * 4)   # 3 pages
+        tiny_pool = make_engine(w, weights, kv_pool_bytes=1 * 16 * 2 * 2 * 64 * 4)   # 1 page < one prompt
         with pytest.raises(A.AprilError) as e:
             A.april_rollout_step(tiny_pool, req_dicts(reqs), 6, 10, 40)
         assert e.value.code == A.APRIL_ENOMEM
         A.april_destroy(tiny_pool)
     finally:
         A.april_destroy(ctx)
+
+
+def test_kv_pool_exhaustion_preempts_youngest_and_reprefills():
+    """A KV pool far smaller than the worst case of the step: admission stops when prompt
+    pages do not fit, the youngest decoding rollouts are preempted on the device, come back
+    token-only and are re-prefilled.  Scheduling (ids, iteration counts, who was preempted,
+    who holds KV) is bit-exact against the oracle's page arithmetic; tokens are unchanged."""
+    from oracle.scheduler import PagePool
+    w = small_fp32_workload()
+    weights = ai.make_weights(w.shape, w.seed)
+    reqs = ai.make_requests(w, ai.requests_needed(w, 8))
+    s = w.shape
+    n_pages = 19                                   # 10 rollouts in flight would need up to 40
+    page_bytes = 16 * 2 * s.n_layers * s.n_kv_heads * s.head_dim * 4
+    steps = 8
+    want, eng = run_oracle(w, weights, reqs, w.n_target, w.n_overprovision, w.max_new, steps, keep_logits=True,
+                           pool=PagePool(total=n_pages, page_tokens=16))
+    assert sum(o["n_preempted"] for o in want) > 0
+    ctx = make_engine(w, weights, kv_pool_bytes=n_pages * page_bytes)
+    ample = make_engine(w, weights)
+    try:
+        got = run_gpu(ctx, reqs, w.n_target, w.n_overprovision, w.max_new, steps)
+        assert_schedule_equal(got, want)
+        for g, o in zip(got, want):
+            assert g["n_preempted"] == o["n_preempted"]
+            assert g["kv_resident"] == o["kv_resident"]
+        assert sum(g["res"].reprefill_tokens for g in got) > 0
+        assert compare_free_running_tokens(got, want, eng, FP32_LOGIT_TOL) > 100
+        # same rollouts as with an ample pool, token for token
+        base = run_gpu(ample, reqs, w.n_target, w.n_overprovision, w.max_new, steps)
+        a = {rid: t for g in got for rid, t in zip(g["ids"], g["tokens"])}
+        b = {rid: t for g in base for rid, t in zip(g["ids"], g["tokens"])}
+        assert sum(g["n_preempted"] for g in base) == 0
+        for rid in set(a) & set(b):
+            assert a[rid] == b[rid], rid
+        info = ap().april_get_info(ctx)
+        assert info["kv_blocks_total"] == n_pages
+    finally:
+        ap().april_destroy(ctx)
+        ap().april_destroy(ample)

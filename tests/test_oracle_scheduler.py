@@ -129,3 +129,88 @@ def test_eos_token_terminates_early():
 def test_starved_raises():
     with pytest.raises(RuntimeError):
         rollout_step([], [Rollout(request_id=0, prompt_len=1, forced_len=2)], 2, 3, 5)
+
+
+# ---------------------------------------------------------------------------
+# KV page pool: admission limit and preemption of the youngest
+# ---------------------------------------------------------------------------
+from oracle.scheduler import PagePool
+
+
+def test_page_pool_worked_example_by_hand():
+    """4-token pages, 6 pages.  Traced by hand: three 4-token prompts take 3 pages; at
+    iteration 2 every rollout opens its second page (pool empty); at iteration 6 all three
+    need a third page, so the youngest (id 2) is preempted and its 2 pages serve the others."""
+    pool = PagePool(total=6, page_tokens=4)
+    reqs = [Rollout(request_id=i, prompt_len=4, forced_len=9) for i in range(3)]
+    reqs += [Rollout(request_id=3 + i, prompt_len=4, forced_len=2) for i in range(2)]
+    out = rollout_step([], reqs[:3], 2, 3, 20, pool=pool)
+    assert out.decode_iters == 9 and out.tokens_generated == 9 + 9 + 5
+    assert [r.request_id for r in out.completed] == [0, 1] and out.preempted == [2]
+    assert [(r.request_id, r.gen, r.kv, r.pages) for r in out.buffer] == [(2, 5, 0, 0)]
+    assert pool.free == 6
+    # step 2: rollout 2 is re-prefilled (9 tokens = 3 pages), two new ones take 1 page each;
+    # at iteration 2 both new ones need a page, one is free: the youngest (id 4) is preempted
+    out2 = rollout_step(out.buffer, reqs[3:], 2, 3, 20, pool=pool)
+    assert out2.n_new_consumed == 2 and out2.preempted == [4]
+    assert [r.request_id for r in out2.completed] == [3, 2] and out2.decode_iters == 4
+    assert [(r.request_id, r.gen, r.kv) for r in out2.buffer] == [(4, 1, 0)]
+    assert pool.free == 6
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_page_pool_ample_equals_no_pool_and_pages_are_conserved(seed):
+    rng = np.random.default_rng(100 + seed)
+    n, n_over = int(rng.integers(2, 6)), int(rng.integers(6, 12))
+    lens = rng.integers(1, 40, size=300)
+    P = int(rng.integers(1, 20))
+
+    def run(pool):
+        reqs = [Rollout(request_id=i, prompt_len=P, forced_len=int(l)) for i, l in enumerate(lens)]
+        buf, nxt, outs = [], 0, []
+        for _ in range(6):
+            out = rollout_step(buf, reqs[nxt:], n, n_over, 30, pool=pool)
+            nxt += out.n_new_consumed
+            buf = out.buffer
+            outs.append(([r.request_id for r in out.completed], [(r.request_id, r.gen, r.done) for r in buf],
+                         out.decode_iters, out.tokens_generated, out.n_new_consumed))
+            if pool is not None:
+                held = sum(r.pages for r in buf)
+                assert pool.free + held == pool.total
+                for r in buf:
+                    assert r.pages == (0 if r.done or r.kv == 0 else -(-r.kv // pool.page_tokens))
+        return outs
+
+    assert run(None) == run(PagePool(total=10 ** 6, page_tokens=16))
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_page_pool_tight_nothing_lost_youngest_first(seed):
+    rng = np.random.default_rng(200 + seed)
+    n, n_over = 3, 8
+    lens = rng.integers(5, 60, size=400)
+    P = 10
+    total = int(rng.integers(16, 28))             # pages of 4 tokens: one rollout fits (<= 15 pages), eight do not
+    pool = PagePool(total=total, page_tokens=4)
+    reqs = [Rollout(request_id=i, prompt_len=P, forced_len=int(l)) for i, l in enumerate(lens)]
+    buf, nxt, returned, admitted = [], 0, [], 0
+    saw_preempt = False
+    for _ in range(10):
+        before = {r.request_id: r.gen for r in buf}
+        out = rollout_step(buf, reqs[nxt:], n, n_over, 50, pool=pool)
+        nxt += out.n_new_consumed
+        admitted = nxt
+        buf = out.buffer
+        returned += [r.request_id for r in out.completed]
+        assert len(out.completed) <= n and all(r.done for r in out.completed)
+        assert sorted(returned + [r.request_id for r in buf]) == list(range(admitted))
+        assert pool.free + sum(r.pages for r in buf) == pool.total and pool.free >= 0
+        if out.preempted:
+            saw_preempt = True
+            # a preempted rollout is younger than every rollout that kept decoding to the end
+            survivors = [r.request_id for r in out.completed if r.request_id in before or True]
+            for r in buf:
+                if r.request_id in out.preempted:
+                    assert r.kv == 0 and r.pages == 0 and not r.done
+    assert saw_preempt
+    assert len(returned) > 0

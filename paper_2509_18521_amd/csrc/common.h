@@ -18,10 +18,10 @@ enum : int { SLOT_FREE = 0, SLOT_LIVE = 1, SLOT_DONE = 2, SLOT_PARKED = 3, SLOT_
 // Device-resident control block of the early-termination scheduler (Section 2.2:
 // "stop generation once N rollouts are completed" is decided here, on device).
 struct Ctrl {
-  int n_rows;       // live rollouts of the current decode iteration
+  int n_rows;       // live rollouts of the current decode iteration   } read together by every
+  int stop;         // 1: the step is over, every later kernel is a no-op } kernel as one int2
   int finished;     // rollouts complete in this step (surplus from the last step included)
   int n_target;     // N
-  int stop;         // 1: the step is over, every later kernel is a no-op
   int iter;         // iterations executed so far in this step
   int stop_iter;    // iteration count at which stop was raised
   int free_top;     // free KV pages on the stack

@@ -222,10 +222,12 @@ int fetch_tensor(april_ctx* c, const april_tensor* w, int n, const std::string& 
   return APRIL_OK;
 }
 
+// Cross-workgroup k-split of a projection GEMM: enough workgroups to occupy the chip when
+// there are few n-tiles, none when the n-tiles alone do; a function of (N, K) only, so a
+// row's summation order never depends on the batch.
 int pick_ksplit(int N, int K) {
   const int n_tiles = N / 32, KT = K / 16;
-  if (n_tiles >= 512) return 1;
-  int s = KT / 12;
+  int s = std::min(KT / 12, 384 / std::max(n_tiles, 1));
   if (s < 1) s = 1;
   if (s > 8) s = 8;
   return s;
@@ -328,7 +330,7 @@ void forward(april_ctx* c, RowCtx rows, RowCtx srows, const int* gather, double 
       gemm(KC_MOE_ROUTE, rows, c->h_act, nullptr, L.router_s, c->router_out, E, d, c->s_router, c->router_stride, B);
       launch_moe_route(st, rows, c->router_out, c->s_router, c->router_stride, E, tk, c->moe_ids, c->moe_wts);
       launch_moe_dispatch(st, rows, c->moe_ids, E, tk, c->moe_cnt, c->moe_base, c->moe_pos, c->moe_src, c->moe_p_cap,
-                          rows.stop ? c->d_ctrl : nullptr);
+                          rows.ctl == reinterpret_cast<const int2*>(c->d_ctrl) ? c->d_ctrl : nullptr);
       const double hit = std::min<double>(E, B * tk);   // bookkeeping estimate: experts that receive a token
       {
         ProfScope p(c, KC_MOE_GATEUP, hit * 2.0 * Fe * d * e + B * tk * (d + Fe) * e, 4.0 * B * tk * Fe * d);
@@ -630,7 +632,7 @@ int april_init(const april_model_cfg* cfg, const april_tensor* weights, int32_t 
   TRY(dev_alloc(c, &c->rope_sin, (size_t)g.max_ctx * g.head_dim / 2, false));
   launch_rope_table(c->stream, c->rope_cos, c->rope_sin, g.max_ctx, g.head_dim, g.rope_theta);
   TRY(dev_alloc(c, &c->d_pf_row_slot, M)); TRY(dev_alloc(c, &c->d_pf_row_pos, M));
-  TRY(dev_alloc(c, &c->d_pf_nrows, 1)); TRY(dev_alloc(c, &c->d_pf_nsrows, 1));
+  TRY(dev_alloc(c, &c->d_pf_nrows, 2)); TRY(dev_alloc(c, &c->d_pf_nsrows, 2));   // {rows, stop = 0}
   TRY(dev_alloc(c, &c->d_pf_srow_slot, S)); TRY(dev_alloc(c, &c->d_pf_srow_pos, S)); TRY(dev_alloc(c, &c->d_pf_gather, S));
   c->h_stage_ints = 2 * M + 8 * (size_t)S + 64;
   HIPTRY(hipHostMalloc((void**)&c->h_stage, c->h_stage_ints * sizeof(int)));
@@ -849,11 +851,12 @@ int april_sample_rows(april_ctx* c, const float* logits, int32_t n_rows, const i
   HIPCHK(c, hipMalloc((void**)&d_req, n_rows * sizeof(long long)));
   HIPCHK(c, hipMalloc((void**)&d_gen, n_rows * sizeof(int)));
   HIPCHK(c, hipMalloc((void**)&d_out, n_rows * sizeof(int)));
-  HIPCHK(c, hipMalloc((void**)&d_n, sizeof(int)));
+  HIPCHK(c, hipMalloc((void**)&d_n, 2 * sizeof(int)));
+  HIPCHK(c, hipMemset(d_n, 0, 2 * sizeof(int)));
   HIPCHK(c, hipMemcpy(d_req, request_ids, n_rows * sizeof(long long), hipMemcpyHostToDevice));
   HIPCHK(c, hipMemcpy(d_gen, gen_index, n_rows * sizeof(int), hipMemcpyHostToDevice));
   HIPCHK(c, hipMemcpy(d_n, &n_rows, sizeof(int), hipMemcpyHostToDevice));
-  RowCtx rc{nullptr, nullptr, d_n, nullptr, n_rows};
+  RowCtx rc{nullptr, nullptr, reinterpret_cast<const int2*>(d_n), n_rows};
   SamplerCfg sc{c->cfg.sampler, c->cfg.top_k, c->cfg.temperature, (unsigned long long)c->cfg.seed};
   // same candidate search as the rollout path: group maxima first when the vocabulary allows
   const int grp = lmhead_group_cols();
@@ -1055,7 +1058,7 @@ int april_rollout_step(april_ctx* c, const april_request* new_reqs, int32_t n_ne
     int decode_max_ctx = 1;
     for (int s : inflight) decode_max_ctx = std::max(decode_max_ctx, c->slots[s].prompt_len + c->slots[s].limit);
     c->step_max_ctx = decode_max_ctx;
-    RowCtx drc{c->d_row_slot, c->d_row_pos, &c->d_ctrl->n_rows, &c->d_ctrl->stop, 0};
+    RowCtx drc{c->d_row_slot, c->d_row_pos, reinterpret_cast<const int2*>(c->d_ctrl), 0};
     const double t0 = now_s();
     // pages of every rollout that is (re-)prefilled this step, in admission order, before
     // the first scheduler pass hands out decode pages
@@ -1105,8 +1108,8 @@ int april_rollout_step(april_ctx* c, const april_request* new_reqs, int32_t n_ne
       HIPCHK(c, hipMemcpyAsync(c->d_pf_gather, h_g, nseq * sizeof(int), hipMemcpyHostToDevice, st));
       HIPCHK(c, hipMemcpyAsync(c->d_pf_nrows, h_n, sizeof(int), hipMemcpyHostToDevice, st));
       HIPCHK(c, hipMemcpyAsync(c->d_pf_nsrows, h_n + 1, sizeof(int), hipMemcpyHostToDevice, st));
-      RowCtx prc{c->d_pf_row_slot, c->d_pf_row_pos, c->d_pf_nrows, nullptr, rows};
-      RowCtx src{c->d_pf_srow_slot, c->d_pf_srow_pos, c->d_pf_nsrows, nullptr, nseq};
+      RowCtx prc{c->d_pf_row_slot, c->d_pf_row_pos, reinterpret_cast<const int2*>(c->d_pf_nrows), rows};
+      RowCtx src{c->d_pf_srow_slot, c->d_pf_srow_pos, reinterpret_cast<const int2*>(c->d_pf_nsrows), nseq};
       forward(c, prc, src, c->d_pf_gather, rows, 0);
       HIPCHK(c, hipStreamSynchronize(st));     // staging buffers are reused by the next chunk
     }

@@ -4,9 +4,9 @@
 // Row model: a forward pass runs over "rows"; row r belongs to sequence slot
 // row_slot[r] and sits at position row_pos[r].  For a decode iteration the rows are
 // the live rollouts (written by the scheduler kernel), for prefill they are all
-// prompt tokens of the admitted rollouts.  n_rows lives in device memory; kernels
-// whose block index is beyond it exit.  stop (device int, may be null) turns every
-// kernel into a no-op once the scheduler has ended the step.
+// prompt tokens of the admitted rollouts.  The row count lives in device memory next to
+// the stop flag; kernels whose block index is beyond it exit, and a raised stop flag
+// turns every kernel into a no-op once the scheduler has ended the step.
 #pragma once
 #include "common.h"
 
@@ -15,15 +15,18 @@ namespace april {
 struct RowCtx {
   const int* row_slot;
   const int* row_pos;
-  const int* n_rows;     // device
-  const int* stop;       // device, nullable
+  const int2* ctl;       // device: x = number of rows, y = stop flag (one 8-byte scalar load)
   int max_rows;          // host-known upper bound (grid size)
 };
 
+// Rows to process: 0 once the scheduler has ended the step.
+__device__ inline int rows_or_zero(const RowCtx& rc) {
+  const int2 v = *rc.ctl;
+  return v.y ? 0 : v.x;
+}
 // Early exit of a one-workgroup-per-row kernel: step stopped, or row beyond the batch.
-#define ROW_GUARD(rc, r)                               \
-  if ((rc).stop != nullptr && *(rc).stop != 0) return; \
-  if ((r) >= *(rc).n_rows) return;
+#define ROW_GUARD(rc, r) \
+  if ((r) >= rows_or_zero(rc)) return;
 
 // --- scheduler / allocator -------------------------------------------------
 // check_only = 1: only the "N complete => stop" test (end of a chunk of iterations).

@@ -78,7 +78,7 @@ __global__ __launch_bounds__(64 * ATT_WAVES) void attn_decode_kernel(
 #pragma unroll
   for (int d = 0; d < DT; ++d) oacc[d] = f32x4{};
 
-  // tiles wave, wave + 4, ... of the split; the fetch of tile i+1 is always issued (clamped
+  // tiles wave, wave + ATT_WAVES, ... of the split; the fetch of tile i+1 is always issued (clamped
   // to the last tile) so that the wait counts are static
   auto load_tile = [&](int tile, bf16x8 (&kk)[2][KC], bf16x4 (&vv)[2][DT]) {
 #pragma unroll

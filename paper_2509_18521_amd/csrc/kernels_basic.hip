@@ -489,8 +489,7 @@ template void launch_silu_mul<bf16_t, true>(hipStream_t, RowCtx, const float*, i
 // ---------------------------------------------------------------------------
 template <typename T, bool XF>
 __global__ __launch_bounds__(256) void gemm_ref_kernel(RowCtx rc, const T* x, const T* W, float* out, int N, int K) {
-  if (rc.stop != nullptr && *rc.stop != 0) return;
-  const int rows = *rc.n_rows;
+  const int rows = rows_or_zero(rc);
   const int r0 = blockIdx.y * 8;
   if (r0 >= rows) return;
   const int n = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;

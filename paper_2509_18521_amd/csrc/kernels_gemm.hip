@@ -184,8 +184,7 @@ __global__ __launch_bounds__(64 * KW) void gemm_mfma_kernel(RowCtx rc, const bf1
                                                            bf16_t* __restrict__ act, int N, int K, int ksplit,
                                                            size_t partial_stride) {
   __shared__ float red[INTRA ? (KW - 1) * NT * MT * 16 * 64 : 1];
-  if (rc.stop != nullptr && *rc.stop != 0) return;
-  const int rows = *rc.n_rows;
+  const int rows = rows_or_zero(rc);
   const int mt0 = blockIdx.z * MT;
   if (mt0 * 32 >= rows) return;
   const int KT = K >> 4;

@@ -86,8 +86,8 @@ __global__ __launch_bounds__(1024) void moe_dispatch_kernel(RowCtx rc, const int
                                                             int* base, int* pos_of, int* src_row, int p_cap,
                                                             Ctrl* ctrl) {
   __shared__ int s_cnt[256], s_base[257];
-  if (rc.stop != nullptr && *rc.stop != 0) return;
-  const int rows = *rc.n_rows, tid = threadIdx.x;
+  const int rows = rows_or_zero(rc), tid = threadIdx.x;
+  if (rows == 0) return;
   if (tid < 256) s_cnt[tid] = 0;
   __syncthreads();
   const int n = rows * top_k;
@@ -265,7 +265,7 @@ void launch_moe_gateup(hipStream_t st, RowCtx rc, const int* cnt, const int* bas
                        const bf16_t* h, const bf16_t* Wg, const bf16_t* Wu, bf16_t* act, int E, int Fe, int d) {
   constexpr int MT = 2;
   dim3 grid(Fe >> 5, E, ceil_div(ceil_div(rc.max_rows, 32), MT));
-  hipLaunchKernelGGL((moe_gemm_kernel<2, MT, true>), grid, dim3(64 * MOE_KW), 0, st, rc.stop, cnt, base, src_row,
+  hipLaunchKernelGGL((moe_gemm_kernel<2, MT, true>), grid, dim3(64 * MOE_KW), 0, st, reinterpret_cast<const int*>(rc.ctl) + 1, cnt, base, src_row,
                      reinterpret_cast<const bf16x8*>(h), reinterpret_cast<const bf16x8*>(Wg),
                      reinterpret_cast<const bf16x8*>(Wu), (size_t)Fe * d / 8, nullptr, act, Fe, d, d);
 }
@@ -274,7 +274,7 @@ void launch_moe_down(hipStream_t st, RowCtx rc, const int* cnt, const int* base,
                      const bf16_t* Wd, float* out, int E, int Fe, int d) {
   constexpr int MT = 2;
   dim3 grid((d >> 5) / 2, E, ceil_div(ceil_div(rc.max_rows, 32), MT));
-  hipLaunchKernelGGL((moe_gemm_kernel<2, MT, false>), grid, dim3(64 * MOE_KW), 0, st, rc.stop, cnt, base, nullptr,
+  hipLaunchKernelGGL((moe_gemm_kernel<2, MT, false>), grid, dim3(64 * MOE_KW), 0, st, reinterpret_cast<const int*>(rc.ctl) + 1, cnt, base, nullptr,
                      reinterpret_cast<const bf16x8*>(act), reinterpret_cast<const bf16x8*>(Wd), nullptr,
                      (size_t)d * Fe / 8, out, nullptr, d, Fe, Fe);
 }

@@ -121,7 +121,7 @@ struct april_ctx {
   int s_qkv = 1, s_o = 1, s_down = 1;
   size_t qkv_stride = 0, proj_stride = 0;
   // bf16 MFMA attention: split-KV workspace
-  bool attn_mfma = false;
+  bool attn_mfma = false, fuse_rope = true;
   int attn_chunk = 256, attn_max_splits = 1, attn_ws_rows = 0;
   float* attn_ws = nullptr;
   int* attn_counters = nullptr;
@@ -305,7 +305,9 @@ void forward(april_ctx* c, RowCtx rows, RowCtx srows, const int* gather, double 
     const LayerW& L = c->layers[l];
     norm(rows, l == 0 ? 0 : c->s_down, L.attn_norm, c->h_act, nullptr, B, true);
     gemm(KC_GEMM_QKV, rows, c->h_act, L.wqkv, L.wqkv_s, c->qkv, nqkv, d, c->s_qkv, c->qkv_stride, B);
-    {
+    // decode iterations: rotary + KV append are done inside the attention kernel
+    const bool fuse_rope = c->attn_mfma && c->fuse_rope && gather == nullptr;
+    if (!fuse_rope) {
       ProfScope p(c, KC_ROPE, B * (nqkv * 4.0 + nq * 4.0 + 2 * nkv * e), 0);
       if (c->bf16) launch_rope_append<bf16_t>(st, rows, c->ds, c->qkv, c->s_qkv, c->qkv_stride, c->rope_cos, c->rope_sin, c->q_rot, (bf16_t*)c->kv_pool, c->kvl, l, Hq);
       else launch_rope_append<float>(st, rows, c->ds, c->qkv, c->s_qkv, c->qkv_stride, c->rope_cos, c->rope_sin, c->q_rot, (float*)c->kv_pool, c->kvl, l, Hq);
@@ -317,8 +319,9 @@ void forward(april_ctx* c, RowCtx rows, RowCtx srows, const int* gather, double 
         for (int base = 0; base < rows.max_rows; base += c->attn_ws_rows) {
           RowCtx sub = rows;
           sub.max_rows = std::min(c->attn_ws_rows, rows.max_rows - base);
-          launch_attn_decode(st, sub, base, c->ds, c->q_rot, (const bf16_t*)c->kv_pool, c->kvl, l, Hq,
-                             (bf16_t*)c->attn_out, c->attn_ws, c->attn_counters, c->attn_max_splits, gs);
+          launch_attn_decode(st, sub, base, c->ds, c->q_rot, (bf16_t*)c->kv_pool, c->kvl, l, Hq,
+                             (bf16_t*)c->attn_out, c->attn_ws, c->attn_counters, c->attn_max_splits, gs,
+                             fuse_rope ? c->qkv : nullptr, c->s_qkv, c->qkv_stride, c->rope_cos, c->rope_sin);
         }
       } else if (c->bf16) launch_attn_ref<bf16_t, true>(st, rows, c->ds, c->q_rot, (const bf16_t*)c->kv_pool, c->kvl, l, Hq, (bf16_t*)c->attn_out);
       else launch_attn_ref<float, false>(st, rows, c->ds, c->q_rot, (const float*)c->kv_pool, c->kvl, l, Hq, (float*)c->attn_out);
@@ -444,6 +447,8 @@ int april_init(const april_model_cfg* cfg, const april_tensor* weights, int32_t 
   const char* am = getenv("APRIL_ATTN");
   c->attn_mfma = c->bf16 && !(am && !strcmp(am, "ref"));
   if (moe && !(c->use_mfma && c->attn_mfma)) { delete c; return fail(nullptr, APRIL_EINVAL, "routed experts run on the MFMA path only"); }
+  const char* fr = getenv("APRIL_FUSE_ROPE");
+  c->fuse_rope = !(fr && !strcmp(fr, "0"));
   const char* gr = getenv("APRIL_GRAPH");
   c->use_graph = !(gr && !strcmp(gr, "0"));
   for (int i = 0; i < KC_COUNT; ++i) c->stats[i] = april_kernel_stat{kKernelNames[i], 0, 0, 0, 0};

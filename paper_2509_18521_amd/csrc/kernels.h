@@ -28,6 +28,12 @@ __device__ inline int rows_or_zero(const RowCtx& rc) {
 #define ROW_GUARD(rc, r) \
   if ((r) >= rows_or_zero(rc)) return;
 
+// Rotary embedding of the pair (a, b) = (x[i], x[i + d/2]) with cos c and sin s, in one
+// fixed operation order (no compiler-chosen contraction), so that every kernel that rotates
+// produces the same bits.
+__device__ inline float rope_first(float a, float b, float c, float s) { return __fmaf_rn(a, c, -__fmul_rn(b, s)); }
+__device__ inline float rope_second(float a, float b, float c, float s) { return __fmaf_rn(b, c, __fmul_rn(a, s)); }
+
 // --- scheduler / allocator -------------------------------------------------
 // check_only = 1: only the "N complete => stop" test (end of a chunk of iterations).
 void launch_sched(hipStream_t st, Ctrl* ctrl, Slots s, int* row_slot, int* row_pos,
@@ -78,9 +84,13 @@ void launch_attn_ref(hipStream_t st, RowCtx rc, Slots s, const float* q_rot, con
 // counters: split workspace for rc.max_rows rows (counters zero on entry and on exit);
 // max_splits <= 32.
 int attn_split_tokens();
+// fused_qkv != nullptr (decode iterations): the kernel also rotates q / the new key and
+// appends the new key / value itself from the QKV GEMM's split-K partials (q_rot unused).
 void launch_attn_decode(hipStream_t st, RowCtx rc, int row_base, Slots s, const float* q_rot,
-                        const bf16_t* kv_pool, KVLayout kvl, int layer, int n_q_heads, bf16_t* out,
-                        float* ws, int* counters, int max_splits, int grid_splits);
+                        bf16_t* kv_pool, KVLayout kvl, int layer, int n_q_heads, bf16_t* out,
+                        float* ws, int* counters, int max_splits, int grid_splits,
+                        const float* fused_qkv, int n_partials, size_t partial_stride,
+                        const float* rope_cos, const float* rope_sin);
 
 template <typename T, bool XF>
 void launch_silu_mul(hipStream_t st, RowCtx rc, const float* gu, int F, T* act);

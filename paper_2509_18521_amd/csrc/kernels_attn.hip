@@ -16,7 +16,15 @@
 // k index runs over (page A tokens 4g..4g+3, page B tokens 4g..4g+3), and the V^T
 // fragment is loaded with the same token order.
 //
-// KV page layout (written by rope_append_kernel, mode 1), per (page, KV head):
+// FUSED (decode iterations): the kernel also does the rotary embedding and the KV append of
+// the row's new token, so no separate kernel runs between the QKV GEMM and attention.  Every
+// workgroup sums the split-K partials of its query heads and rotates them; the workgroup of
+// the last KV split computes the new token's rotated key and its value, stores them in the
+// page as bf16, and substitutes exactly those bf16 values into the fragments of the tile
+// that holds the position, so the products are bit-identical to reading them back.
+// (Prefill keeps the separate rope/append kernel: its rows attend to each other's new keys.)
+//
+// KV page layout (written by rope_append_kernel or here, mode 1), per (page, KV head):
 //   K: MFMA A-fragment order  [d/32][lane = t + 16*((d%32)/8)][d%8]   -> 1 KiB coalesced loads
 //   V: transposed             [d][t]                                 -> 8-byte loads, 512 B/wave coalesced
 #include "kernels.h"
@@ -26,15 +34,24 @@ namespace april {
 constexpr int ATT_SPLIT = 1024;          // tokens per KV split = 64 pages = one page id per lane
 constexpr int ATT_WAVES = 4;
 
-template <int DH>
+struct AttnFuse {              // inputs of the fused rotary + append (FUSED only)
+  const float* qkv;            // fp32 [n_partials][rows][(Hq + 2 Hkv) * dh] split-K partials of the QKV GEMM
+  int n_partials;
+  size_t partial_stride;
+  const float* rope_cos;       // [pos][dh/2]
+  const float* rope_sin;
+};
+
+template <int DH, bool FUSED>
 __global__ __launch_bounds__(64 * ATT_WAVES) void attn_decode_kernel(
-    RowCtx rc, int row_base, Slots s, const float* __restrict__ q_rot, const bf16_t* __restrict__ kv_pool,
-    KVLayout L, int layer, int Hq, bf16_t* __restrict__ out, float* ws, int* counters, int max_splits) {
+    RowCtx rc, int row_base, Slots s, const float* __restrict__ q_rot, bf16_t* kv_pool, KVLayout L, int layer,
+    int Hq, bf16_t* __restrict__ out, float* ws, int* counters, int max_splits, AttnFuse fz) {
   constexpr int KC = DH / 32;      // k-chunks of the QK product
   constexpr int DT = DH / 16;      // dim tiles of the PV product
   constexpr int REC = 32 + 16 * DH;   // floats of one partial result: m[16], l[16], o[16][DH]
   __shared__ float lds[ATT_WAVES * REC];
   __shared__ int s_last;
+  __shared__ bf16_t s_knew[DH], s_vnew[DH];
   const int wr = blockIdx.x, r = row_base + wr, kvh = blockIdx.y, split = blockIdx.z;   // wr: workspace row
   ROW_GUARD(rc, r);
   const int slot = rc.row_slot[r], pos = rc.row_pos[r];
@@ -57,8 +74,61 @@ __global__ __launch_bounds__(64 * ATT_WAVES) void attn_decode_kernel(
 
   // Q^T fragments: lane holds q[head hh][32c + 8g .. +7]; heads beyond the group read
   // the group's last head and are zeroed.
+  constexpr int HALF = DH / 2;
+  const bool last_split = split == n_splits - 1;
   bf16x8 qf[KC];
-  {
+  if (FUSED) {
+    const int hq = hh < G ? hh : G - 1;
+    const int ncol = (Hq + 2 * Hkv) * DH;
+    const float* qsrc = fz.qkv + (size_t)r * ncol + (size_t)(kvh * G + hq) * DH;
+    const float* cs = fz.rope_cos + (size_t)pos * HALF;
+    const float* sn = fz.rope_sin + (size_t)pos * HALF;
+#pragma unroll
+    for (int c = 0; c < KC; ++c) {
+      const int d0 = 32 * c + 8 * g;            // 8 consecutive dims, all in the same half
+      const bool lo = d0 < HALF;
+      const int i0 = lo ? d0 : d0 - HALF;
+      f32x4 a[2] = {f32x4{}, f32x4{}}, b[2] = {f32x4{}, f32x4{}};
+      for (int p = 0; p < fz.n_partials; ++p) {  // same order as rope_append_kernel: p = 0, 1, ...
+        const float* q = qsrc + p * fz.partial_stride;
+        a[0] += *reinterpret_cast<const f32x4*>(q + i0);
+        a[1] += *reinterpret_cast<const f32x4*>(q + i0 + 4);
+        b[0] += *reinterpret_cast<const f32x4*>(q + i0 + HALF);
+        b[1] += *reinterpret_cast<const f32x4*>(q + i0 + HALF + 4);
+      }
+      const f32x4 c4[2] = {*reinterpret_cast<const f32x4*>(cs + i0), *reinterpret_cast<const f32x4*>(cs + i0 + 4)};
+      const f32x4 s4[2] = {*reinterpret_cast<const f32x4*>(sn + i0), *reinterpret_cast<const f32x4*>(sn + i0 + 4)};
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const float av = a[j >> 2][j & 3], bv = b[j >> 2][j & 3], cv = c4[j >> 2][j & 3], sv2 = s4[j >> 2][j & 3];
+        const float rot = lo ? rope_first(av, bv, cv, sv2) : rope_second(av, bv, cv, sv2);
+        qf[c][j] = hh < G ? (bf16_t)rot : (bf16_t)0.f;
+      }
+    }
+    if (last_split && wave == 0) {
+      // the new token: rotated key and value of this KV head, to the page and to LDS
+      const float* ksrc = fz.qkv + (size_t)r * ncol + (size_t)(Hq + kvh) * DH;
+      const float* vsrc = fz.qkv + (size_t)r * ncol + (size_t)(Hq + Hkv + kvh) * DH;
+      const int page = s.block_table[(size_t)slot * s.max_blocks + (pos >> 4)], tin = pos & 15;
+      for (int d = lane; d < DH; d += 64) {
+        const bool lo = d < HALF;
+        const int i = lo ? d : d - HALF;
+        float av = ksrc[i], bv = ksrc[i + HALF], vv = vsrc[d];
+        for (int p = 1; p < fz.n_partials; ++p) {
+          av += ksrc[p * fz.partial_stride + i];
+          bv += ksrc[p * fz.partial_stride + i + HALF];
+          vv += vsrc[p * fz.partial_stride + d];
+        }
+        const float rot = lo ? rope_first(av, bv, cs[i], sn[i]) : rope_second(av, bv, cs[i], sn[i]);
+        const bf16_t kb = (bf16_t)rot, vb = (bf16_t)vv;
+        s_knew[d] = kb;
+        s_vnew[d] = vb;
+        kv_pool[L.at(layer, 0, page, kvh, tin, d)] = kb;
+        kv_pool[L.at(layer, 1, page, kvh, tin, d)] = vb;
+      }
+    }
+    if (last_split) __syncthreads();
+  } else {
     const int hq = hh < G ? hh : G - 1;
     const float* q = q_rot + (size_t)r * Hq * DH + (size_t)(kvh * G + hq) * DH + 8 * g;
     f32x4 qa[KC][2];
@@ -108,6 +178,30 @@ __global__ __launch_bounds__(64 * ATT_WAVES) void attn_decode_kernel(
       __builtin_amdgcn_sched_barrier(0);
 
       const int t0 = t_begin + tile * 32;
+      if (FUSED && last_split && tile == ((pos - t_begin) >> 5)) {
+        // the tile that holds the new token: take its key / value from LDS (the page copy may
+        // not be visible yet); same bf16 values as the page now holds
+        const int pp = ((pos - t_begin) >> 4) & 1, tin = pos & 15;
+#pragma unroll
+        for (int p = 0; p < 2; ++p) {
+          if (p != pp) continue;
+          if (hh == tin) {
+#pragma unroll
+            for (int c = 0; c < KC; ++c)
+#pragma unroll
+              for (int j = 0; j < 8; ++j) kf[p][c][j] = s_knew[32 * c + 8 * g + j];
+          }
+          if ((tin >> 2) == g) {
+#pragma unroll
+            for (int d = 0; d < DT; ++d) {
+              const bf16_t nv = s_vnew[d * 16 + hh];
+#pragma unroll
+              for (int j = 0; j < 4; ++j)
+                if (j == (tin & 3)) vf[p][d][j] = nv;
+            }
+          }
+        }
+      }
       f32x4 sacc[2];
 #pragma unroll
       for (int p = 0; p < 2; ++p) {
@@ -267,24 +361,22 @@ __global__ __launch_bounds__(64 * ATT_WAVES) void attn_decode_kernel(
 
 int attn_split_tokens() { return ATT_SPLIT; }
 
-void launch_attn_decode(hipStream_t st, RowCtx rc, int row_base, Slots s, const float* q_rot, const bf16_t* kv_pool,
+void launch_attn_decode(hipStream_t st, RowCtx rc, int row_base, Slots s, const float* q_rot, bf16_t* kv_pool,
                         KVLayout kvl, int layer, int n_q_heads, bf16_t* out, float* ws, int* counters,
-                        int max_splits, int grid_splits) {
+                        int max_splits, int grid_splits, const float* fused_qkv, int n_partials,
+                        size_t partial_stride, const float* rope_cos, const float* rope_sin) {
   dim3 grid(rc.max_rows, kvl.n_kv_heads, grid_splits), block(64 * ATT_WAVES);
+  AttnFuse fz{fused_qkv, n_partials, partial_stride, rope_cos, rope_sin};
+#define ATT_LAUNCH(DH, F)                                                                                    \
+  hipLaunchKernelGGL((attn_decode_kernel<DH, F>), grid, block, 0, st, rc, row_base, s, q_rot, kv_pool, kvl, layer, \
+                     n_q_heads, out, ws, counters, max_splits, fz)
+  const bool fused = fused_qkv != nullptr;
   switch (kvl.head_dim) {
-    case 32:
-      hipLaunchKernelGGL(attn_decode_kernel<32>, grid, block, 0, st, rc, row_base, s, q_rot, kv_pool, kvl, layer,
-                         n_q_heads, out, ws, counters, max_splits);
-      break;
-    case 64:
-      hipLaunchKernelGGL(attn_decode_kernel<64>, grid, block, 0, st, rc, row_base, s, q_rot, kv_pool, kvl, layer,
-                         n_q_heads, out, ws, counters, max_splits);
-      break;
-    default:
-      hipLaunchKernelGGL(attn_decode_kernel<128>, grid, block, 0, st, rc, row_base, s, q_rot, kv_pool, kvl, layer,
-                         n_q_heads, out, ws, counters, max_splits);
-      break;
+    case 32: if (fused) ATT_LAUNCH(32, true); else ATT_LAUNCH(32, false); break;
+    case 64: if (fused) ATT_LAUNCH(64, true); else ATT_LAUNCH(64, false); break;
+    default: if (fused) ATT_LAUNCH(128, true); else ATT_LAUNCH(128, false); break;
   }
+#undef ATT_LAUNCH
 }
 
 }  // namespace april

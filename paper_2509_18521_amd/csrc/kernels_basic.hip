@@ -394,7 +394,7 @@ __global__ __launch_bounds__(256) void rope_append_kernel(RowCtx rc, Slots s, co
     const int hd = e / half, i = e % half;
     const float a = val(hd * dh + i), b = val(hd * dh + i + half);
     const float c = cs[i], sI = sn[i];
-    const float ra = a * c - b * sI, rb = b * c + a * sI;
+    const float ra = rope_first(a, b, c, sI), rb = rope_second(a, b, c, sI);
     if (hd < Hq) {
       q_rot[(size_t)r * nq + hd * dh + i] = ra;
       q_rot[(size_t)r * nq + hd * dh + i + half] = rb;

@@ -87,3 +87,32 @@ def test_wide_shapes_head_dim_128_gqa4(name):
     shape = ai.reduced(base, n_layers=1, vocab=8192).shape
     w = ai.Workload(name + "_L1", shape, 4, 70, 2, 4, 12, 2.0, 0.5, 3, 12, ai.SAMPLER_GREEDY, 0, 2, base.seed)
     teacher_forced_parity(w, 2, 8)
+
+
+def test_bf16_scheduling_invariance_is_bit_exact():
+    """On the bf16 path too, a rollout's tokens do not depend on how it was scheduled:
+    carried over with resident KV, re-prefilled after its KV was dropped (prefill kernels
+    instead of decode kernels for the same positions), or run with N' = N."""
+    shape = ai.ModelShape(3, 128, 4, 2, 64, 256, 1024)
+    w = ai.Workload("bf16_small", shape, 8, 37, 5, 9, 60, 3.0, 0.6, 3, 60, ai.SAMPLER_GREEDY, 0, 4, 31)
+    weights = ai.make_weights(shape, w.seed)
+    reqs = ai.make_requests(w, ai.requests_needed(w))
+    ctxs = [make_engine(w, weights) for _ in range(3)]
+    try:
+        def drop(ctx, buf):
+            ap().april_buffer_drop_kv(ctx, buf)
+            return buf
+        a = run_gpu(ctxs[0], reqs, w.n_target, w.n_overprovision, w.max_new, w.steps)
+        b = run_gpu(ctxs[1], reqs, w.n_target, w.n_overprovision, w.max_new, w.steps, between=drop)
+        c = run_gpu(ctxs[2], reqs, w.n_target, w.n_target, w.max_new, w.steps)
+        assert sum(g["res"].reprefill_tokens for g in b) > 0
+        assert_schedule_equal(b, a)
+        for g, o in zip(b, a):
+            assert g["tokens"] == o["tokens"] and g["buffer_tokens"] == o["buffer_tokens"]
+        ta = {rid: t for g in a for rid, t in zip(g["ids"], g["tokens"])}
+        tc = {rid: t for g in c for rid, t in zip(g["ids"], g["tokens"])}
+        for rid in set(ta) & set(tc):
+            assert ta[rid] == tc[rid], rid
+    finally:
+        for x in ctxs:
+            ap().april_destroy(x)

@@ -69,6 +69,34 @@ def cpu_baseline(w, weights, reqs, budget_s=20.0):
                        f"{per_roll} generated tokens, one rollout at a time ({dt:.1f} s)")
 
 
+def measured_traffic(workload, kernel_class):
+    """HBM bytes per launch of a kernel class (fetch + write), from the committed summary of
+    the two rocprofv3 --pmc runs over this benchmark's command (already scaled by the copy
+    calibration recorded in the same file); None when no summary covers the class."""
+    path = os.path.join(ROOT, "profiles", f"hbm_traffic_{workload}.txt")
+    try:
+        with open(path) as f:
+            for line in f:
+                parts = line.split()
+                if len(parts) >= 3 and parts[0] == "traffic_bytes_per_launch" and parts[1] == kernel_class:
+                    return float(parts[2])
+    except OSError:
+        pass
+    return None
+
+
+def copy_calibration(n_bytes=1 << 30, reps=3):
+    """A plain device copy of known size, so that a --pmc run of this command also holds
+    the counter reading for known traffic (n_bytes read + n_bytes written per launch)."""
+    import torch
+    src = torch.empty(n_bytes, dtype=torch.uint8, device="cuda").fill_(3)
+    dst = torch.empty_like(src)
+    for _ in range(reps):
+        dst.copy_(src)
+    torch.cuda.synchronize()
+    del src, dst
+
+
 def main():
     p = argparse.ArgumentParser()
     p.add_argument("--gpus", type=int, default=1)
@@ -79,6 +107,8 @@ def main():
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--no-wait-all", action="store_true")
     p.add_argument("--profile-every", type=int, default=16)
+    p.add_argument("--copy-calibration", action="store_true",
+                   help="also run three 1 GiB device copies first (reference dispatches for --pmc counter runs)")
     args = p.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no sharding, no collectives); --gpus must be 1", file=sys.stderr)
@@ -92,6 +122,8 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
         sys.exit(3)
+    if args.copy_calibration:
+        copy_calibration()
     w = ai.WORKLOADS[args.workload]
     if args.layers:
         w = ai.reduced(w, n_layers=args.layers)
@@ -142,6 +174,7 @@ def main():
     sum_ctx = sum(r.dec_sum_ctx for r in res_april)
     kv_tok = info["kv_bytes_per_token"]
     dec_bytes = (sum(max(r.decode_iters - 1, 0) for r in res_april) * info["decode_weight_bytes"]
+                 + sum(r.dec_sum_experts for r in res_april) * info["expert_bytes"]
                  + sum_ctx * kv_tok + sum_live * kv_tok
                  + sum_live * s.d_model * 4 * 2 * (2 * s.n_layers + 1) + sum_live * 8)
     decode_gbs = dec_bytes / decode_time / 1e9 if decode_time > 0 else 0.0
@@ -170,7 +203,8 @@ def main():
         dom = max(timed, key=lambda k: k["total_ms"])
         ach = dom["alg_bytes"] / (dom["total_ms"] * 1e-3) / 1e9
         out["roofline"] = {"kernel": dom["name"], "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS,
-                           "unit": "GB/s", "frac": ach / HBM_PEAK_GBS, "traffic": None,
+                           "unit": "GB/s", "frac": ach / HBM_PEAK_GBS, "traffic": measured_traffic(w.name, dom["name"]),
+                           "alg_bytes_per_launch": dom["alg_bytes"] / dom["launches"],
                            "avg_launch_us": 1e3 * dom["total_ms"] / dom["launches"], "launches_timed": dom["launches"]}
         tot = sum(k["total_ms"] for k in timed)
         out["kernels"] = [{"name": k["name"], "launches": k["launches"], "avg_us": 1e3 * k["total_ms"] / k["launches"],

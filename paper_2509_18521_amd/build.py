@@ -6,7 +6,7 @@ import sys
 PKG = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libapril.so")
-SOURCES = ["engine.hip", "kernels_basic.hip", "kernels_gemm.hip", "kernels_attn.hip", "kernels_moe.hip", "kernels_sample.hip"]
+SOURCES = ["engine.hip", "kernels_basic.hip", "kernels_gemm.hip", "kernels_gemm_tile.hip", "kernels_attn.hip", "kernels_moe.hip", "kernels_sample.hip"]
 FLAGS = ["-O3", "--offload-arch=gfx950", "-fPIC", "-shared", "-std=c++17",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wno-unused-command-line-argument", "-Wno-unused-value", "-Wno-unused-result"]

@@ -121,7 +121,7 @@ struct april_ctx {
   int s_qkv = 1, s_o = 1, s_down = 1;
   size_t qkv_stride = 0, proj_stride = 0;
   // bf16 MFMA attention: split-KV workspace
-  bool attn_mfma = false, fuse_rope = true;
+  bool attn_mfma = false, fuse_rope = true, tile_gemm = true;
   int attn_chunk = 256, attn_max_splits = 1, attn_ws_rows = 0;
   float* attn_ws = nullptr;
   int* attn_counters = nullptr;
@@ -294,23 +294,29 @@ void forward(april_ctx* c, RowCtx rows, RowCtx srows, const int* gather, double 
     else if (c->bf16) launch_add_rmsnorm<bf16_t, true>(st, rc, c->x_res, c->proj, n_part, c->proj_stride, gain, (bf16_t*)out, d, m.rms_eps, gth);
     else launch_add_rmsnorm<float, false>(st, rc, c->x_res, c->proj, n_part, c->proj_stride, gain, (float*)out, d, m.rms_eps, gth);
   };
+  // Prefill rows (hundreds to thousands) go through the LDS-tiled GEMM, which needs no k-split
+  // across workgroups: its consumers then read a single partial.  The choice follows the kind
+  // of pass, never the number of rows, so a rollout's arithmetic does not depend on the batch.
+  const bool tile = c->use_mfma && c->tile_gemm && gather != nullptr;
+  const int sq = tile ? 1 : c->s_qkv, so = tile ? 1 : c->s_o, sd = tile ? 1 : c->s_down, sr = tile ? 1 : c->s_router;
   auto gemm = [&](int kc, RowCtx rc, const void* x, const void* w_plain, const bf16_t* w_s, float* out, int N, int K,
                   int ks, size_t stride, double rowsB) {
     ProfScope p(c, kc, (double)N * K * e + rowsB * K * e + rowsB * N * 4.0, 2.0 * rowsB * N * K);
-    if (c->use_mfma) launch_gemm_mfma(st, rc, (const bf16_t*)x, w_s, out, N, K, ks, stride);
+    if (tile) launch_gemm_tile(st, rc, (const bf16_t*)x, w_s, out, N, K);
+    else if (c->use_mfma) launch_gemm_mfma(st, rc, (const bf16_t*)x, w_s, out, N, K, ks, stride);
     else if (c->bf16) launch_gemm_ref<bf16_t, true>(st, rc, (const bf16_t*)x, (const bf16_t*)w_plain, out, N, K);
     else launch_gemm_ref<float, false>(st, rc, (const float*)x, (const float*)w_plain, out, N, K);
   };
   for (int l = 0; l < m.n_layers; ++l) {
     const LayerW& L = c->layers[l];
-    norm(rows, l == 0 ? 0 : c->s_down, L.attn_norm, c->h_act, nullptr, B, true);
-    gemm(KC_GEMM_QKV, rows, c->h_act, L.wqkv, L.wqkv_s, c->qkv, nqkv, d, c->s_qkv, c->qkv_stride, B);
+    norm(rows, l == 0 ? 0 : sd, L.attn_norm, c->h_act, nullptr, B, true);
+    gemm(KC_GEMM_QKV, rows, c->h_act, L.wqkv, L.wqkv_s, c->qkv, nqkv, d, sq, c->qkv_stride, B);
     // decode iterations: rotary + KV append are done inside the attention kernel
     const bool fuse_rope = c->attn_mfma && c->fuse_rope && gather == nullptr;
     if (!fuse_rope) {
       ProfScope p(c, KC_ROPE, B * (nqkv * 4.0 + nq * 4.0 + 2 * nkv * e), 0);
-      if (c->bf16) launch_rope_append<bf16_t>(st, rows, c->ds, c->qkv, c->s_qkv, c->qkv_stride, c->rope_cos, c->rope_sin, c->q_rot, (bf16_t*)c->kv_pool, c->kvl, l, Hq);
-      else launch_rope_append<float>(st, rows, c->ds, c->qkv, c->s_qkv, c->qkv_stride, c->rope_cos, c->rope_sin, c->q_rot, (float*)c->kv_pool, c->kvl, l, Hq);
+      if (c->bf16) launch_rope_append<bf16_t>(st, rows, c->ds, c->qkv, sq, c->qkv_stride, c->rope_cos, c->rope_sin, c->q_rot, (bf16_t*)c->kv_pool, c->kvl, l, Hq);
+      else launch_rope_append<float>(st, rows, c->ds, c->qkv, sq, c->qkv_stride, c->rope_cos, c->rope_sin, c->q_rot, (float*)c->kv_pool, c->kvl, l, Hq);
     }
     {
       ProfScope p(c, KC_ATTN, C * 2.0 * nkv * e + B * nq * (4.0 + e), 4.0 * C * nq);
@@ -321,17 +327,17 @@ void forward(april_ctx* c, RowCtx rows, RowCtx srows, const int* gather, double 
           sub.max_rows = std::min(c->attn_ws_rows, rows.max_rows - base);
           launch_attn_decode(st, sub, base, c->ds, c->q_rot, (bf16_t*)c->kv_pool, c->kvl, l, Hq,
                              (bf16_t*)c->attn_out, c->attn_ws, c->attn_counters, c->attn_max_splits, gs,
-                             fuse_rope ? c->qkv : nullptr, c->s_qkv, c->qkv_stride, c->rope_cos, c->rope_sin);
+                             fuse_rope ? c->qkv : nullptr, sq, c->qkv_stride, c->rope_cos, c->rope_sin);
         }
       } else if (c->bf16) launch_attn_ref<bf16_t, true>(st, rows, c->ds, c->q_rot, (const bf16_t*)c->kv_pool, c->kvl, l, Hq, (bf16_t*)c->attn_out);
       else launch_attn_ref<float, false>(st, rows, c->ds, c->q_rot, (const float*)c->kv_pool, c->kvl, l, Hq, (float*)c->attn_out);
     }
-    gemm(KC_GEMM_O, rows, c->attn_out, L.wo, L.wo_s, c->proj, d, nq, c->s_o, c->proj_stride, B);
-    norm(rows, c->s_o, L.mlp_norm, c->h_act, nullptr, B, false);
+    gemm(KC_GEMM_O, rows, c->attn_out, L.wo, L.wo_s, c->proj, d, nq, so, c->proj_stride, B);
+    norm(rows, so, L.mlp_norm, c->h_act, nullptr, B, false);
     if (c->moe) {
       const int E = c->n_experts, Fe = c->d_expert, tk = c->top_k_experts;
-      gemm(KC_MOE_ROUTE, rows, c->h_act, nullptr, L.router_s, c->router_out, E, d, c->s_router, c->router_stride, B);
-      launch_moe_route(st, rows, c->router_out, c->s_router, c->router_stride, E, tk, c->moe_ids, c->moe_wts);
+      gemm(KC_MOE_ROUTE, rows, c->h_act, nullptr, L.router_s, c->router_out, E, d, sr, c->router_stride, B);
+      launch_moe_route(st, rows, c->router_out, sr, c->router_stride, E, tk, c->moe_ids, c->moe_wts);
       launch_moe_dispatch(st, rows, c->moe_ids, E, tk, c->moe_cnt, c->moe_base, c->moe_pos, c->moe_src, c->moe_p_cap,
                           rows.ctl == reinterpret_cast<const int2*>(c->d_ctrl) ? c->d_ctrl : nullptr);
       const double hit = std::min<double>(E, B * tk);   // bookkeeping estimate: experts that receive a token
@@ -347,17 +353,18 @@ void forward(april_ctx* c, RowCtx rows, RowCtx srows, const int* gather, double 
     }
     if (c->use_mfma) {
       ProfScope p(c, KC_GEMM_GATEUP, 2.0 * F * d * e + B * d * e + B * F * e, 4.0 * B * F * d);
-      launch_gemm_mfma_swiglu(st, rows, (const bf16_t*)c->h_act, L.wg_s, L.wu_s, (bf16_t*)c->act, F, d);
+      if (tile) launch_gemm_tile_swiglu(st, rows, (const bf16_t*)c->h_act, L.wg_s, L.wu_s, (bf16_t*)c->act, F, d);
+      else launch_gemm_mfma_swiglu(st, rows, (const bf16_t*)c->h_act, L.wg_s, L.wu_s, (bf16_t*)c->act, F, d);
     } else {
       gemm(KC_GEMM_GATEUP, rows, c->h_act, L.wgu, nullptr, c->gu, 2 * F, d, 1, 0, B);
       ProfScope p(c, KC_SILU, B * F * (8.0 + e), 0);
       if (c->bf16) launch_silu_mul<bf16_t, true>(st, rows, c->gu, F, (bf16_t*)c->act);
       else launch_silu_mul<float, false>(st, rows, c->gu, F, (float*)c->act);
     }
-    gemm(KC_GEMM_DOWN, rows, c->act, L.wd, L.wd_s, c->proj, d, F, c->s_down, c->proj_stride, B);
+    gemm(KC_GEMM_DOWN, rows, c->act, L.wd, L.wd_s, c->proj, d, F, sd, c->proj_stride, B);
   }
   const double SB = gather ? (double)srows.max_rows : B;
-  norm(srows, c->s_down, c->final_norm, c->hf, gather, SB, true);
+  norm(srows, sd, c->final_norm, c->hf, gather, SB, true);
   {
     ProfScope p(c, KC_GEMM_LMHEAD, (double)V * d * e + SB * d * e, 2.0 * SB * V * d);
     if (c->use_mfma && c->group_max) launch_gemm_mfma_logits(st, srows, (const bf16_t*)c->hf, c->lm_head_s, c->logits, c->group_max, V, d);
@@ -449,6 +456,8 @@ int april_init(const april_model_cfg* cfg, const april_tensor* weights, int32_t 
   if (moe && !(c->use_mfma && c->attn_mfma)) { delete c; return fail(nullptr, APRIL_EINVAL, "routed experts run on the MFMA path only"); }
   const char* fr = getenv("APRIL_FUSE_ROPE");
   c->fuse_rope = !(fr && !strcmp(fr, "0"));
+  const char* tg = getenv("APRIL_TILE_GEMM");
+  c->tile_gemm = !(tg && !strcmp(tg, "0"));
   const char* gr = getenv("APRIL_GRAPH");
   c->use_graph = !(gr && !strcmp(gr, "0"));
   for (int i = 0; i < KC_COUNT; ++i) c->stats[i] = april_kernel_stat{kKernelNames[i], 0, 0, 0, 0};
@@ -595,7 +604,7 @@ int april_init(const april_model_cfg* cfg, const april_tensor* weights, int32_t 
   HIPTRY(hipStreamSynchronize(c->stream));
 
   // ---- workspaces -----------------------------------------------------------------
-  c->prefill_cap = std::max(g.max_ctx, 4096);
+  c->prefill_cap = std::max(g.max_ctx, 16384);   // rows per prefill chunk: enough tiles to fill the chip
   c->m_cap = ((std::max(c->prefill_cap, S) + 31) / 32) * 32;
   const size_t M = c->m_cap;
   if (c->use_mfma) { c->s_qkv = pick_ksplit(nqkv, d); c->s_o = pick_ksplit(d, nq); c->s_down = pick_ksplit(d, F); }

@@ -1,0 +1,355 @@
+// bf16 MFMA GEMM for tall activations (prefill: hundreds to thousands of rows), gfx950.
+//
+// out[m][n] = sum_k x[m][k] * W[n][k], same operand layouts as the skinny decode GEMM
+// (both operands fragment-tiled for v_mfma_f32_32x32x16_bf16: one 32x16 fragment is 1 KiB of
+// consecutive bytes), but compute-bound, so it is organised around operand reuse:
+//   * a workgroup of WGM x WGN wavefronts owns a (WGM*MTW*32) x (WGN*NTW*32) output tile;
+//     each wavefront keeps MTW x NTW accumulator tiles;
+//   * the k loop advances in stages of BK k-tiles; the fragments of a stage go
+//     global -> registers -> LDS once per workgroup (every fragment is one contiguous 1 KiB
+//     piece; LDS reads are lane-consecutive 16-byte pieces, conflict-free) while the MFMAs of
+//     the previous stage run from the other LDS buffer; one barrier per stage;
+//   * every output element is one accumulator chain over k-tiles 0..K/16-1 in order, whatever
+//     the tile shape or the number of rows: results do not depend on the batch.
+#include "kernels.h"
+
+namespace april {
+
+enum { TEPI_F32 = 0, TEPI_SWIGLU = 1 };
+
+// Epilogue of one wavefront: accumulator tile = out^T (lane l, register e:
+// n = 8*(e/4) + 4*(l/32) + e%4, m = l%32).  nt0: first weight tile (SwiGLU: first feature
+// tile; acc[i] = gate, acc[i + NTW/2] = up), mt0: first activation tile.
+template <int MTW, int NTW, int EPI>
+__device__ inline void tile_epilogue(f32x16 (&acc)[NTW][MTW], int nt0, int mt0, int rows, int n_tiles, int N, int lane,
+                                     float* __restrict__ out, bf16_t* __restrict__ act) {
+  const int mloc = lane & 31, nhalf = (lane >> 5) << 2;
+  if (EPI == TEPI_F32) {
+#pragma unroll
+    for (int i = 0; i < NTW; ++i) {
+      const int nt = nt0 + i;
+      if (nt >= n_tiles) continue;
+#pragma unroll
+      for (int j = 0; j < MTW; ++j) {
+        const int m = (mt0 + j) * 32 + mloc;
+        if (m < rows) {
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            const int n = nt * 32 + 8 * q + nhalf;
+            f32x4 v = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
+            *reinterpret_cast<f32x4*>(out + (size_t)m * N + n) = v;
+          }
+        }
+      }
+    }
+  } else {
+    constexpr int H = NTW / 2;
+#pragma unroll
+    for (int i = 0; i < H; ++i) {
+      const int ft = nt0 + i;
+      if (ft >= n_tiles) continue;
+#pragma unroll
+      for (int j = 0; j < MTW; ++j) {
+        const int m = (mt0 + j) * 32 + mloc;
+        if (m < rows) {
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            const int f = ft * 32 + 8 * q + nhalf;
+            bf16x4 v;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              const float g = acc[i][j][4 * q + e], u = acc[i + H][j][4 * q + e];
+              v[e] = (bf16_t)(g / (1.0f + __expf(-g)) * u);
+            }
+            *reinterpret_cast<bf16x4*>(act + act_index<true>(m, f, N)) = v;
+          }
+        }
+      }
+    }
+  }
+}
+
+template <int WGM, int WGN, int MTW, int NTW, int BK, int EPI>
+__global__ __launch_bounds__(64 * WGM * WGN) __attribute__((amdgpu_waves_per_eu(2)))
+void gemm_tile_kernel(RowCtx rc, const bf16x8* __restrict__ x,
+                                                                   const bf16x8* __restrict__ w0,
+                                                                   const bf16x8* __restrict__ w1,
+                                                                   float* __restrict__ out, bf16_t* __restrict__ act,
+                                                                   int N, int K) {
+  constexpr int NW = WGM * WGN, MT = WGM * MTW, NT = WGN * NTW, FR = MT + NT;
+  constexpr int PER = FR * BK / NW;             // fragments one wavefront stages per stage
+  static_assert(FR * BK % NW == 0 && NW % BK == 0, "staging split");
+  static_assert(EPI != TEPI_SWIGLU || NTW % 2 == 0, "gate/up pairs");
+  __shared__ bf16x8 lds[2][BK][FR][64];
+  const int rows = rows_or_zero(rc);
+  const int m0 = blockIdx.y * MT;
+  if (m0 * 32 >= rows) return;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int wm = wave / WGN, wn = wave % WGN;
+  const int KT = K >> 4;
+  const int m_last = (rows - 1) >> 5;           // last activation tile that holds a live row
+  const int n_tiles = N >> 5;                   // SwiGLU: feature tiles (N = F)
+
+  // Fragment slot t of a stage: t < MT activation tile m0 + t, else weight slot t - MT.
+  // Weight slot i belongs to wavefront column i / NTW; plain: tile n0 + i; SwiGLU: the first
+  // half of a wavefront's slots are gate tiles, the second half the up tiles of the same
+  // features.  Tiles past the end are clamped for the loads and never stored.
+  auto slot_base = [&](int t) -> const bf16x8* {
+    if (t < MT) {
+      int mt = m0 + t;
+      if (mt > m_last) mt = m_last;
+      return x + (size_t)mt * KT * 64;
+    }
+    const int i = t - MT;
+    if (EPI == TEPI_SWIGLU) {
+      constexpr int H = NTW / 2;
+      const int col = i / NTW, ii = i % NTW;
+      int f = blockIdx.x * (NT / 2) + col * H + (ii < H ? ii : ii - H);
+      if (f >= n_tiles) f = n_tiles - 1;
+      return (ii < H ? w0 : w1) + (size_t)f * KT * 64;
+    }
+    int nt = blockIdx.x * NT + i;
+    if (nt >= n_tiles) nt = n_tiles - 1;
+    return w0 + (size_t)nt * KT * 64;
+  };
+
+  // staging: wavefront w moves k-tile (w % BK) of the slots t = w / BK + (NW / BK) * u
+  const int skk = wave % BK, st0 = wave / BK;
+  const bf16x8* src[PER];
+#pragma unroll
+  for (int u = 0; u < PER; ++u) src[u] = slot_base(st0 + (NW / BK) * u) + lane;
+  bf16x8 stg[PER];
+  auto stage_load = [&](int s) {
+    const int kt = s * BK + skk;
+    const bool live = kt < KT;                  // a k-tile past the end contributes zeros
+    const size_t off = (size_t)(live ? kt : KT - 1) * 64;
+#pragma unroll
+    for (int u = 0; u < PER; ++u) {
+      const bf16x8 v = src[u][off];
+      stg[u] = live ? v : bf16x8{};
+    }
+  };
+  auto stage_store = [&](int buf) {
+#pragma unroll
+    for (int u = 0; u < PER; ++u) lds[buf][skk][st0 + (NW / BK) * u][lane] = stg[u];
+  };
+
+  f32x16 acc[NTW][MTW];
+#pragma unroll
+  for (int i = 0; i < NTW; ++i)
+#pragma unroll
+    for (int j = 0; j < MTW; ++j) acc[i][j] = f32x16{};
+
+  const int n_stages = (KT + BK - 1) / BK;
+  stage_load(0);
+  stage_store(0);
+  __syncthreads();
+  for (int s = 0; s < n_stages; ++s) {
+    const int buf = s & 1;
+    const bool more = s + 1 < n_stages;
+    if (more) stage_load(s + 1);
+    // operand fragments of k-tile kk+1 are read from LDS while the MFMAs of k-tile kk run
+    bf16x8 a[2][NTW], b[2][MTW];
+#pragma unroll
+    for (int i = 0; i < NTW; ++i) a[0][i] = lds[buf][0][MT + wn * NTW + i][lane];
+#pragma unroll
+    for (int j = 0; j < MTW; ++j) b[0][j] = lds[buf][0][wm * MTW + j][lane];
+#pragma unroll
+    for (int kk = 0; kk < BK; ++kk) {
+      const int cur = kk & 1, nxt = cur ^ 1;
+      if (kk + 1 < BK) {
+#pragma unroll
+        for (int i = 0; i < NTW; ++i) a[nxt][i] = lds[buf][kk + 1][MT + wn * NTW + i][lane];
+#pragma unroll
+        for (int j = 0; j < MTW; ++j) b[nxt][j] = lds[buf][kk + 1][wm * MTW + j][lane];
+      }
+#pragma unroll
+      for (int i = 0; i < NTW; ++i)
+#pragma unroll
+        for (int j = 0; j < MTW; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[cur][i], b[cur][j], acc[i][j], 0, 0, 0);
+    }
+    if (more) stage_store(buf ^ 1);
+    __syncthreads();
+  }
+
+  tile_epilogue<MTW, NTW, EPI>(acc, blockIdx.x * (EPI == TEPI_SWIGLU ? NT / 2 : NT) + wn * (EPI == TEPI_SWIGLU ? NTW / 2 : NTW),
+                               m0 + wm * MTW, rows, n_tiles, N, lane, out, act);
+}
+
+// One wavefront-wide copy of 64 x 16 bytes from global memory (a per-lane address) to LDS
+// (a wavefront-uniform base; lane l lands at base + 16*l).  Device pass only: the host pass
+// has no such instruction to type-check.
+__device__ inline void copy_fragment_to_lds(const bf16x8* src_lane, bf16x8* lds_base) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  __builtin_amdgcn_global_load_lds(src_lane, lds_base, 16, 0, 0);
+#else
+  (void)src_lane; (void)lds_base;
+#endif
+}
+template <int LEFT>
+__device__ inline void wait_vector_memory() {   // until at most LEFT vector-memory operations are outstanding
+#if defined(__HIP_DEVICE_COMPILE__)
+  // s_waitcnt with the expcnt and lgkmcnt fields all-ones: only vmcnt is waited for
+  __builtin_amdgcn_s_waitcnt(0x0f70 | (LEFT & 15) | ((LEFT >> 4) << 14));
+#endif
+}
+
+// Same tiling with the stage fragments copied global -> LDS by the memory pipeline itself
+// (global_load_lds_dwordx4: each lane's 16 bytes land at consecutive LDS addresses, which is
+// exactly the fragment layout), through a ring of R stage buffers.  Nothing is staged in
+// registers, so R - 1 stages of loads stay in flight behind the MFMAs.  Hand-placed waits:
+// the copies of stage s are this wavefront's oldest outstanding vector-memory operations, so
+// "at most (R - 2) stages still outstanding" means stage s has landed; the barrier that
+// follows makes that true for every wavefront's share and also says everyone has finished
+// reading the buffer that the next copies overwrite.  Requires K % (16 * BK) == 0.
+template <int WGM, int WGN, int MTW, int NTW, int BK, int R, int EPI>
+__global__ __launch_bounds__(64 * WGM * WGN) __attribute__((amdgpu_waves_per_eu(2)))
+void gemm_tile_dma_kernel(RowCtx rc, const bf16x8* __restrict__ x, const bf16x8* __restrict__ w0,
+                          const bf16x8* __restrict__ w1, float* __restrict__ out, bf16_t* __restrict__ act, int N,
+                          int K) {
+  constexpr int NW = WGM * WGN, MT = WGM * MTW, NT = WGN * NTW, FR = MT + NT;
+  constexpr int PER = FR * BK / NW;
+  static_assert(FR * BK % NW == 0 && NW % BK == 0, "staging split");
+  static_assert(EPI != TEPI_SWIGLU || NTW % 2 == 0, "gate/up pairs");
+  static_assert(R >= 3 && (R - 2) * PER < 64, "ring depth");
+  __shared__ bf16x8 lds[R][BK][FR][64];
+  const int bx = blockIdx.x, by = blockIdx.y;
+  const int rows = rows_or_zero(rc);
+  const int m0 = by * MT;
+  if (m0 * 32 >= rows) return;
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int wm = wave / WGN, wn = wave % WGN;
+  const int KT = K >> 4;
+  const int m_last = (rows - 1) >> 5;
+  const int n_tiles = N >> 5;
+  auto slot_base = [&](int t) -> const bf16x8* {
+    if (t < MT) {
+      int mt = m0 + t;
+      if (mt > m_last) mt = m_last;
+      return x + (size_t)mt * KT * 64;
+    }
+    const int i = t - MT;
+    if (EPI == TEPI_SWIGLU) {
+      constexpr int H = NTW / 2;
+      const int col = i / NTW, ii = i % NTW;
+      int f = bx * (NT / 2) + col * H + (ii < H ? ii : ii - H);
+      if (f >= n_tiles) f = n_tiles - 1;
+      return (ii < H ? w0 : w1) + (size_t)f * KT * 64;
+    }
+    int nt = bx * NT + i;
+    if (nt >= n_tiles) nt = n_tiles - 1;
+    return w0 + (size_t)nt * KT * 64;
+  };
+  const int skk = wave % BK, st0 = wave / BK;
+  const bf16x8* src[PER];
+#pragma unroll
+  for (int u = 0; u < PER; ++u) src[u] = slot_base(st0 + (NW / BK) * u) + lane;
+  const int n_stages = KT / BK;
+  auto issue = [&](int s) {
+    const size_t off = (size_t)(s * BK + skk) * 64;
+    const int slot = s % R;
+#pragma unroll
+    for (int u = 0; u < PER; ++u)
+      copy_fragment_to_lds(src[u] + off, &lds[slot][skk][st0 + (NW / BK) * u][0]);
+  };
+
+  f32x16 acc[NTW][MTW];
+#pragma unroll
+  for (int i = 0; i < NTW; ++i)
+#pragma unroll
+    for (int j = 0; j < MTW; ++j) acc[i][j] = f32x16{};
+
+#pragma unroll
+  for (int r = 0; r < R - 1; ++r)
+    if (r < n_stages) issue(r);
+  for (int s = 0; s < n_stages; ++s) {
+    // wait for this wavefront's copies of stage s (s_waitcnt vmcnt only: expcnt/lgkmcnt fields all-ones)
+    constexpr int LEFT = (R - 2) * PER;
+    if (s + R - 2 < n_stages) wait_vector_memory<LEFT>();
+    else wait_vector_memory<0>();
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    if (s + R - 1 < n_stages) issue(s + R - 1);
+    const int slot = s % R;
+    bf16x8 a[2][NTW], b[2][MTW];
+#pragma unroll
+    for (int i = 0; i < NTW; ++i) a[0][i] = lds[slot][0][MT + wn * NTW + i][lane];
+#pragma unroll
+    for (int j = 0; j < MTW; ++j) b[0][j] = lds[slot][0][wm * MTW + j][lane];
+#pragma unroll
+    for (int kk = 0; kk < BK; ++kk) {
+      const int cur = kk & 1, nxt = cur ^ 1;
+      if (kk + 1 < BK) {
+#pragma unroll
+        for (int i = 0; i < NTW; ++i) a[nxt][i] = lds[slot][kk + 1][MT + wn * NTW + i][lane];
+#pragma unroll
+        for (int j = 0; j < MTW; ++j) b[nxt][j] = lds[slot][kk + 1][wm * MTW + j][lane];
+      }
+#pragma unroll
+      for (int i = 0; i < NTW; ++i)
+#pragma unroll
+        for (int j = 0; j < MTW; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[cur][i], b[cur][j], acc[i][j], 0, 0, 0);
+      if (kk + 1 < BK) {          // issue order: the LDS reads of k-tile kk+1, then the MFMAs of kk
+        __builtin_amdgcn_sched_group_barrier(0x100, NTW + MTW, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, NTW * MTW, 0);
+      }
+    }
+    asm volatile("" ::: "memory");
+  }
+  tile_epilogue<MTW, NTW, EPI>(acc, bx * (EPI == TEPI_SWIGLU ? NT / 2 : NT) + wn * (EPI == TEPI_SWIGLU ? NTW / 2 : NTW),
+                               m0 + wm * MTW, rows, n_tiles, N, lane, out, act);
+}
+
+// Tile shapes.  WIDE: 256 x 256 outputs on 8 wavefronts (2 per SIMD, each 128 x 64), ring of
+// 4 stages of 32 values of k (128 KiB LDS).  NARROW: 256 x 128 on 4 wavefronts, ring of 3
+// (72 KiB, two workgroups per CU) - for few or ragged weight tiles and for short batches.
+// REGS: register-staged fallback for K not a multiple of 32.  Measured on MI355X, 8192 x
+// (2 x 14336) x 4096 fused gate/up: REGS 0.84, NARROW 0.99, WIDE 1.03 PFLOP/s.  The choice
+// changes no result (see the header comment).
+#define TILE_WIDE(EPI) gemm_tile_dma_kernel<2, 4, 4, 2, 2, 4, EPI>
+#define TILE_NARROW(EPI) gemm_tile_dma_kernel<2, 2, 4, 2, 2, 3, EPI>
+#define TILE_REGS(EPI) gemm_tile_kernel<2, 2, 4, 2, 2, EPI>
+
+// units: weight tiles (plain) or feature tiles (SwiGLU); per_wide: units per WIDE workgroup
+static bool wide_tile(int units, int per_wide, int m_tiles) {
+  const int wgs = ceil_div(units, per_wide) * ceil_div(m_tiles, 8);
+  return wgs >= 128 && ceil_div(units, per_wide) * per_wide * 20 <= units * 23;   // <= 15 % padding
+}
+
+void launch_gemm_tile(hipStream_t st, RowCtx rc, const bf16_t* x, const bf16_t* Wp, float* out, int N, int K) {
+  const int n_tiles = N >> 5, m_tiles = ceil_div(rc.max_rows, 32);
+  const bf16x8* xv = reinterpret_cast<const bf16x8*>(x);
+  const bf16x8* wv = reinterpret_cast<const bf16x8*>(Wp);
+  if (K % 32 != 0) {
+    dim3 grid(ceil_div(n_tiles, 4), ceil_div(m_tiles, 8));
+    hipLaunchKernelGGL((TILE_REGS(TEPI_F32)), grid, dim3(256), 0, st, rc, xv, wv, nullptr, out, nullptr, N, K);
+  } else if (wide_tile(n_tiles, 8, m_tiles)) {
+    dim3 grid(ceil_div(n_tiles, 8), ceil_div(m_tiles, 8));
+    hipLaunchKernelGGL((TILE_WIDE(TEPI_F32)), grid, dim3(512), 0, st, rc, xv, wv, nullptr, out, nullptr, N, K);
+  } else {
+    dim3 grid(ceil_div(n_tiles, 4), ceil_div(m_tiles, 8));
+    hipLaunchKernelGGL((TILE_NARROW(TEPI_F32)), grid, dim3(256), 0, st, rc, xv, wv, nullptr, out, nullptr, N, K);
+  }
+}
+
+void launch_gemm_tile_swiglu(hipStream_t st, RowCtx rc, const bf16_t* x, const bf16_t* Wg, const bf16_t* Wu,
+                             bf16_t* act, int F, int K) {
+  const int f_tiles = F >> 5, m_tiles = ceil_div(rc.max_rows, 32);
+  const bf16x8* xv = reinterpret_cast<const bf16x8*>(x);
+  const bf16x8* gv = reinterpret_cast<const bf16x8*>(Wg);
+  const bf16x8* uv = reinterpret_cast<const bf16x8*>(Wu);
+  if (K % 32 != 0) {
+    dim3 grid(ceil_div(f_tiles, 2), ceil_div(m_tiles, 8));
+    hipLaunchKernelGGL((TILE_REGS(TEPI_SWIGLU)), grid, dim3(256), 0, st, rc, xv, gv, uv, nullptr, act, F, K);
+  } else if (wide_tile(f_tiles, 4, m_tiles)) {
+    dim3 grid(ceil_div(f_tiles, 4), ceil_div(m_tiles, 8));
+    hipLaunchKernelGGL((TILE_WIDE(TEPI_SWIGLU)), grid, dim3(512), 0, st, rc, xv, gv, uv, nullptr, act, F, K);
+  } else {
+    dim3 grid(ceil_div(f_tiles, 2), ceil_div(m_tiles, 8));
+    hipLaunchKernelGGL((TILE_NARROW(TEPI_SWIGLU)), grid, dim3(256), 0, st, rc, xv, gv, uv, nullptr, act, F, K);
+  }
+}
+
+}  // namespace april

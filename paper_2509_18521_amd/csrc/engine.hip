@@ -637,8 +637,12 @@ int april_init(const april_model_cfg* cfg, const april_tensor* weights, int32_t 
   if (c->attn_mfma) {
     c->attn_chunk = attn_split_tokens();
     c->attn_max_splits = ceil_div(g.max_ctx, c->attn_chunk);
-    c->attn_ws_rows = std::min<int>(c->m_cap, std::max(512, (S + 31) / 32 * 32));
     const size_t rec = 32 + (size_t)16 * g.head_dim;
+    // rows per attention launch: all decode rows; prefill chunks go in pieces of up to 4096 rows
+    // (fewer, fuller launches) as long as the split workspace stays within 1 GiB
+    const size_t ws_row_bytes = (size_t)g.n_kv_heads * c->attn_max_splits * rec * sizeof(float);
+    const int by_bytes = (int)std::min<size_t>(4096, ((size_t)1 << 30) / ws_row_bytes) / 32 * 32;
+    c->attn_ws_rows = std::min<int>(c->m_cap, std::max({512, (S + 31) / 32 * 32, by_bytes}));
     TRY(dev_alloc(c, &c->attn_ws, (size_t)c->attn_ws_rows * g.n_kv_heads * c->attn_max_splits * rec, false));
     TRY(dev_alloc(c, &c->attn_counters, (size_t)c->attn_ws_rows * g.n_kv_heads, true));
   }

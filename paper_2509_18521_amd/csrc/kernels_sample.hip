@@ -55,9 +55,19 @@ struct SampleShared {
 
 // Key of the k-th largest of vals[0..n) (k <= n): 4 radix passes of 8 bits.  On return
 // sh.prefix = that key, sh.krem = how many entries equal to it belong to the top k,
-// sh.ntie = how many entries equal it.  All threads must call.
+// sh.ntie = how many entries equal it.  All threads must call.  Up to 4 keys per thread are
+// kept in registers across the passes (n <= 4 * SAMPLE_THREADS reads memory once).
 __device__ inline void block_kth_largest(const float* vals, int n, int k, SampleShared& sh) {
   const int tid = threadIdx.x;
+  const bool cached = n <= 4 * SAMPLE_THREADS;
+  unsigned ck[4] = {0u, 0u, 0u, 0u};
+  if (cached) {
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int i = tid + q * SAMPLE_THREADS;
+      if (i < n) ck[q] = f2key(vals[i]);
+    }
+  }
   if (tid == 0) { sh.prefix = 0u; sh.krem = (unsigned)k; }
   for (int pass = 0; pass < 4; ++pass) {
     const int shift = 24 - 8 * pass;
@@ -65,22 +75,43 @@ __device__ inline void block_kth_largest(const float* vals, int n, int k, Sample
     if (tid < 256) sh.hist[tid] = 0u;
     __syncthreads();
     const unsigned prefix = sh.prefix;
-    for (int i = tid; i < n; i += SAMPLE_THREADS) {
-      const unsigned key = f2key(vals[i]);
-      if ((key & mask_hi) == prefix) atomicAdd(&sh.hist[(key >> shift) & 255u], 1u);
+    if (cached) {
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+        if (tid + q * SAMPLE_THREADS < n && (ck[q] & mask_hi) == prefix) atomicAdd(&sh.hist[(ck[q] >> shift) & 255u], 1u);
+    } else {
+      for (int i = tid; i < n; i += SAMPLE_THREADS) {
+        const unsigned key = f2key(vals[i]);
+        if ((key & mask_hi) == prefix) atomicAdd(&sh.hist[(key >> shift) & 255u], 1u);
+      }
     }
     __syncthreads();
-    if (tid == 0) {
-      unsigned cum = 0u;
+    if (tid < 64) {
+      // Wavefront 0 walks the histogram from the top: lane l owns bins 4l..4l+3; `above` =
+      // entries in higher bins.  The one lane with above < krem <= above + own holds the digit.
       const unsigned krem = sh.krem;
-      for (int b = 255; b >= 0; --b) {
-        if (cum + sh.hist[b] >= krem) {
-          sh.prefix = prefix | ((unsigned)b << shift);
-          sh.krem = krem - cum;
-          sh.ntie = sh.hist[b];
-          break;
+      const unsigned h0 = sh.hist[4 * tid], h1 = sh.hist[4 * tid + 1], h2 = sh.hist[4 * tid + 2], h3 = sh.hist[4 * tid + 3];
+      const unsigned own = h0 + h1 + h2 + h3;
+      unsigned suf = own;                                   // inclusive suffix sum over lanes >= tid
+#pragma unroll
+      for (int off = 1; off < 64; off <<= 1) {
+        const unsigned o = __shfl_down(suf, off, 64);
+        if (tid + off < 64) suf += o;
+      }
+      const unsigned above = suf - own;
+      if (above < krem && krem <= above + own) {
+        unsigned cum = above;
+        const unsigned hs[4] = {h3, h2, h1, h0};
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          if (cum + hs[q] >= krem) {
+            sh.prefix = prefix | ((unsigned)(4 * tid + 3 - q) << shift);
+            sh.krem = krem - cum;
+            sh.ntie = hs[q];
+            break;
+          }
+          cum += hs[q];
         }
-        cum += sh.hist[b];
       }
     }
     __syncthreads();
@@ -228,7 +259,10 @@ __global__ __launch_bounds__(SAMPLE_THREADS) void sample_kernel(RowCtx rc, Slots
       if (rank < k) { sh.sort_logit[rank] = lg[mi]; sh.sort_idx[rank] = mi; }
     }
     __syncthreads();
-    if (tid == 0) {
+    if (tid < 64) {
+      // Wavefront 0: lane j holds candidate j (k <= 64).  fp64 softmax over the candidates and
+      // its running sum; the token is the first candidate whose cumulative probability
+      // exceeds the uniform draw, the last candidate if none does.
       const int n = n_cand < k ? n_cand : k;
       const unsigned long long rid = (unsigned long long)req;
       const unsigned w0 = philox4x32_10_word0((unsigned)(rid & 0xFFFFFFFFull), (unsigned)(rid >> 32),
@@ -237,15 +271,18 @@ __global__ __launch_bounds__(SAMPLE_THREADS) void sample_kernel(RowCtx rc, Slots
       const double u = (double)(w0 >> 8) * (1.0 / 16777216.0);
       const double T = (double)sc.temperature;
       const double z0 = (double)sh.sort_logit[0] / T;
-      double sum = 0.0;
-      for (int j = 0; j < n; ++j) sum += exp((double)sh.sort_logit[j] / T - z0);
-      double c = 0.0;
-      int choice = sh.sort_idx[n - 1];
-      for (int j = 0; j < n; ++j) {
-        c += exp((double)sh.sort_logit[j] / T - z0) / sum;
-        if (c > u) { choice = sh.sort_idx[j]; break; }
+      const double e = tid < n ? exp((double)sh.sort_logit[tid < n ? tid : 0] / T - z0) : 0.0;
+      double sum = e;
+#pragma unroll
+      for (int off = 32; off > 0; off >>= 1) sum += __shfl_xor(sum, off, 64);
+      double c = e / sum;                                   // inclusive prefix sum over lanes <= tid
+#pragma unroll
+      for (int off = 1; off < 64; off <<= 1) {
+        const double o = __shfl_up(c, off, 64);
+        if (tid >= off) c += o;
       }
-      sh.choice = choice;
+      const unsigned long long hit = __ballot(tid < n && c > u);
+      if (tid == 0) sh.choice = sh.sort_idx[hit ? __ffsll((long long)hit) - 1 : n - 1];
     }
     __syncthreads();
   }

@@ -326,7 +326,7 @@ void forward(april_ctx* c, RowCtx rows, RowCtx srows, const int* gather, double 
           RowCtx sub = rows;
           sub.max_rows = std::min(c->attn_ws_rows, rows.max_rows - base);
           launch_attn_decode(st, sub, base, c->ds, c->q_rot, (bf16_t*)c->kv_pool, c->kvl, l, Hq,
-                             (bf16_t*)c->attn_out, c->attn_ws, c->attn_counters, c->attn_max_splits, gs,
+                             (bf16_t*)c->attn_out, c->attn_ws, c->attn_max_splits, gs,
                              fuse_rope ? c->qkv : nullptr, sq, c->qkv_stride, c->rope_cos, c->rope_sin);
         }
       } else if (c->bf16) launch_attn_ref<bf16_t, true>(st, rows, c->ds, c->q_rot, (const bf16_t*)c->kv_pool, c->kvl, l, Hq, (bf16_t*)c->attn_out);
@@ -470,8 +470,9 @@ int april_init(const april_model_cfg* cfg, const april_tensor* weights, int32_t 
 
   // ---- weights ------------------------------------------------------------------
   const size_t e = c->esz;
-  size_t stage_bytes = std::max<size_t>((size_t)V * d, (size_t)2 * F * d) * e;
-  if (moe) stage_bytes = std::max<size_t>(stage_bytes, (size_t)g.n_experts * g.d_expert_ffn * d * e);
+  // staging buffer for one matrix at a time: the largest of every matrix that goes through it
+  size_t stage_bytes = std::max({(size_t)V * d, (size_t)F * d, (size_t)nqkv * d, (size_t)d * nq}) * e;
+  if (moe) stage_bytes = std::max({stage_bytes, (size_t)g.n_experts * g.d_expert_ffn * d * e, (size_t)g.n_experts * d * e});
   void* stage = nullptr;
   if (c->use_mfma) HIPTRY(hipMalloc(&stage, stage_bytes));
   auto free_stage = [&]() { if (stage) { hipFree(stage); stage = nullptr; } };
@@ -644,7 +645,6 @@ int april_init(const april_model_cfg* cfg, const april_tensor* weights, int32_t 
     const int by_bytes = (int)std::min<size_t>(4096, ((size_t)1 << 30) / ws_row_bytes) / 32 * 32;
     c->attn_ws_rows = std::min<int>(c->m_cap, std::max({512, (S + 31) / 32 * 32, by_bytes}));
     TRY(dev_alloc(c, &c->attn_ws, (size_t)c->attn_ws_rows * g.n_kv_heads * c->attn_max_splits * rec, false));
-    TRY(dev_alloc(c, &c->attn_counters, (size_t)c->attn_ws_rows * g.n_kv_heads, true));
   }
   TRY(dev_alloc(c, &c->rope_cos, (size_t)g.max_ctx * g.head_dim / 2, false));
   TRY(dev_alloc(c, &c->rope_sin, (size_t)g.max_ctx * g.head_dim / 2, false));
@@ -1093,7 +1093,8 @@ int april_rollout_step(april_ctx* c, const april_request* new_reqs, int32_t n_ne
       HIPCHK(c, hipStreamSynchronize(st));
     }
     // iteration 1: resident rollouts decode, the others are (re-)prefilled
-    launch_sched(st, c->d_ctrl, c->ds, c->d_row_slot, c->d_row_pos, c->d_free_stack, blk, 0);
+    const int NOCAP = 0x7fffffff;
+    launch_sched(st, c->d_ctrl, c->ds, c->d_row_slot, c->d_row_pos, c->d_free_stack, blk, 0, NOCAP, NOCAP);
     if (n_resident > 0) {
       drc.max_rows = n_resident;
       forward(c, drc, drc, nullptr, n_resident, 0);
@@ -1138,31 +1139,46 @@ int april_rollout_step(april_ctx* c, const april_request* new_reqs, int32_t n_ne
     t_prefill = now_s() - t0;
 
     // iterations 2..: pure decode
-    c->step_max_ctx = decode_max_ctx;
     const double t1 = now_s();
-    drc.max_rows = ((int)inflight.size() + 31) / 32 * 32;
-    if (drc.max_rows > c->n_slots) drc.max_rows = c->n_slots;
-    // the iteration graph for this geometry (captured once, replayed every iteration)
-    hipGraphExec_t iter_exec = nullptr;
-    if (c->use_graph) {
-      const int gs_key = c->attn_mfma ? std::min(c->attn_max_splits, std::max(1, ceil_div(c->step_max_ctx, c->attn_chunk))) : 0;
-      // round the split bound up so that steps with slightly different limits share a graph
-      const std::pair<int, int> key{drc.max_rows, gs_key};
+    // What the host knows about iteration `it` without asking the device: a rollout with r
+    // tokens left is live in iterations 1..r, and its context then is at most prompt + generated
+    // + it.  (EOS and preemption only take rows away.)  Each iteration is launched with grids
+    // sized for these bounds; the scheduler kernel checks them.
+    std::vector<std::pair<int, int>> by_rem;          // (tokens left, prompt + generated) per rollout
+    for (int s : inflight) by_rem.push_back({c->slots[s].limit - c->slots[s].gen, c->slots[s].prompt_len + c->slots[s].gen});
+    std::sort(by_rem.begin(), by_rem.end(), [](const auto& a, const auto& b) { return a.first > b.first; });
+    std::vector<int> ctx_prefix_max(by_rem.size() + 1, 0);   // max base over the j longest-running rollouts
+    for (size_t j = 0; j < by_rem.size(); ++j) ctx_prefix_max[j + 1] = std::max(ctx_prefix_max[j], by_rem[j].second);
+    size_t n_alive = by_rem.size();
+    auto bounds_at = [&](int it, int* rows_cap, int* ctx_cap) {
+      while (n_alive > 0 && by_rem[n_alive - 1].first < it) --n_alive;     // `it` only grows
+      int rb = ((int)n_alive + 31) / 32 * 32;
+      if (rb < 32) rb = 32;
+      if (rb > c->n_slots) rb = c->n_slots;
+      *rows_cap = rb;
+      *ctx_cap = std::min(c->max_ctx, ctx_prefix_max[n_alive] + it);
+    };
+    // one captured graph per (row bound, KV-split bound), replayed by every iteration that fits it
+    auto graph_for = [&](int rows_cap, int gs, int ctx_grid, hipGraphExec_t* out) -> int {
+      const std::pair<int, int> key{rows_cap, gs};
       auto it = c->iter_graphs.find(key);
       if (it == c->iter_graphs.end()) {
         hipGraph_t graph = nullptr;
         c->prof_now = false;
+        RowCtx grc{c->d_row_slot, c->d_row_pos, reinterpret_cast<const int2*>(c->d_ctrl), rows_cap};
+        c->step_max_ctx = ctx_grid;
         HIPCHK(c, hipStreamBeginCapture(st, hipStreamCaptureModeThreadLocal));
-        launch_sched(st, c->d_ctrl, c->ds, c->d_row_slot, c->d_row_pos, c->d_free_stack, blk, 0);
-        forward(c, drc, drc, nullptr, 0, 0);
+        launch_sched(st, c->d_ctrl, c->ds, c->d_row_slot, c->d_row_pos, c->d_free_stack, blk, 0, rows_cap, ctx_grid);
+        forward(c, grc, grc, nullptr, 0, 0);
         HIPCHK(c, hipStreamEndCapture(st, &graph));
         hipGraphExec_t exec = nullptr;
         HIPCHK(c, hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0));
         HIPCHK(c, hipGraphDestroy(graph));
         it = c->iter_graphs.emplace(key, exec).first;
       }
-      iter_exec = it->second;
-    }
+      *out = it->second;
+      return APRIL_OK;
+    };
     bool stopped = false;
     int launched = 1;
     const int chunk = 32;
@@ -1171,14 +1187,22 @@ int april_rollout_step(april_ctx* c, const april_request* new_reqs, int32_t n_ne
       if (todo < 0) todo = 0;
       for (int k = 0; k < todo; ++k) {
         const int it = launched + k + 1;
+        int rows_cap = 0, ctx_cap = 0;
+        bounds_at(it, &rows_cap, &ctx_cap);
+        const int gs = c->attn_mfma ? std::min(c->attn_max_splits, std::max(1, ceil_div(ctx_cap, c->attn_chunk))) : 1;
+        const int ctx_grid = c->attn_mfma ? gs * c->attn_chunk : c->max_ctx;
         c->prof_now = c->prof_every > 0 && (it % c->prof_every) == 0 && c->snaps_used < c->snaps_cap;
-        if (iter_exec && !c->prof_now) {
-          HIPCHK(c, hipGraphLaunch(iter_exec, st));
+        if (c->use_graph && !c->prof_now) {
+          hipGraphExec_t exec = nullptr;
+          { int rc = graph_for(rows_cap, gs, ctx_grid, &exec); if (rc != APRIL_OK) return rc; }
+          HIPCHK(c, hipGraphLaunch(exec, st));
           continue;
         }
+        drc.max_rows = rows_cap;
+        c->step_max_ctx = ctx_grid;
         {
           ProfScope p(c, KC_SCHED, 0, 0);
-          launch_sched(st, c->d_ctrl, c->ds, c->d_row_slot, c->d_row_pos, c->d_free_stack, blk, 0);
+          launch_sched(st, c->d_ctrl, c->ds, c->d_row_slot, c->d_row_pos, c->d_free_stack, blk, 0, rows_cap, ctx_grid);
         }
         double B = 0, C = 0;
         if (c->prof_now) {
@@ -1191,15 +1215,16 @@ int april_rollout_step(april_ctx* c, const april_request* new_reqs, int32_t n_ne
         c->prof_now = false;
       }
       launched += todo;
-      launch_sched(st, c->d_ctrl, c->ds, c->d_row_slot, c->d_row_pos, c->d_free_stack, blk, 1);
+      launch_sched(st, c->d_ctrl, c->ds, c->d_row_slot, c->d_row_pos, c->d_free_stack, blk, 1, NOCAP, NOCAP);
       HIPCHK(c, hipMemcpyAsync(c->h_ctrl, c->d_ctrl, sizeof(Ctrl), hipMemcpyDeviceToHost, st));
       HIPCHK(c, hipStreamSynchronize(st));
+      if (c->h_ctrl->error & 2) return fail(c, APRIL_EDEVICE, "an iteration met more rows or a longer context than the host sized it for");
       if (c->h_ctrl->error) return fail(c, APRIL_ENOMEM, "KV page stack underflow on device");
       stopped = c->h_ctrl->stop != 0;
       if (!stopped && launched >= T_bound) {
         // every rollout has run to its limit or was preempted: a full scheduler pass ends the
         // step (nothing live, nothing waiting for prefill)
-        launch_sched(st, c->d_ctrl, c->ds, c->d_row_slot, c->d_row_pos, c->d_free_stack, blk, 0);
+        launch_sched(st, c->d_ctrl, c->ds, c->d_row_slot, c->d_row_pos, c->d_free_stack, blk, 0, NOCAP, NOCAP);
         HIPCHK(c, hipMemcpyAsync(c->h_ctrl, c->d_ctrl, sizeof(Ctrl), hipMemcpyDeviceToHost, st));
         HIPCHK(c, hipStreamSynchronize(st));
         stopped = c->h_ctrl->stop != 0;

@@ -36,8 +36,10 @@ __device__ inline float rope_second(float a, float b, float c, float s) { return
 
 // --- scheduler / allocator -------------------------------------------------
 // check_only = 1: only the "N complete => stop" test (end of a chunk of iterations).
+// row_cap / ctx_cap: the bounds the host sized this iteration's launches for (live rows, longest
+// context); exceeding one sets error bit 2 in the control block and stops the step.
 void launch_sched(hipStream_t st, Ctrl* ctrl, Slots s, int* row_slot, int* row_pos,
-                  int* free_stack, int blk, int check_only);
+                  int* free_stack, int blk, int check_only, int row_cap, int ctx_cap);
 void launch_alloc_prefill(hipStream_t st, Ctrl* ctrl, Slots s, const int* slot_list,
                           const int* n_blocks_needed, int n, int* free_stack);
 void launch_free_slots(hipStream_t st, Ctrl* ctrl, Slots s, const int* slot_list, int n,
@@ -88,7 +90,7 @@ int attn_split_tokens();
 // appends the new key / value itself from the QKV GEMM's split-K partials (q_rot unused).
 void launch_attn_decode(hipStream_t st, RowCtx rc, int row_base, Slots s, const float* q_rot,
                         bf16_t* kv_pool, KVLayout kvl, int layer, int n_q_heads, bf16_t* out,
-                        float* ws, int* counters, int max_splits, int grid_splits,
+                        float* ws, int max_splits, int grid_splits,
                         const float* fused_qkv, int n_partials, size_t partial_stride,
                         const float* rope_cos, const float* rope_sin);
 

@@ -3,9 +3,11 @@
 // One workgroup (4 wavefronts) per (row, KV head, KV split of ATT_SPLIT tokens).  The
 // wavefronts take the split's 32-token tiles round-robin, each keeps an online softmax
 // in registers, the four partial results are merged through LDS in wavefront order;
-// when a context spans several splits the merged partials go to a workspace and the
-// last workgroup to finish merges them in split order (deterministic: the order of
-// every floating-point sum depends on the row's own length only).
+// when a context spans several splits the merged partials go to a workspace and a small
+// second kernel merges them in split order (deterministic: the order of every
+// floating-point sum depends on the row's own length only).  The kernel boundary is the
+// cheapest device-wide ordering on this chip: publishing the partials behind agent-scope
+// fences and letting the last workgroup merge cost more than the extra launch.
 //
 // Both products run on v_mfma_f32_16x16x32_bf16, computed transposed so that no
 // operand has to be re-laid between them:
@@ -31,7 +33,10 @@
 
 namespace april {
 
-constexpr int ATT_SPLIT = 1024;          // tokens per KV split = 64 pages = one page id per lane
+#ifndef ATT_SPLIT_TOKENS
+#define ATT_SPLIT_TOKENS 1024
+#endif
+constexpr int ATT_SPLIT = ATT_SPLIT_TOKENS;   // tokens per KV split (at most 64 pages: one page id per lane)
 constexpr int ATT_WAVES = 4;
 
 struct AttnFuse {              // inputs of the fused rotary + append (FUSED only)
@@ -45,16 +50,17 @@ struct AttnFuse {              // inputs of the fused rotary + append (FUSED onl
 template <int DH, bool FUSED>
 __global__ __launch_bounds__(64 * ATT_WAVES) void attn_decode_kernel(
     RowCtx rc, int row_base, Slots s, const float* __restrict__ q_rot, bf16_t* kv_pool, KVLayout L, int layer,
-    int Hq, bf16_t* __restrict__ out, float* ws, int* counters, int max_splits, AttnFuse fz) {
+    int Hq, bf16_t* __restrict__ out, float* __restrict__ ws, int max_splits, AttnFuse fz) {
   constexpr int KC = DH / 32;      // k-chunks of the QK product
   constexpr int DT = DH / 16;      // dim tiles of the PV product
   constexpr int REC = 32 + 16 * DH;   // floats of one partial result: m[16], l[16], o[16][DH]
   __shared__ float lds[ATT_WAVES * REC];
-  __shared__ int s_last;
   __shared__ bf16_t s_knew[DH], s_vnew[DH];
   const int wr = blockIdx.x, r = row_base + wr, kvh = blockIdx.y, split = blockIdx.z;   // wr: workspace row
+  // the row arrays hold max_rows entries: fetch them together with the control word
+  const int slot_raw = rc.row_slot[r], pos = rc.row_pos[r];
   ROW_GUARD(rc, r);
-  const int slot = rc.row_slot[r], pos = rc.row_pos[r];
+  const int slot = slot_raw;
   const int ctx = pos + 1;
   const int n_splits = (ctx + ATT_SPLIT - 1) / ATT_SPLIT;
   if (split >= n_splits) return;
@@ -300,18 +306,31 @@ __global__ __launch_bounds__(64 * ATT_WAVES) void attn_decode_kernel(
     return;
   }
 
-  // ---- several splits: publish (m, l, O); the last workgroup to arrive merges --------------
+  // ---- several splits: publish (m, l, O) for the merge kernel -----------------------------
   if (wave == 0) {
     float* my = ws + (((size_t)wr * Hkv + kvh) * max_splits + split) * REC;
     if (g == 0) { my[hh] = m_run; my[16 + hh] = l_run; }
 #pragma unroll
     for (int d = 0; d < DT; ++d) *reinterpret_cast<f32x4*>(my + 32 + hh * DH + d * 16 + 4 * g) = oacc[d];
-    __threadfence();
-    if (lane == 0) s_last = atomicAdd(&counters[wr * Hkv + kvh], 1) == n_splits - 1;
   }
-  __syncthreads();
-  if (!s_last || wave != 0) return;
-  __threadfence();
+}
+
+// Merge of the per-split partial results of the rows whose context spans several splits
+// (one wavefront per (row, KV head); rows with a single split were finished by the main
+// kernel).  Split order, so a row's result depends on its own length only.
+template <int DH>
+__global__ __launch_bounds__(64) void attn_merge_kernel(RowCtx rc, int row_base, int Hkv, int Hq,
+                                                        bf16_t* __restrict__ out, const float* __restrict__ ws,
+                                                        int max_splits) {
+  constexpr int DT = DH / 16;
+  constexpr int REC = 32 + 16 * DH;
+  const int wr = blockIdx.x, r = row_base + wr, kvh = blockIdx.y;
+  const int pos = rc.row_pos[r];
+  ROW_GUARD(rc, r);
+  const int n_splits = (pos + ATT_SPLIT) / ATT_SPLIT;          // ceil((pos + 1) / ATT_SPLIT)
+  if (n_splits == 1) return;
+  const int lane = threadIdx.x, hh = lane & 15, g = lane >> 4;
+  const int G = Hq / Hkv, K = Hq * DH;
   const float* base = ws + ((size_t)wr * Hkv + kvh) * max_splits * REC;
   // every load of the merge is independent of the others: issue them in batches
   float M = -INFINITY;
@@ -356,20 +375,19 @@ __global__ __launch_bounds__(64 * ATT_WAVES) void attn_decode_kernel(
       *reinterpret_cast<bf16x4*>(out + act_index<true>(r, (kvh * G + hh) * DH + d * 16 + 4 * g, K)) = o;
     }
   }
-  if (lane == 0) counters[wr * Hkv + kvh] = 0;
 }
 
 int attn_split_tokens() { return ATT_SPLIT; }
 
 void launch_attn_decode(hipStream_t st, RowCtx rc, int row_base, Slots s, const float* q_rot, bf16_t* kv_pool,
-                        KVLayout kvl, int layer, int n_q_heads, bf16_t* out, float* ws, int* counters,
+                        KVLayout kvl, int layer, int n_q_heads, bf16_t* out, float* ws,
                         int max_splits, int grid_splits, const float* fused_qkv, int n_partials,
                         size_t partial_stride, const float* rope_cos, const float* rope_sin) {
   dim3 grid(rc.max_rows, kvl.n_kv_heads, grid_splits), block(64 * ATT_WAVES);
   AttnFuse fz{fused_qkv, n_partials, partial_stride, rope_cos, rope_sin};
 #define ATT_LAUNCH(DH, F)                                                                                    \
   hipLaunchKernelGGL((attn_decode_kernel<DH, F>), grid, block, 0, st, rc, row_base, s, q_rot, kv_pool, kvl, layer, \
-                     n_q_heads, out, ws, counters, max_splits, fz)
+                     n_q_heads, out, ws, max_splits, fz)
   const bool fused = fused_qkv != nullptr;
   switch (kvl.head_dim) {
     case 32: if (fused) ATT_LAUNCH(32, true); else ATT_LAUNCH(32, false); break;
@@ -377,6 +395,18 @@ void launch_attn_decode(hipStream_t st, RowCtx rc, int row_base, Slots s, const 
     default: if (fused) ATT_LAUNCH(128, true); else ATT_LAUNCH(128, false); break;
   }
 #undef ATT_LAUNCH
+  if (grid_splits > 1) {       // some row may span several splits: merge their partials
+    dim3 mgrid(rc.max_rows, kvl.n_kv_heads);
+#define ATT_MERGE(DH)                                                                                       \
+  hipLaunchKernelGGL((attn_merge_kernel<DH>), mgrid, dim3(64), 0, st, rc, row_base, kvl.n_kv_heads, n_q_heads, out, \
+                     (const float*)ws, max_splits)
+    switch (kvl.head_dim) {
+      case 32: ATT_MERGE(32); break;
+      case 64: ATT_MERGE(64); break;
+      default: ATT_MERGE(128); break;
+    }
+#undef ATT_MERGE
+  }
 }
 
 }  // namespace april

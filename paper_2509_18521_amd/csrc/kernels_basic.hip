@@ -38,7 +38,8 @@ template <typename T> __device__ inline T from_f32(float v) { return (T)v; }
 //   - if nothing is live and nothing waits for prefill, the step ends (fewer than N).
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(1024) void sched_kernel(Ctrl* c, Slots s, int* row_slot, int* row_pos,
-                                                     int* free_stack, int blk, int check_only) {
+                                                     int* free_stack, int blk, int check_only, int row_cap,
+                                                     int ctx_cap) {
   __shared__ int sh_a[16], sh_b[16], sh_err[16];
   __shared__ long long sh_ctx[16];
   const int tid = threadIdx.x, lane = tid & 63, wid = tid >> 6;
@@ -116,12 +117,13 @@ __global__ __launch_bounds__(1024) void sched_kernel(Ctrl* c, Slots s, int* row_
       row_slot[r] = slot;
       row_pos[r] = pos;
       ctx_sum += pos + 1;
+      if (pos + 1 > ctx_cap) err |= 2;       // the host sized this iteration's launches for shorter contexts
     }
     if (need) {
       const int idx = free_top - 1 - (base_need + wb + ib - 1);
       const int bi = pos / blk;
       if (idx < 0 || bi >= s.max_blocks) {
-        err = 1;
+        err |= 1;
       } else {
         s.block_table[(size_t)slot * s.max_blocks + bi] = free_stack[idx];
         s.n_blocks[slot] = bi + 1;
@@ -151,14 +153,15 @@ __global__ __launch_bounds__(1024) void sched_kernel(Ctrl* c, Slots s, int* row_
       c->sum_ctx += tot;
       c->iter_ctx = tot;
     }
-    if (e) { c->error = 1; c->stop = 1; c->stop_iter = iter; c->n_rows = 0; }
+    if (base_live > row_cap) e |= 2;         // ... or for fewer rows
+    if (e) { c->error = e; c->stop = 1; c->stop_iter = iter; c->n_rows = 0; }
   }
 }
 
 void launch_sched(hipStream_t st, Ctrl* ctrl, Slots s, int* row_slot, int* row_pos, int* free_stack, int blk,
-                  int check_only) {
+                  int check_only, int row_cap, int ctx_cap) {
   hipLaunchKernelGGL(sched_kernel, dim3(1), dim3(1024), 0, st, ctrl, s, row_slot, row_pos, free_stack, blk,
-                     check_only);
+                     check_only, row_cap, ctx_cap);
 }
 
 // Pages for freshly admitted rollouts (prefill): slot_list[i] gets need[i] pages.

@@ -89,6 +89,16 @@ def test_wide_shapes_head_dim_128_gqa4(name):
     teacher_forced_parity(w, 2, 8)
 
 
+@pytest.mark.parametrize("head_dim", [64, 128])
+def test_long_context_spans_several_kv_splits(head_dim):
+    """Contexts beyond 1024 and 2048 tokens: the attention kernel cuts them into KV splits whose
+    partial results a second kernel merges; prefill rows and decode rows both cross the
+    boundaries here (2100-token prompts, then a resumed step on resident KV)."""
+    shape = ai.ModelShape(1, 256, 256 // head_dim, 2, head_dim, 256, 512)
+    w = ai.Workload("long_ctx", shape, 3, 2100, 2, 3, 8, 1.6, 0.4, 3, 8, ai.SAMPLER_GREEDY, 0, 2, 77)
+    teacher_forced_parity(w, 2, 5, min_rows=12)
+
+
 def test_bf16_scheduling_invariance():
     """On the bf16 path a rollout's tokens do not depend on how it was scheduled: carried over
     with resident KV or run with N' = N, token for token.  A rollout whose KV was dropped is

@@ -41,9 +41,11 @@ __device__ inline void gemm_group(const bf16x8* __restrict__ w0, const bf16x8* _
                                   const bf16x8* __restrict__ x, int KT, int k0, int k1, int nt0, int mt0,
                                   int rows, int N, float* __restrict__ out, bf16_t* __restrict__ act,
                                   float* red) {
-  // k-tiles fetched per trip: as many as the register file takes (4 VGPRs per fragment),
-  // so that a wavefront's whole k range is usually in flight at once
-  constexpr int KU = (NT + MTC) <= 4 ? 16 : ((NT + MTC) == 5 ? 14 : 10);
+  // k-tiles per fetch group: two groups fill the register file (4 VGPRs per fragment).  The
+  // next group is requested before the MFMAs of the current one, so a wavefront whose k range
+  // fits in two groups has all of it in flight at once, and a longer range streams with one
+  // group always in flight behind the arithmetic.
+  constexpr int KH = (NT + MTC) <= 4 ? 8 : ((NT + MTC) == 5 ? 7 : 5);
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   f32x16 acc[NT][MTC];
 #pragma unroll
@@ -66,29 +68,40 @@ __device__ inline void gemm_group(const bf16x8* __restrict__ w0, const bf16x8* _
   const int len = k1 - k0;
   const int kb = INTRA ? k0 + (int)((long long)len * wave / KW) : k0;
   const int ke = INTRA ? k0 + (int)((long long)len * (wave + 1) / KW) : k1;
-  // KU k-tiles per trip; the last trip re-reads the final tile for the missing ones
-  // (loads stay unconditional and in flight together) and skips their MFMAs.
-  for (int kt = kb; kt < ke; kt += KU) {
-    bf16x8 a[KU][NT], b[KU][MTC];
+  // A group past the end re-reads the final k-tile (loads stay unconditional and in flight
+  // together) and skips its MFMAs.
+  bf16x8 a[2][KH][NT], b[2][KH][MTC];
+  auto fetch = [&](int g, int kt) {
 #pragma unroll
-    for (int u = 0; u < KU; ++u) {
+    for (int u = 0; u < KH; ++u) {
       const size_t k = (size_t)(kt + u < ke ? kt + u : ke - 1) * 64;
 #pragma unroll
-      for (int i = 0; i < NT; ++i) a[u][i] = wp[i][k];
+      for (int i = 0; i < NT; ++i) a[g][u][i] = wp[i][k];
 #pragma unroll
-      for (int j = 0; j < MTC; ++j) b[u][j] = xp[j][k];
+      for (int j = 0; j < MTC; ++j) b[g][u][j] = xp[j][k];
     }
-    // keep every load of this trip in flight before the first MFMA waits on one
-    __builtin_amdgcn_sched_barrier(0);
+  };
+  auto multiply = [&](int g, int kt) {
 #pragma unroll
-    for (int u = 0; u < KU; ++u) {
+    for (int u = 0; u < KH; ++u) {
       if (kt + u < ke) {
 #pragma unroll
         for (int i = 0; i < NT; ++i)
 #pragma unroll
           for (int j = 0; j < MTC; ++j)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[u][i], b[u][j], acc[i][j], 0, 0, 0);
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[g][u][i], b[g][u][j], acc[i][j], 0, 0, 0);
       }
+    }
+  };
+  if (kb < ke) {
+    fetch(0, kb);
+    for (int kt = kb; kt < ke; kt += 2 * KH) {
+      fetch(1, kt + KH);
+      __builtin_amdgcn_sched_barrier(0);        // both groups requested before the first MFMA waits
+      multiply(0, kt);
+      if (kt + 2 * KH < ke) fetch(0, kt + 2 * KH);
+      __builtin_amdgcn_sched_barrier(0);
+      multiply(1, kt + KH);
     }
   }
 

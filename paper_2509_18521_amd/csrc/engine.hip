@@ -27,11 +27,11 @@ double now_s() {
 
 enum KernelClass {
   KC_SCHED = 0, KC_EMBED, KC_NORM, KC_GEMM_QKV, KC_ROPE, KC_ATTN, KC_GEMM_O, KC_GEMM_GATEUP, KC_SILU,
-  KC_GEMM_DOWN, KC_GEMM_LMHEAD, KC_SAMPLE, KC_MOE_ROUTE, KC_MOE_GATEUP, KC_MOE_DOWN, KC_COUNT
+  KC_GEMM_DOWN, KC_GEMM_LMHEAD, KC_SAMPLE, KC_MOE_ROUTE, KC_MOE_GATEUP, KC_MOE_DOWN, KC_ATTN_MERGE, KC_EVENT_EMPTY, KC_COUNT
 };
 const char* kKernelNames[KC_COUNT] = {"sched", "embed", "add_rmsnorm", "gemm_qkv", "rope_append", "attn_decode",
                                       "gemm_o", "gemm_gateup", "silu_mul", "gemm_down", "gemm_lmhead", "sample",
-                                      "moe_route", "moe_gateup", "moe_down"};
+                                      "moe_route", "moe_gateup", "moe_down", "attn_merge", "event_pair_empty_kernel"};
 
 struct LayerW {
   float *attn_norm = nullptr, *mlp_norm = nullptr;
@@ -124,7 +124,7 @@ struct april_ctx {
   bool attn_mfma = false, fuse_rope = true, tile_gemm = true;
   int attn_chunk = 256, attn_max_splits = 1, attn_ws_rows = 0;
   float* attn_ws = nullptr;
-  int* attn_counters = nullptr;
+  int* d_dummy = nullptr;       // target of the empty kernel that calibrates event-pair timing
   int step_max_ctx = 0;        // bound on the context length of any row in the current pass
   // routed experts
   bool moe = false;
@@ -318,18 +318,25 @@ void forward(april_ctx* c, RowCtx rows, RowCtx srows, const int* gather, double 
       if (c->bf16) launch_rope_append<bf16_t>(st, rows, c->ds, c->qkv, sq, c->qkv_stride, c->rope_cos, c->rope_sin, c->q_rot, (bf16_t*)c->kv_pool, c->kvl, l, Hq);
       else launch_rope_append<float>(st, rows, c->ds, c->qkv, sq, c->qkv_stride, c->rope_cos, c->rope_sin, c->q_rot, (float*)c->kv_pool, c->kvl, l, Hq);
     }
-    {
-      ProfScope p(c, KC_ATTN, C * 2.0 * nkv * e + B * nq * (4.0 + e), 4.0 * C * nq);
-      if (c->attn_mfma) {
-        const int gs = std::min(c->attn_max_splits, std::max(1, ceil_div(c->step_max_ctx, c->attn_chunk)));
-        for (int base = 0; base < rows.max_rows; base += c->attn_ws_rows) {
-          RowCtx sub = rows;
-          sub.max_rows = std::min(c->attn_ws_rows, rows.max_rows - base);
+    if (c->attn_mfma) {
+      const int gs = std::min(c->attn_max_splits, std::max(1, ceil_div(c->step_max_ctx, c->attn_chunk)));
+      for (int base = 0; base < rows.max_rows; base += c->attn_ws_rows) {
+        RowCtx sub = rows;
+        sub.max_rows = std::min(c->attn_ws_rows, rows.max_rows - base);
+        {
+          ProfScope p(c, KC_ATTN, C * 2.0 * nkv * e + B * nq * (4.0 + e), 4.0 * C * nq);
           launch_attn_decode(st, sub, base, c->ds, c->q_rot, (bf16_t*)c->kv_pool, c->kvl, l, Hq,
                              (bf16_t*)c->attn_out, c->attn_ws, c->attn_max_splits, gs,
                              fuse_rope ? c->qkv : nullptr, sq, c->qkv_stride, c->rope_cos, c->rope_sin);
         }
-      } else if (c->bf16) launch_attn_ref<bf16_t, true>(st, rows, c->ds, c->q_rot, (const bf16_t*)c->kv_pool, c->kvl, l, Hq, (bf16_t*)c->attn_out);
+        if (gs > 1) {      // some row may span several KV splits: merge their partial results
+          ProfScope p(c, KC_ATTN_MERGE, 0, 0);
+          launch_attn_merge(st, sub, base, c->kvl, Hq, (bf16_t*)c->attn_out, c->attn_ws, c->attn_max_splits);
+        }
+      }
+    } else {
+      ProfScope p(c, KC_ATTN, C * 2.0 * nkv * e + B * nq * (4.0 + e), 4.0 * C * nq);
+      if (c->bf16) launch_attn_ref<bf16_t, true>(st, rows, c->ds, c->q_rot, (const bf16_t*)c->kv_pool, c->kvl, l, Hq, (bf16_t*)c->attn_out);
       else launch_attn_ref<float, false>(st, rows, c->ds, c->q_rot, (const float*)c->kv_pool, c->kvl, l, Hq, (float*)c->attn_out);
     }
     gemm(KC_GEMM_O, rows, c->attn_out, L.wo, L.wo_s, c->proj, d, nq, so, c->proj_stride, B);
@@ -891,6 +898,7 @@ int april_sample_rows(april_ctx* c, const float* logits, int32_t n_rows, const i
   return APRIL_OK;
 }
 
+static int measure_event_overhead(april_ctx* c);
 int april_profile_enable(april_ctx* c, int32_t every) {
   if (!c || every < 0) return APRIL_EINVAL;
   c->prof_every = every;
@@ -898,11 +906,29 @@ int april_profile_enable(april_ctx* c, int32_t every) {
     c->snaps_cap = 4096;
     HIPCHK(c, hipHostMalloc((void**)&c->h_snaps, c->snaps_cap * sizeof(Ctrl)));
   }
+  if (every > 0 && c->stats[KC_EVENT_EMPTY].launches == 0) return measure_event_overhead(c);
+  return APRIL_OK;
+}
+// What an event pair around one eager launch reads for a kernel that does nothing: the part
+// of every profiled launch's time that is dispatch and completion latency, not execution.
+static int measure_event_overhead(april_ctx* c) {
+  if (!c->d_dummy) { int rc = dev_alloc(c, &c->d_dummy, 64, true); if (rc != APRIL_OK) return rc; }
+  const bool was = c->prof_now;
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  c->prof_now = true;
+  for (int i = 0; i < 64; ++i) {
+    ProfScope p(c, KC_EVENT_EMPTY, 0, 0);
+    launch_fill_i32(c->stream, c->d_dummy, 0, 1);
+  }
+  c->prof_now = was;
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  prof_collect(c);
   return APRIL_OK;
 }
 int april_profile_reset(april_ctx* c) {
   if (!c) return APRIL_EINVAL;
   for (int i = 0; i < KC_COUNT; ++i) c->stats[i] = april_kernel_stat{kKernelNames[i], 0, 0, 0, 0};
+  if (c->prof_every > 0) return measure_event_overhead(c);
   return APRIL_OK;
 }
 int april_profile_get(april_ctx* c, april_kernel_stat* out, int32_t cap) {

@@ -93,6 +93,9 @@ void launch_attn_decode(hipStream_t st, RowCtx rc, int row_base, Slots s, const 
                         float* ws, int max_splits, int grid_splits,
                         const float* fused_qkv, int n_partials, size_t partial_stride,
                         const float* rope_cos, const float* rope_sin);
+// Merge of the KV-split partials (needed after launch_attn_decode whenever grid_splits > 1).
+void launch_attn_merge(hipStream_t st, RowCtx rc, int row_base, KVLayout kvl, int n_q_heads, bf16_t* out,
+                       const float* ws, int max_splits);
 
 template <typename T, bool XF>
 void launch_silu_mul(hipStream_t st, RowCtx rc, const float* gu, int F, T* act);

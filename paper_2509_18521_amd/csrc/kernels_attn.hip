@@ -395,18 +395,21 @@ void launch_attn_decode(hipStream_t st, RowCtx rc, int row_base, Slots s, const 
     default: if (fused) ATT_LAUNCH(128, true); else ATT_LAUNCH(128, false); break;
   }
 #undef ATT_LAUNCH
-  if (grid_splits > 1) {       // some row may span several splits: merge their partials
-    dim3 mgrid(rc.max_rows, kvl.n_kv_heads);
+}
+
+// Second pass for iterations in which some row may span several KV splits.
+void launch_attn_merge(hipStream_t st, RowCtx rc, int row_base, KVLayout kvl, int n_q_heads, bf16_t* out,
+                       const float* ws, int max_splits) {
+  dim3 mgrid(rc.max_rows, kvl.n_kv_heads);
 #define ATT_MERGE(DH)                                                                                       \
   hipLaunchKernelGGL((attn_merge_kernel<DH>), mgrid, dim3(64), 0, st, rc, row_base, kvl.n_kv_heads, n_q_heads, out, \
-                     (const float*)ws, max_splits)
-    switch (kvl.head_dim) {
-      case 32: ATT_MERGE(32); break;
-      case 64: ATT_MERGE(64); break;
-      default: ATT_MERGE(128); break;
-    }
-#undef ATT_MERGE
+                     ws, max_splits)
+  switch (kvl.head_dim) {
+    case 32: ATT_MERGE(32); break;
+    case 64: ATT_MERGE(64); break;
+    default: ATT_MERGE(128); break;
   }
+#undef ATT_MERGE
 }
 
 }  // namespace april

@@ -104,6 +104,7 @@ def main():
     p.add_argument("--warmup", type=int, default=1)
     p.add_argument("--workload", default="cfg2_small_bf16")
     p.add_argument("--layers", type=int, default=0, help="override the layer count (debug only; invalidates the number)")
+    p.add_argument("--max-new", type=int, default=0, help="cap the generated length (debug only; invalidates the number)")
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--no-wait-all", action="store_true")
     p.add_argument("--profile-every", type=int, default=16)
@@ -127,6 +128,9 @@ def main():
     w = ai.WORKLOADS[args.workload]
     if args.layers:
         w = ai.reduced(w, n_layers=args.layers)
+    if args.max_new:
+        import dataclasses
+        w = dataclasses.replace(w, max_new=args.max_new)
     s = w.shape
     t_setup = time.perf_counter()
     weights = ai.make_weights(s, w.seed)

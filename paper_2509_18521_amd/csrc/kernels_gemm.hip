@@ -106,29 +106,30 @@ __device__ inline void gemm_group(const bf16x8* __restrict__ w0, const bf16x8* _
   }
 
   // reduction over the KW wavefronts through LDS: wavefronts 1.. publish, wavefront 0 adds
-  // them in wavefront order
-  constexpr int NREG = NT * MTC * 16;
+  // them in wavefront order; one weight tile per round, so the buffer stays at
+  // (KW-1) x MTC accumulator tiles whatever NT is
+  constexpr int NREG = MTC * 16;
   if (INTRA) {
-    if (wave != 0) {
-      float* dst = red + (size_t)(wave - 1) * NREG * 64 + lane;
 #pragma unroll
-      for (int i = 0; i < NT; ++i)
+    for (int i = 0; i < NT; ++i) {
+      if (i > 0) __syncthreads();               // wavefront 0 has read the previous round
+      if (wave != 0) {
+        float* dst = red + (size_t)(wave - 1) * NREG * 64 + lane;
 #pragma unroll
         for (int j = 0; j < MTC; ++j)
 #pragma unroll
-          for (int e = 0; e < 16; ++e) dst[((i * MTC + j) * 16 + e) * 64] = acc[i][j][e];
-    }
-    __syncthreads();
-    if (wave == 0) {
+          for (int e = 0; e < 16; ++e) dst[(j * 16 + e) * 64] = acc[i][j][e];
+      }
+      __syncthreads();
+      if (wave == 0) {
 #pragma unroll
-      for (int w = 0; w < KW - 1; ++w) {
-        const float* src = red + (size_t)w * NREG * 64 + lane;
-#pragma unroll
-        for (int i = 0; i < NT; ++i)
+        for (int w = 0; w < KW - 1; ++w) {
+          const float* src = red + (size_t)w * NREG * 64 + lane;
 #pragma unroll
           for (int j = 0; j < MTC; ++j)
 #pragma unroll
-            for (int e = 0; e < 16; ++e) acc[i][j][e] += src[((i * MTC + j) * 16 + e) * 64];
+            for (int e = 0; e < 16; ++e) acc[i][j][e] += src[(j * 16 + e) * 64];
+        }
       }
     }
   }
@@ -196,15 +197,20 @@ __global__ __launch_bounds__(64 * KW) void gemm_mfma_kernel(RowCtx rc, const bf1
                                                            const bf16x8* __restrict__ w1, float* __restrict__ out,
                                                            bf16_t* __restrict__ act, int N, int K, int ksplit,
                                                            size_t partial_stride) {
-  __shared__ float red[INTRA ? (KW - 1) * NT * MT * 16 * 64 : 1];
+  __shared__ float red[INTRA ? (KW - 1) * MT * 16 * 64 : 1];
   const int rows = rows_or_zero(rc);
   const int mt0 = blockIdx.z * MT;
   if (mt0 * 32 >= rows) return;
   const int KT = K >> 4;
-  const int grp = INTRA ? blockIdx.x : blockIdx.x * KW + (threadIdx.x >> 6);
+  // Split-k launches put the k split in blockIdx.x: consecutive workgroups go to consecutive
+  // XCDs, so with 8 (4) splits every XCD works on one (two) k slices and pulls only that slice
+  // of the activations into its L2 instead of all of them.
+  constexpr bool SPLIT_FIRST = INTRA && EPI == EPI_F32;
+  const int bgrp = SPLIT_FIRST ? blockIdx.y : blockIdx.x;
+  const int grp = INTRA ? bgrp : bgrp * KW + (threadIdx.x >> 6);
   const int nt0 = (EPI == EPI_SWIGLU) ? grp : grp * NT;
   if (!INTRA && nt0 >= (N >> 5)) return;
-  const int sidx = blockIdx.y;
+  const int sidx = SPLIT_FIRST ? blockIdx.x : blockIdx.y;
   const int k0 = (int)((long long)KT * sidx / ksplit), k1 = (int)((long long)KT * (sidx + 1) / ksplit);
   float* o = out ? out + sidx * partial_stride : nullptr;
   int mtc = ceil_div(rows, 32) - mt0;
@@ -230,7 +236,7 @@ void launch_gemm_mfma(hipStream_t st, RowCtx rc, const bf16_t* x, const bf16_t* 
     hipLaunchKernelGGL((gemm_mfma_kernel<2, MT, EPI_F32, false>), grid, dim3(64 * KW), 0, st, rc, xv, wv, nullptr,
                        out, nullptr, N, K, ksplit, partial_stride);
   } else {
-    dim3 grid(n_tiles, ksplit, m_groups);
+    dim3 grid(ksplit, n_tiles, m_groups);
     hipLaunchKernelGGL((gemm_mfma_kernel<1, MT, EPI_F32, true>), grid, dim3(64 * KW), 0, st, rc, xv, wv, nullptr,
                        out, nullptr, N, K, ksplit, partial_stride);
   }

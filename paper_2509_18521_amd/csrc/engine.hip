@@ -121,7 +121,8 @@ struct april_ctx {
   int s_qkv = 1, s_o = 1, s_down = 1;
   size_t qkv_stride = 0, proj_stride = 0;
   // bf16 MFMA attention: split-KV workspace
-  bool attn_mfma = false, fuse_rope = true, tile_gemm = true;
+  bool attn_mfma = false, fuse_rope = true, tile_gemm = true, fuse_norm = true;
+  float* ssq = nullptr;         // [d_model / 32][m_cap] per-row partial sums of squares (fused norm)
   int attn_chunk = 256, attn_max_splits = 1, attn_ws_rows = 0;
   float* attn_ws = nullptr;
   int* d_dummy = nullptr;       // target of the empty kernel that calibrates event-pair timing
@@ -339,8 +340,17 @@ void forward(april_ctx* c, RowCtx rows, RowCtx srows, const int* gather, double 
       if (c->bf16) launch_attn_ref<bf16_t, true>(st, rows, c->ds, c->q_rot, (const bf16_t*)c->kv_pool, c->kvl, l, Hq, (bf16_t*)c->attn_out);
       else launch_attn_ref<float, false>(st, rows, c->ds, c->q_rot, (const float*)c->kv_pool, c->kvl, l, Hq, (float*)c->attn_out);
     }
-    gemm(KC_GEMM_O, rows, c->attn_out, L.wo, L.wo_s, c->proj, d, nq, so, c->proj_stride, B);
-    norm(rows, so, L.mlp_norm, c->h_act, nullptr, B, false);
+    // decode, dense MLP: the output projection adds into the residual stream itself and hands the
+    // gate/up GEMM un-normalised activations plus per-row sums of squares (no norm launch)
+    const bool fuse_norm2 = c->use_mfma && c->fuse_norm && !tile && !c->moe;
+    if (fuse_norm2) {
+      ProfScope p(c, KC_GEMM_O, (double)d * nq * e + B * nq * e + B * d * (8.0 + e), 2.0 * B * d * nq);
+      launch_gemm_mfma_resid(st, rows, (const bf16_t*)c->attn_out, L.wo_s, c->x_res, L.mlp_norm, (bf16_t*)c->h_act,
+                             c->ssq, c->m_cap, d, nq);
+    } else {
+      gemm(KC_GEMM_O, rows, c->attn_out, L.wo, L.wo_s, c->proj, d, nq, so, c->proj_stride, B);
+      norm(rows, so, L.mlp_norm, c->h_act, nullptr, B, false);
+    }
     if (c->moe) {
       const int E = c->n_experts, Fe = c->d_expert, tk = c->top_k_experts;
       gemm(KC_MOE_ROUTE, rows, c->h_act, nullptr, L.router_s, c->router_out, E, d, sr, c->router_stride, B);
@@ -361,7 +371,8 @@ void forward(april_ctx* c, RowCtx rows, RowCtx srows, const int* gather, double 
     if (c->use_mfma) {
       ProfScope p(c, KC_GEMM_GATEUP, 2.0 * F * d * e + B * d * e + B * F * e, 4.0 * B * F * d);
       if (tile) launch_gemm_tile_swiglu(st, rows, (const bf16_t*)c->h_act, L.wg_s, L.wu_s, (bf16_t*)c->act, F, d);
-      else launch_gemm_mfma_swiglu(st, rows, (const bf16_t*)c->h_act, L.wg_s, L.wu_s, (bf16_t*)c->act, F, d);
+      else launch_gemm_mfma_swiglu(st, rows, (const bf16_t*)c->h_act, L.wg_s, L.wu_s, (bf16_t*)c->act, F, d,
+                                   fuse_norm2 ? c->ssq : nullptr, c->m_cap, m.rms_eps);
     } else {
       gemm(KC_GEMM_GATEUP, rows, c->h_act, L.wgu, nullptr, c->gu, 2 * F, d, 1, 0, B);
       ProfScope p(c, KC_SILU, B * F * (8.0 + e), 0);
@@ -463,6 +474,8 @@ int april_init(const april_model_cfg* cfg, const april_tensor* weights, int32_t 
   if (moe && !(c->use_mfma && c->attn_mfma)) { delete c; return fail(nullptr, APRIL_EINVAL, "routed experts run on the MFMA path only"); }
   const char* fr = getenv("APRIL_FUSE_ROPE");
   c->fuse_rope = !(fr && !strcmp(fr, "0"));
+  const char* fn = getenv("APRIL_FUSE_NORM");
+  c->fuse_norm = !(fn && !strcmp(fn, "0"));
   const char* tg = getenv("APRIL_TILE_GEMM");
   c->tile_gemm = !(tg && !strcmp(tg, "0"));
   const char* gr = getenv("APRIL_GRAPH");
@@ -619,6 +632,7 @@ int april_init(const april_model_cfg* cfg, const april_tensor* weights, int32_t 
   c->qkv_stride = M * nqkv;
   c->proj_stride = M * d;
   TRY(dev_alloc(c, &c->x_res, M * d));
+  if (c->use_mfma) TRY(dev_alloc(c, &c->ssq, (size_t)(d / 32) * M));
   TRY(dev_alloc(c, &c->qkv, (size_t)c->s_qkv * c->qkv_stride));
   TRY(dev_alloc(c, &c->q_rot, M * nq));
   TRY(dev_alloc(c, &c->proj, (size_t)std::max(c->s_o, c->s_down) * c->proj_stride));

@@ -109,8 +109,14 @@ void launch_gemm_ref(hipStream_t st, RowCtx rc, const T* x, const T* W, float* o
 void launch_gemm_mfma(hipStream_t st, RowCtx rc, const bf16_t* x, const bf16_t* Wp, float* out,
                       int N, int K, int ksplit, size_t partial_stride);
 // act[m][f] = silu(x.Wg[f]) * (x.Wu[f]) as fragment-tiled bf16.
+// ssq != nullptr: the activations are residual * gain (not yet normalised); the kernel divides
+// its accumulators by the row's RMS, from the sums of squares the producer left (see
+// launch_gemm_mfma_resid).
 void launch_gemm_mfma_swiglu(hipStream_t st, RowCtx rc, const bf16_t* x, const bf16_t* Wg,
-                             const bf16_t* Wu, bf16_t* act, int F, int K);
+                             const bf16_t* Wu, bf16_t* act, int F, int K, const float* ssq = nullptr,
+                             int ssq_stride = 0, float eps = 0.f);
+void launch_gemm_mfma_resid(hipStream_t st, RowCtx rc, const bf16_t* x, const bf16_t* Wp, float* x_res,
+                            const float* gain, bf16_t* act, float* ssq, int ssq_stride, int N, int K);
 // LDS-tiled GEMM for tall activations (prefill); single pass over k, no partials.
 void launch_gemm_tile(hipStream_t st, RowCtx rc, const bf16_t* x, const bf16_t* Wp, float* out, int N, int K);
 void launch_gemm_tile_swiglu(hipStream_t st, RowCtx rc, const bf16_t* x, const bf16_t* Wg, const bf16_t* Wu,

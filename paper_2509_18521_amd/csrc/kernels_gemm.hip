@@ -29,7 +29,21 @@ void launch_shuffle_weights(hipStream_t st, const bf16_t* src, bf16_t* dst, int 
                      reinterpret_cast<bf16x8*>(dst), N, K);
 }
 
-enum { EPI_F32 = 0, EPI_SWIGLU = 1, EPI_LOGITS = 2 };
+enum { EPI_F32 = 0, EPI_SWIGLU = 1, EPI_LOGITS = 2, EPI_RESID = 3 };
+
+// RMSNorm folded into the GEMMs around it (decode).  The producer (EPI_RESID, the attention
+// output projection) adds its result to the residual stream in place, writes the residual times
+// the next norm's gain as the bf16 activations of the next GEMM, and leaves per row the sum of
+// squares of its 32 columns (ssq[n_tile][row]).  The consumer (EPI_SWIGLU with ssq set) sums
+// those partials in a fixed order and scales its accumulators by 1/sqrt(mean square + eps):
+// W . (x g / rms) = (W . (x g)) / rms.  No separate normalisation launch in between.
+struct NormFuse {
+  const float* gain;     // producer: gain of the following norm [N]
+  float* ssq;            // producer: out; consumer: in.  nullptr = not fused
+  int ssq_stride;        // rows per n-tile slab
+  int n_ssq;             // consumer: number of slabs (= d_model / 32)
+  float inv_d, eps;      // consumer
+};
 
 constexpr int KW = 4;        // wavefronts of a workgroup; they split the k range among themselves
 
@@ -40,7 +54,7 @@ template <int NT, int MTC, int EPI, bool INTRA>
 __device__ inline void gemm_group(const bf16x8* __restrict__ w0, const bf16x8* __restrict__ w1,
                                   const bf16x8* __restrict__ x, int KT, int k0, int k1, int nt0, int mt0,
                                   int rows, int N, float* __restrict__ out, bf16_t* __restrict__ act,
-                                  float* red) {
+                                  float* red, float* ssp, const NormFuse& nf) {
   // k-tiles per fetch group: two groups fill the register file (4 VGPRs per fragment).  The
   // next group is requested before the MFMAs of the current one, so a wavefront whose k range
   // fits in two groups has all of it in flight at once, and a longer range streams with one
@@ -93,6 +107,22 @@ __device__ inline void gemm_group(const bf16x8* __restrict__ w0, const bf16x8* _
       }
     }
   };
+  // Fused norm (consumer side): wavefront w adds the slabs w, w + KW, ... of its rows, wavefront
+  // 0 later adds the four sums.  The first 8 slabs per wavefront are requested here and summed
+  // after the k loop, so their latency hides behind the operand stream.
+  constexpr bool NORM_IN = EPI == EPI_SWIGLU && INTRA;
+  float sq[NORM_IN ? MTC : 1][8];
+  if (NORM_IN && nf.ssq != nullptr) {
+#pragma unroll
+    for (int j = 0; j < MTC; ++j) {
+      const float* col = nf.ssq + (mt0 + j) * 32 + (lane & 31);
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int t = wave + u * KW;
+        sq[j][u] = col[(size_t)(t < nf.n_ssq ? t : nf.n_ssq - 1) * nf.ssq_stride];
+      }
+    }
+  }
   if (kb < ke) {
     fetch(0, kb);
     for (int kt = kb; kt < ke; kt += 2 * KH) {
@@ -105,6 +135,18 @@ __device__ inline void gemm_group(const bf16x8* __restrict__ w0, const bf16x8* _
     }
   }
 
+  if (NORM_IN && nf.ssq != nullptr) {
+#pragma unroll
+    for (int j = 0; j < MTC; ++j) {
+      float sacc = 0.f;
+#pragma unroll
+      for (int u = 0; u < 8; ++u)
+        if (wave + u * KW < nf.n_ssq) sacc += sq[j][u];
+      const float* col = nf.ssq + (mt0 + j) * 32 + (lane & 31);
+      for (int t = wave + 8 * KW; t < nf.n_ssq; t += KW) sacc += col[(size_t)t * nf.ssq_stride];
+      if (lane < 32) ssp[(wave * MTC + j) * 32 + lane] = sacc;
+    }
+  }
   // reduction over the KW wavefronts through LDS: wavefronts 1.. publish, wavefront 0 adds
   // them in wavefront order; one weight tile per round, so the buffer stays at
   // (KW-1) x MTC accumulator tiles whatever NT is
@@ -166,11 +208,45 @@ __device__ inline void gemm_group(const bf16x8* __restrict__ w0, const bf16x8* _
           }
         }
       }
+  } else if (EPI == EPI_RESID) {
+    // out = residual stream (updated in place), act = gain-scaled bf16 copy for the next GEMM
+#pragma unroll
+    for (int j = 0; j < MTC; ++j) {
+      const int m = (mt0 + j) * 32 + mloc;
+      float ss = 0.f;
+      if (m < rows) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int n = nt0 * 32 + 8 * q + nhalf;
+          float* xr = out + (size_t)m * N + n;
+          f32x4 v = *reinterpret_cast<const f32x4*>(xr);
+          const f32x4 gn = *reinterpret_cast<const f32x4*>(nf.gain + n);
+          bf16x4 h;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            v[e] += acc[0][j][4 * q + e];
+            ss += v[e] * v[e];
+            h[e] = (bf16_t)(v[e] * gn[e]);
+          }
+          *reinterpret_cast<f32x4*>(xr) = v;
+          *reinterpret_cast<bf16x4*>(act + act_index<true>(m, n, N)) = h;
+        }
+      }
+      ss += __shfl_xor(ss, 32, 64);
+      if (m < rows && lane < 32) nf.ssq[(size_t)nt0 * nf.ssq_stride + m] = ss;
+    }
   } else {
     // acc[0] = gate tile, acc[1] = up tile of features [nt0*32, nt0*32+32); N is F here.
 #pragma unroll
     for (int j = 0; j < MTC; ++j) {
       const int m = (mt0 + j) * 32 + mloc;
+      float inv = 1.0f;
+      if (INTRA && nf.ssq != nullptr) {
+        float ssum = ssp[j * 32 + mloc];
+#pragma unroll
+        for (int w = 1; w < KW; ++w) ssum += ssp[(w * MTC + j) * 32 + mloc];
+        inv = 1.0f / sqrtf(ssum * nf.inv_d + nf.eps);
+      }
       if (m < rows) {
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
@@ -178,7 +254,7 @@ __device__ inline void gemm_group(const bf16x8* __restrict__ w0, const bf16x8* _
           bf16x4 v;
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
-            const float g = acc[0][j][4 * q + e], u = acc[NT - 1][j][4 * q + e];
+            const float g = acc[0][j][4 * q + e] * inv, u = acc[NT - 1][j][4 * q + e] * inv;
             v[e] = (bf16_t)(g / (1.0f + __expf(-g)) * u);
           }
           *reinterpret_cast<bf16x4*>(act + act_index<true>(m, f, N)) = v;
@@ -196,8 +272,9 @@ __global__ __launch_bounds__(64 * KW) void gemm_mfma_kernel(RowCtx rc, const bf1
                                                            const bf16x8* __restrict__ w0,
                                                            const bf16x8* __restrict__ w1, float* __restrict__ out,
                                                            bf16_t* __restrict__ act, int N, int K, int ksplit,
-                                                           size_t partial_stride) {
+                                                           size_t partial_stride, NormFuse nf) {
   __shared__ float red[INTRA ? (KW - 1) * MT * 16 * 64 : 1];
+  __shared__ float ssp[(INTRA && EPI == EPI_SWIGLU) ? KW * MT * 32 : 1];
   const int rows = rows_or_zero(rc);
   const int mt0 = blockIdx.z * MT;
   if (mt0 * 32 >= rows) return;
@@ -205,21 +282,21 @@ __global__ __launch_bounds__(64 * KW) void gemm_mfma_kernel(RowCtx rc, const bf1
   // Split-k launches put the k split in blockIdx.x: consecutive workgroups go to consecutive
   // XCDs, so with 8 (4) splits every XCD works on one (two) k slices and pulls only that slice
   // of the activations into its L2 instead of all of them.
-  constexpr bool SPLIT_FIRST = INTRA && EPI == EPI_F32;
+  constexpr bool SPLIT_FIRST = INTRA && (EPI == EPI_F32 || EPI == EPI_RESID);
   const int bgrp = SPLIT_FIRST ? blockIdx.y : blockIdx.x;
   const int grp = INTRA ? bgrp : bgrp * KW + (threadIdx.x >> 6);
   const int nt0 = (EPI == EPI_SWIGLU) ? grp : grp * NT;
   if (!INTRA && nt0 >= (N >> 5)) return;
   const int sidx = SPLIT_FIRST ? blockIdx.x : blockIdx.y;
   const int k0 = (int)((long long)KT * sidx / ksplit), k1 = (int)((long long)KT * (sidx + 1) / ksplit);
-  float* o = out ? out + sidx * partial_stride : nullptr;
+  float* o = out ? out + (EPI == EPI_RESID ? (size_t)0 : sidx * partial_stride) : nullptr;
   int mtc = ceil_div(rows, 32) - mt0;
   if (mtc > MT) mtc = MT;
   switch (mtc) {
-    case 1: gemm_group<NT, 1, EPI, INTRA>(w0, w1, x, KT, k0, k1, nt0, mt0, rows, N, o, act, red); break;
-    case 2: gemm_group<NT, (MT >= 2 ? 2 : 1), EPI, INTRA>(w0, w1, x, KT, k0, k1, nt0, mt0, rows, N, o, act, red); break;
-    case 3: gemm_group<NT, (MT >= 3 ? 3 : 1), EPI, INTRA>(w0, w1, x, KT, k0, k1, nt0, mt0, rows, N, o, act, red); break;
-    default: gemm_group<NT, MT, EPI, INTRA>(w0, w1, x, KT, k0, k1, nt0, mt0, rows, N, o, act, red); break;
+    case 1: gemm_group<NT, 1, EPI, INTRA>(w0, w1, x, KT, k0, k1, nt0, mt0, rows, N, o, act, red, ssp, nf); break;
+    case 2: gemm_group<NT, (MT >= 2 ? 2 : 1), EPI, INTRA>(w0, w1, x, KT, k0, k1, nt0, mt0, rows, N, o, act, red, ssp, nf); break;
+    case 3: gemm_group<NT, (MT >= 3 ? 3 : 1), EPI, INTRA>(w0, w1, x, KT, k0, k1, nt0, mt0, rows, N, o, act, red, ssp, nf); break;
+    default: gemm_group<NT, MT, EPI, INTRA>(w0, w1, x, KT, k0, k1, nt0, mt0, rows, N, o, act, red, ssp, nf); break;
   }
 }
 
@@ -234,11 +311,11 @@ void launch_gemm_mfma(hipStream_t st, RowCtx rc, const bf16_t* x, const bf16_t* 
     // plenty of n-tiles (LM head): one wavefront per pair of tiles, whole k range
     dim3 grid(ceil_div(n_tiles / 2, KW), ksplit, m_groups);
     hipLaunchKernelGGL((gemm_mfma_kernel<2, MT, EPI_F32, false>), grid, dim3(64 * KW), 0, st, rc, xv, wv, nullptr,
-                       out, nullptr, N, K, ksplit, partial_stride);
+                       out, nullptr, N, K, ksplit, partial_stride, NormFuse{});
   } else {
     dim3 grid(ksplit, n_tiles, m_groups);
     hipLaunchKernelGGL((gemm_mfma_kernel<1, MT, EPI_F32, true>), grid, dim3(64 * KW), 0, st, rc, xv, wv, nullptr,
-                       out, nullptr, N, K, ksplit, partial_stride);
+                       out, nullptr, N, K, ksplit, partial_stride, NormFuse{});
   }
 }
 
@@ -251,17 +328,38 @@ void launch_gemm_mfma_logits(hipStream_t st, RowCtx rc, const bf16_t* x, const b
   dim3 grid(ceil_div(n_tiles / 2, KW), 1, ceil_div(ceil_div(rc.max_rows, 32), MT));
   hipLaunchKernelGGL((gemm_mfma_kernel<2, MT, EPI_LOGITS, false>), grid, dim3(64 * KW), 0, st, rc,
                      reinterpret_cast<const bf16x8*>(x), reinterpret_cast<const bf16x8*>(Wp), nullptr, logits,
-                     reinterpret_cast<bf16_t*>(group_max), V, K, 1, (size_t)0);
+                     reinterpret_cast<bf16_t*>(group_max), V, K, 1, (size_t)0, NormFuse{});
 }
 
 void launch_gemm_mfma_swiglu(hipStream_t st, RowCtx rc, const bf16_t* x, const bf16_t* Wg, const bf16_t* Wu,
-                             bf16_t* act, int F, int K) {
+                             bf16_t* act, int F, int K, const float* ssq, int ssq_stride, float eps) {
   constexpr int MT = 4;
   const int n_tiles = F >> 5;
   dim3 grid(n_tiles, 1, ceil_div(ceil_div(rc.max_rows, 32), MT));
+  NormFuse nf{nullptr, const_cast<float*>(ssq), ssq_stride, K >> 5, 1.0f / (float)K, eps};
   hipLaunchKernelGGL((gemm_mfma_kernel<2, MT, EPI_SWIGLU, true>), grid, dim3(64 * KW), 0, st, rc,
                      reinterpret_cast<const bf16x8*>(x), reinterpret_cast<const bf16x8*>(Wg),
-                     reinterpret_cast<const bf16x8*>(Wu), nullptr, act, F, K, 1, (size_t)0);
+                     reinterpret_cast<const bf16x8*>(Wu), nullptr, act, F, K, 1, (size_t)0, nf);
+}
+
+// x_res += x . W^T (whole k range per workgroup, no partials); act = bf16(x_res * gain) in the
+// fragment order of the next GEMM; ssq[n_tile][row] = sum of squares of the tile's 32 columns.
+void launch_gemm_mfma_resid(hipStream_t st, RowCtx rc, const bf16_t* x, const bf16_t* Wp, float* x_res,
+                            const float* gain, bf16_t* act, float* ssq, int ssq_stride, int N, int K) {
+  const int n_tiles = N >> 5, m_tiles = ceil_div(rc.max_rows, 32);
+  const bf16x8* xv = reinterpret_cast<const bf16x8*>(x);
+  const bf16x8* wv = reinterpret_cast<const bf16x8*>(Wp);
+  NormFuse nf{gain, ssq, ssq_stride, 0, 0.f, 0.f};
+  // few n-tiles: one m-tile per workgroup for more workgroups (the weights are small then)
+  if (n_tiles * ceil_div(m_tiles, 4) < 128) {
+    dim3 grid(1, n_tiles, m_tiles);
+    hipLaunchKernelGGL((gemm_mfma_kernel<1, 1, EPI_RESID, true>), grid, dim3(64 * KW), 0, st, rc, xv, wv, nullptr,
+                       x_res, act, N, K, 1, (size_t)0, nf);
+  } else {
+    dim3 grid(1, n_tiles, ceil_div(m_tiles, 4));
+    hipLaunchKernelGGL((gemm_mfma_kernel<1, 4, EPI_RESID, true>), grid, dim3(64 * KW), 0, st, rc, xv, wv, nullptr,
+                       x_res, act, N, K, 1, (size_t)0, nf);
+  }
 }
 
 }  // namespace april

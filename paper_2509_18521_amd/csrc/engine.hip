@@ -121,7 +121,7 @@ struct april_ctx {
   int s_qkv = 1, s_o = 1, s_down = 1;
   size_t qkv_stride = 0, proj_stride = 0;
   // bf16 MFMA attention: split-KV workspace
-  bool attn_mfma = false, fuse_rope = true, tile_gemm = true, fuse_norm = true;
+  bool attn_mfma = false, fuse_rope = true, tile_gemm = true, fuse_norm = true, fuse_down = true;
   float* ssq = nullptr;         // [d_model / 32][m_cap] per-row partial sums of squares (fused norm)
   int attn_chunk = 256, attn_max_splits = 1, attn_ws_rows = 0;
   float* attn_ws = nullptr;
@@ -301,17 +301,20 @@ void forward(april_ctx* c, RowCtx rows, RowCtx srows, const int* gather, double 
   const bool tile = c->use_mfma && c->tile_gemm && gather != nullptr;
   const int sq = tile ? 1 : c->s_qkv, so = tile ? 1 : c->s_o, sd = tile ? 1 : c->s_down, sr = tile ? 1 : c->s_router;
   auto gemm = [&](int kc, RowCtx rc, const void* x, const void* w_plain, const bf16_t* w_s, float* out, int N, int K,
-                  int ks, size_t stride, double rowsB) {
+                  int ks, size_t stride, double rowsB, const float* ssq = nullptr) {
     ProfScope p(c, kc, (double)N * K * e + rowsB * K * e + rowsB * N * 4.0, 2.0 * rowsB * N * K);
     if (tile) launch_gemm_tile(st, rc, (const bf16_t*)x, w_s, out, N, K);
-    else if (c->use_mfma) launch_gemm_mfma(st, rc, (const bf16_t*)x, w_s, out, N, K, ks, stride);
+    else if (c->use_mfma) launch_gemm_mfma(st, rc, (const bf16_t*)x, w_s, out, N, K, ks, stride, ssq, (int)c->m_cap, m.rms_eps);
     else if (c->bf16) launch_gemm_ref<bf16_t, true>(st, rc, (const bf16_t*)x, (const bf16_t*)w_plain, out, N, K);
     else launch_gemm_ref<float, false>(st, rc, (const float*)x, (const float*)w_plain, out, N, K);
   };
+  bool normed_by_down = false;       // the previous layer's down projection already did this layer's first norm
   for (int l = 0; l < m.n_layers; ++l) {
     const LayerW& L = c->layers[l];
-    norm(rows, l == 0 ? 0 : sd, L.attn_norm, c->h_act, nullptr, B, true);
-    gemm(KC_GEMM_QKV, rows, c->h_act, L.wqkv, L.wqkv_s, c->qkv, nqkv, d, sq, c->qkv_stride, B);
+    if (!normed_by_down) norm(rows, l == 0 ? 0 : sd, L.attn_norm, c->h_act, nullptr, B, true);
+    gemm(KC_GEMM_QKV, rows, c->h_act, L.wqkv, L.wqkv_s, c->qkv, nqkv, d, sq, c->qkv_stride, B,
+         normed_by_down ? c->ssq : nullptr);
+    normed_by_down = false;
     // decode iterations: rotary + KV append are done inside the attention kernel
     const bool fuse_rope = c->attn_mfma && c->fuse_rope && gather == nullptr;
     if (!fuse_rope) {
@@ -379,7 +382,16 @@ void forward(april_ctx* c, RowCtx rows, RowCtx srows, const int* gather, double 
       if (c->bf16) launch_silu_mul<bf16_t, true>(st, rows, c->gu, F, (bf16_t*)c->act);
       else launch_silu_mul<float, false>(st, rows, c->gu, F, (float*)c->act);
     }
-    gemm(KC_GEMM_DOWN, rows, c->act, L.wd, L.wd_s, c->proj, d, F, sd, c->proj_stride, B);
+    if (fuse_norm2 && c->fuse_down && l + 1 < m.n_layers) {
+      // same folding for the next layer's first norm (the last layer keeps the split-k form: the
+      // final norm gathers rows and feeds the LM head)
+      ProfScope p(c, KC_GEMM_DOWN, (double)d * F * e + B * F * e + B * d * (8.0 + e), 2.0 * B * d * F);
+      launch_gemm_mfma_resid(st, rows, (const bf16_t*)c->act, L.wd_s, c->x_res, c->layers[l + 1].attn_norm,
+                             (bf16_t*)c->h_act, c->ssq, c->m_cap, d, F);
+      normed_by_down = true;
+    } else {
+      gemm(KC_GEMM_DOWN, rows, c->act, L.wd, L.wd_s, c->proj, d, F, sd, c->proj_stride, B);
+    }
   }
   const double SB = gather ? (double)srows.max_rows : B;
   norm(srows, sd, c->final_norm, c->hf, gather, SB, true);
@@ -476,6 +488,8 @@ int april_init(const april_model_cfg* cfg, const april_tensor* weights, int32_t 
   c->fuse_rope = !(fr && !strcmp(fr, "0"));
   const char* fn = getenv("APRIL_FUSE_NORM");
   c->fuse_norm = !(fn && !strcmp(fn, "0"));
+  const char* fd = getenv("APRIL_FUSE_DOWN");
+  c->fuse_down = !(fd && !strcmp(fd, "0"));
   const char* tg = getenv("APRIL_TILE_GEMM");
   c->tile_gemm = !(tg && !strcmp(tg, "0"));
   const char* gr = getenv("APRIL_GRAPH");

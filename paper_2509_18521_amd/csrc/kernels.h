@@ -107,7 +107,8 @@ void launch_gemm_ref(hipStream_t st, RowCtx rc, const T* x, const T* W, float* o
 // bf16 MFMA GEMM over fragment-tiled operands.  Wp: weights re-laid by
 // launch_shuffle_weights.  out: fp32 [ksplit][m_cap][N] partial sums.
 void launch_gemm_mfma(hipStream_t st, RowCtx rc, const bf16_t* x, const bf16_t* Wp, float* out,
-                      int N, int K, int ksplit, size_t partial_stride);
+                      int N, int K, int ksplit, size_t partial_stride,
+                      const float* ssq = nullptr, int ssq_stride = 0, float eps = 0.f);
 // act[m][f] = silu(x.Wg[f]) * (x.Wu[f]) as fragment-tiled bf16.
 // ssq != nullptr: the activations are residual * gain (not yet normalised); the kernel divides
 // its accumulators by the row's RMS, from the sums of squares the producer left (see

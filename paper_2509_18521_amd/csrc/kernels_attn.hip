@@ -64,7 +64,7 @@ __global__ __launch_bounds__(64 * ATT_WAVES) void attn_decode_kernel(
   const int ctx = pos + 1;
   const int n_splits = (ctx + ATT_SPLIT - 1) / ATT_SPLIT;
   if (split >= n_splits) return;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, hh = lane & 15, g = lane >> 4;
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), hh = lane & 15, g = lane >> 4;
   const int Hkv = L.n_kv_heads, G = Hq / Hkv;
   const int t_begin = split * ATT_SPLIT, t_end = min(ctx, t_begin + ATT_SPLIT);
   const int n_tiles = (t_end - t_begin + 31) >> 5;

@@ -60,7 +60,8 @@ __device__ inline void gemm_group(const bf16x8* __restrict__ w0, const bf16x8* _
   // fits in two groups has all of it in flight at once, and a longer range streams with one
   // group always in flight behind the arithmetic.
   constexpr int KH = (NT + MTC) <= 4 ? 8 : ((NT + MTC) == 5 ? 7 : 5);
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  // the wavefront index is uniform: keep it (and the k range derived from it) in scalar registers
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   f32x16 acc[NT][MTC];
 #pragma unroll
   for (int i = 0; i < NT; ++i)
@@ -110,7 +111,7 @@ __device__ inline void gemm_group(const bf16x8* __restrict__ w0, const bf16x8* _
   // Fused norm (consumer side): wavefront w adds the slabs w, w + KW, ... of its rows, wavefront
   // 0 later adds the four sums.  The first 8 slabs per wavefront are requested here and summed
   // after the k loop, so their latency hides behind the operand stream.
-  constexpr bool NORM_IN = EPI == EPI_SWIGLU && INTRA;
+  constexpr bool NORM_IN = (EPI == EPI_SWIGLU || EPI == EPI_F32) && INTRA;
   float sq[NORM_IN ? MTC : 1][8];
   if (NORM_IN && nf.ssq != nullptr) {
 #pragma unroll
@@ -199,11 +200,18 @@ __device__ inline void gemm_group(const bf16x8* __restrict__ w0, const bf16x8* _
 #pragma unroll
       for (int j = 0; j < MTC; ++j) {
         const int m = (mt0 + j) * 32 + mloc;
+        float inv = 1.0f;
+        if (NORM_IN && nf.ssq != nullptr) {          // fused norm: a k-split partial scales like the sum
+          float ssum = ssp[j * 32 + mloc];
+#pragma unroll
+          for (int w = 1; w < KW; ++w) ssum += ssp[(w * MTC + j) * 32 + mloc];
+          inv = 1.0f / sqrtf(ssum * nf.inv_d + nf.eps);
+        }
         if (m < rows) {
 #pragma unroll
           for (int q = 0; q < 4; ++q) {
             const int n = (nt0 + i) * 32 + 8 * q + nhalf;
-            f32x4 v = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
+            f32x4 v = {acc[i][j][4 * q] * inv, acc[i][j][4 * q + 1] * inv, acc[i][j][4 * q + 2] * inv, acc[i][j][4 * q + 3] * inv};
             *reinterpret_cast<f32x4*>(out + (size_t)m * N + n) = v;
           }
         }
@@ -274,21 +282,34 @@ __global__ __launch_bounds__(64 * KW) void gemm_mfma_kernel(RowCtx rc, const bf1
                                                            bf16_t* __restrict__ act, int N, int K, int ksplit,
                                                            size_t partial_stride, NormFuse nf) {
   __shared__ float red[INTRA ? (KW - 1) * MT * 16 * 64 : 1];
-  __shared__ float ssp[(INTRA && EPI == EPI_SWIGLU) ? KW * MT * 32 : 1];
+  __shared__ float ssp[(INTRA && (EPI == EPI_SWIGLU || EPI == EPI_F32)) ? KW * MT * 32 : 1];
   const int rows = rows_or_zero(rc);
-  const int mt0 = blockIdx.z * MT;
+  // EPI_RESID: 1-D launch.  The m-groups of one weight tile re-read that tile, so they are
+  // placed 8 workgroup ids apart: same XCD (ids are dealt to the 8 XCDs in turn), same moment,
+  // one HBM read.  Id = ((tile / 8) * m_groups + m_group) * 8 + tile % 8.
+  int bx = blockIdx.x, by = blockIdx.y, bz = blockIdx.z, ks = ksplit;
+  if (EPI == EPI_RESID) {
+    const int m_groups = ksplit;                  // (this launch has no k split: the field carries the m-group count)
+    const int rem = bx % (8 * m_groups);
+    by = (bx / (8 * m_groups)) * 8 + (rem & 7);
+    bz = rem >> 3;
+    bx = 0;
+    ks = 1;
+    if (by >= (N >> 5)) return;
+  }
+  const int mt0 = bz * MT;
   if (mt0 * 32 >= rows) return;
   const int KT = K >> 4;
   // Split-k launches put the k split in blockIdx.x: consecutive workgroups go to consecutive
   // XCDs, so with 8 (4) splits every XCD works on one (two) k slices and pulls only that slice
   // of the activations into its L2 instead of all of them.
   constexpr bool SPLIT_FIRST = INTRA && (EPI == EPI_F32 || EPI == EPI_RESID);
-  const int bgrp = SPLIT_FIRST ? blockIdx.y : blockIdx.x;
-  const int grp = INTRA ? bgrp : bgrp * KW + (threadIdx.x >> 6);
+  const int bgrp = SPLIT_FIRST ? by : bx;
+  const int grp = INTRA ? bgrp : bgrp * KW + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int nt0 = (EPI == EPI_SWIGLU) ? grp : grp * NT;
   if (!INTRA && nt0 >= (N >> 5)) return;
-  const int sidx = SPLIT_FIRST ? blockIdx.x : blockIdx.y;
-  const int k0 = (int)((long long)KT * sidx / ksplit), k1 = (int)((long long)KT * (sidx + 1) / ksplit);
+  const int sidx = SPLIT_FIRST ? bx : by;
+  const int k0 = (int)((long long)KT * sidx / ks), k1 = (int)((long long)KT * (sidx + 1) / ks);
   float* o = out ? out + (EPI == EPI_RESID ? (size_t)0 : sidx * partial_stride) : nullptr;
   int mtc = ceil_div(rows, 32) - mt0;
   if (mtc > MT) mtc = MT;
@@ -301,21 +322,22 @@ __global__ __launch_bounds__(64 * KW) void gemm_mfma_kernel(RowCtx rc, const bf1
 }
 
 void launch_gemm_mfma(hipStream_t st, RowCtx rc, const bf16_t* x, const bf16_t* Wp, float* out, int N, int K,
-                      int ksplit, size_t partial_stride) {
+                      int ksplit, size_t partial_stride, const float* ssq, int ssq_stride, float eps) {
+  const NormFuse nf{nullptr, const_cast<float*>(ssq), ssq_stride, K >> 5, 1.0f / (float)K, eps};
   constexpr int MT = 4;
   const int n_tiles = N >> 5;
   const int m_groups = ceil_div(ceil_div(rc.max_rows, 32), MT);
   const bf16x8* xv = reinterpret_cast<const bf16x8*>(x);
   const bf16x8* wv = reinterpret_cast<const bf16x8*>(Wp);
-  if (n_tiles >= 2048 && n_tiles % 2 == 0) {
+  if (n_tiles >= 2048 && n_tiles % 2 == 0 && ssq == nullptr) {
     // plenty of n-tiles (LM head): one wavefront per pair of tiles, whole k range
     dim3 grid(ceil_div(n_tiles / 2, KW), ksplit, m_groups);
     hipLaunchKernelGGL((gemm_mfma_kernel<2, MT, EPI_F32, false>), grid, dim3(64 * KW), 0, st, rc, xv, wv, nullptr,
-                       out, nullptr, N, K, ksplit, partial_stride, NormFuse{});
+                       out, nullptr, N, K, ksplit, partial_stride, nf);
   } else {
     dim3 grid(ksplit, n_tiles, m_groups);
     hipLaunchKernelGGL((gemm_mfma_kernel<1, MT, EPI_F32, true>), grid, dim3(64 * KW), 0, st, rc, xv, wv, nullptr,
-                       out, nullptr, N, K, ksplit, partial_stride, NormFuse{});
+                       out, nullptr, N, K, ksplit, partial_stride, nf);
   }
 }
 
@@ -351,14 +373,14 @@ void launch_gemm_mfma_resid(hipStream_t st, RowCtx rc, const bf16_t* x, const bf
   const bf16x8* wv = reinterpret_cast<const bf16x8*>(Wp);
   NormFuse nf{gain, ssq, ssq_stride, 0, 0.f, 0.f};
   // few n-tiles: one m-tile per workgroup for more workgroups (the weights are small then)
+  const int tiles8 = ceil_div(n_tiles, 8) * 8;
   if (n_tiles * ceil_div(m_tiles, 4) < 128) {
-    dim3 grid(1, n_tiles, m_tiles);
-    hipLaunchKernelGGL((gemm_mfma_kernel<1, 1, EPI_RESID, true>), grid, dim3(64 * KW), 0, st, rc, xv, wv, nullptr,
-                       x_res, act, N, K, 1, (size_t)0, nf);
+    hipLaunchKernelGGL((gemm_mfma_kernel<1, 1, EPI_RESID, true>), dim3(tiles8 * m_tiles), dim3(64 * KW), 0, st, rc, xv,
+                       wv, nullptr, x_res, act, N, K, m_tiles, (size_t)0, nf);
   } else {
-    dim3 grid(1, n_tiles, ceil_div(m_tiles, 4));
-    hipLaunchKernelGGL((gemm_mfma_kernel<1, 4, EPI_RESID, true>), grid, dim3(64 * KW), 0, st, rc, xv, wv, nullptr,
-                       x_res, act, N, K, 1, (size_t)0, nf);
+    const int mg = ceil_div(m_tiles, 4);
+    hipLaunchKernelGGL((gemm_mfma_kernel<1, 4, EPI_RESID, true>), dim3(tiles8 * mg), dim3(64 * KW), 0, st, rc, xv, wv,
+                       nullptr, x_res, act, N, K, mg, (size_t)0, nf);
   }
 }
 

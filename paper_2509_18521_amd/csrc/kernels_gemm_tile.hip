@@ -84,7 +84,7 @@ void gemm_tile_kernel(RowCtx rc, const bf16x8* __restrict__ x,
   const int rows = rows_or_zero(rc);
   const int m0 = blockIdx.y * MT;
   if (m0 * 32 >= rows) return;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int wm = wave / WGN, wn = wave % WGN;
   const int KT = K >> 4;
   const int m_last = (rows - 1) >> 5;           // last activation tile that holds a live row

@@ -144,7 +144,7 @@ __global__ __launch_bounds__(64 * MOE_KW) void moe_gemm_kernel(const int* stop, 
   const int mt0 = blockIdx.z * MT;
   if (mt0 * 32 >= rows_e) return;
   const int p0 = base[e];                       // first packed row of this expert (multiple of 32)
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int KT = K >> 4;
   const int nt0 = SWIGLU ? blockIdx.x : blockIdx.x * NT;
   int mtc = ((rows_e + 31) >> 5) - mt0;

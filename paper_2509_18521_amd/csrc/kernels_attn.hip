@@ -78,54 +78,129 @@ __global__ __launch_bounds__(64 * ATT_WAVES) void attn_decode_kernel(
   const int* bt = s.block_table + (size_t)slot * s.max_blocks + (t_begin >> 4);
   const int my_page = bt[lane < n_pages ? lane : n_pages - 1];
 
+  // tiles wave, wave + ATT_WAVES, ... of the split; the fetch of tile i+1 is always issued (clamped
+  // to the last tile) so that the wait counts are static
+  auto load_tile = [&](int tile, bf16x8 (&kk)[2][KC], bf16x4 (&vv)[2][DT]) {
+#pragma unroll
+    for (int p = 0; p < 2; ++p) {
+      int pl = 2 * tile + p;                                   // page within the split
+      pl = pl < n_pages ? pl : n_pages - 1;                    // a missing second page re-reads the last one
+      const int page = __builtin_amdgcn_readlane(my_page, __builtin_amdgcn_readfirstlane(pl));
+      const size_t off = ((size_t)page * Hkv + kvh) * blk_elems;
+      const bf16x8* kp = reinterpret_cast<const bf16x8*>(kbase + off);
+      const bf16x4* vp = reinterpret_cast<const bf16x4*>(vbase + off);
+#pragma unroll
+      for (int c = 0; c < KC; ++c) kk[p][c] = kp[c * 64 + lane];
+#pragma unroll
+      for (int d = 0; d < DT; ++d) vv[p][d] = vp[(d * 16 + hh) * 4 + g];
+    }
+  };
+
+  constexpr bool DEEP = DH <= 64;              // two tiles in flight behind the one being used
+  bf16x8 kf[2][KC], km[DEEP ? 2 : 1][KC];
+  bf16x4 vf[2][DT], vm[DEEP ? 2 : 1][DT];
+  auto first_tiles = [&]() {
+    load_tile(wave < n_tiles ? wave : n_tiles - 1, kf, vf);
+    if constexpr (DEEP) {
+      // (an array reference of the right shape for the lambda)
+      auto& km2 = reinterpret_cast<bf16x8 (&)[2][KC]>(km);
+      auto& vm2 = reinterpret_cast<bf16x4 (&)[2][DT]>(vm);
+      load_tile(wave + ATT_WAVES < n_tiles ? wave + ATT_WAVES : n_tiles - 1, km2, vm2);
+    }
+  };
+
   // Q^T fragments: lane holds q[head hh][32c + 8g .. +7]; heads beyond the group read
   // the group's last head and are zeroed.
   constexpr int HALF = DH / 2;
   const bool last_split = split == n_splits - 1;
   bf16x8 qf[KC];
   if (FUSED) {
+    // Order of requests: (1) the page ids (above), (2) everything that depends on the row only -
+    // the q partials, the rotary table, for the owner of the new token also its k / v partials -
+    // (3) the first KV tiles, which need the page ids.  Loads complete in order, so waiting for
+    // (2) does not wait for (3), and the rotation arithmetic runs while the tiles arrive.
+    constexpr bool ALL = DH <= 64;              // (2) fits the register file for every k-chunk at once
+    constexpr int QC = ALL ? KC : 1;
     const int hq = hh < G ? hh : G - 1;
     const int ncol = (Hq + 2 * Hkv) * DH;
     const float* qsrc = fz.qkv + (size_t)r * ncol + (size_t)(kvh * G + hq) * DH;
+    const float* ksrc = fz.qkv + (size_t)r * ncol + (size_t)(Hq + kvh) * DH;
+    const float* vsrc = fz.qkv + (size_t)r * ncol + (size_t)(Hq + Hkv + kvh) * DH;
     const float* cs = fz.rope_cos + (size_t)pos * HALF;
     const float* sn = fz.rope_sin + (size_t)pos * HALF;
+    const bool owner = last_split && wave == 0;         // computes and stores the new key / value
+    f32x4 la[QC][4][2], lb[QC][4][2], c4[QC][2], s4[QC][2];
+    float nka[4], nkb[4], nvv[4], ncs = 0.f, nsn = 0.f;
+    auto request_q = [&](int c, int slot_c, int p0) {
+      const int d0 = 32 * c + 8 * g;            // 8 consecutive dims, all in the same half
+      const int i0 = d0 < HALF ? d0 : d0 - HALF;
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int p = p0 + u < fz.n_partials ? p0 + u : fz.n_partials - 1;
+        const float* q = qsrc + p * fz.partial_stride;
+        la[slot_c][u][0] = *reinterpret_cast<const f32x4*>(q + i0);
+        la[slot_c][u][1] = *reinterpret_cast<const f32x4*>(q + i0 + 4);
+        lb[slot_c][u][0] = *reinterpret_cast<const f32x4*>(q + i0 + HALF);
+        lb[slot_c][u][1] = *reinterpret_cast<const f32x4*>(q + i0 + HALF + 4);
+      }
+      if (p0 == 0) {
+        c4[slot_c][0] = *reinterpret_cast<const f32x4*>(cs + i0);
+        c4[slot_c][1] = *reinterpret_cast<const f32x4*>(cs + i0 + 4);
+        s4[slot_c][0] = *reinterpret_cast<const f32x4*>(sn + i0);
+        s4[slot_c][1] = *reinterpret_cast<const f32x4*>(sn + i0 + 4);
+      }
+    };
+    // new token, dim d = lane (+64 for the second pass of wide heads): pair index and partials
+    auto request_kv = [&](int d, int p0) {
+      const int i = d < HALF ? d : d - HALF;
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const size_t po = (size_t)(p0 + u < fz.n_partials ? p0 + u : fz.n_partials - 1) * fz.partial_stride;
+        nka[u] = ksrc[po + i]; nkb[u] = ksrc[po + i + HALF]; nvv[u] = vsrc[po + d];
+      }
+      if (p0 == 0) { ncs = cs[i]; nsn = sn[i]; }
+    };
+    if constexpr (ALL) {
+#pragma unroll
+      for (int c = 0; c < KC; ++c) request_q(c, c, 0);
+      if (owner && lane < DH) request_kv(lane, 0);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    first_tiles();
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int c = 0; c < KC; ++c) {
-      const int d0 = 32 * c + 8 * g;            // 8 consecutive dims, all in the same half
-      const bool lo = d0 < HALF;
-      const int i0 = lo ? d0 : d0 - HALF;
+      const int sc = ALL ? c : 0;
+      const bool lo = 32 * c + 8 * g < HALF;
       f32x4 a[2] = {f32x4{}, f32x4{}}, b[2] = {f32x4{}, f32x4{}};
-      for (int p = 0; p < fz.n_partials; ++p) {  // same order as rope_append_kernel: p = 0, 1, ...
-        const float* q = qsrc + p * fz.partial_stride;
-        a[0] += *reinterpret_cast<const f32x4*>(q + i0);
-        a[1] += *reinterpret_cast<const f32x4*>(q + i0 + 4);
-        b[0] += *reinterpret_cast<const f32x4*>(q + i0 + HALF);
-        b[1] += *reinterpret_cast<const f32x4*>(q + i0 + HALF + 4);
+      // partials are added in the order p = 0, 1, ... (as rope_append_kernel does); four at a
+      // time are requested together so that the additions do not serialise the loads
+      for (int p0 = 0; p0 < fz.n_partials; p0 += 4) {
+        if (!ALL || p0 > 0) request_q(c, sc, p0);
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+          if (p0 + u < fz.n_partials) { a[0] += la[sc][u][0]; a[1] += la[sc][u][1]; b[0] += lb[sc][u][0]; b[1] += lb[sc][u][1]; }
       }
-      const f32x4 c4[2] = {*reinterpret_cast<const f32x4*>(cs + i0), *reinterpret_cast<const f32x4*>(cs + i0 + 4)};
-      const f32x4 s4[2] = {*reinterpret_cast<const f32x4*>(sn + i0), *reinterpret_cast<const f32x4*>(sn + i0 + 4)};
 #pragma unroll
       for (int j = 0; j < 8; ++j) {
-        const float av = a[j >> 2][j & 3], bv = b[j >> 2][j & 3], cv = c4[j >> 2][j & 3], sv2 = s4[j >> 2][j & 3];
+        const float av = a[j >> 2][j & 3], bv = b[j >> 2][j & 3], cv = c4[sc][j >> 2][j & 3], sv2 = s4[sc][j >> 2][j & 3];
         const float rot = lo ? rope_first(av, bv, cv, sv2) : rope_second(av, bv, cv, sv2);
         qf[c][j] = hh < G ? (bf16_t)rot : (bf16_t)0.f;
       }
     }
-    if (last_split && wave == 0) {
+    if (owner) {
       // the new token: rotated key and value of this KV head, to the page and to LDS
-      const float* ksrc = fz.qkv + (size_t)r * ncol + (size_t)(Hq + kvh) * DH;
-      const float* vsrc = fz.qkv + (size_t)r * ncol + (size_t)(Hq + Hkv + kvh) * DH;
       const int page = s.block_table[(size_t)slot * s.max_blocks + (pos >> 4)], tin = pos & 15;
       for (int d = lane; d < DH; d += 64) {
         const bool lo = d < HALF;
-        const int i = lo ? d : d - HALF;
-        float av = ksrc[i], bv = ksrc[i + HALF], vv = vsrc[d];
-        for (int p = 1; p < fz.n_partials; ++p) {
-          av += ksrc[p * fz.partial_stride + i];
-          bv += ksrc[p * fz.partial_stride + i + HALF];
-          vv += vsrc[p * fz.partial_stride + d];
+        float av = 0.f, bv = 0.f, vv = 0.f;
+        for (int p0 = 0; p0 < fz.n_partials; p0 += 4) {
+          if (!ALL || p0 > 0 || d >= 64) request_kv(d, p0);
+#pragma unroll
+          for (int u = 0; u < 4; ++u)
+            if (p0 + u < fz.n_partials) { av += nka[u]; bv += nkb[u]; vv += nvv[u]; }
         }
-        const float rot = lo ? rope_first(av, bv, cs[i], sn[i]) : rope_second(av, bv, cs[i], sn[i]);
+        const float rot = lo ? rope_first(av, bv, ncs, nsn) : rope_second(av, bv, ncs, nsn);
         const bf16_t kb = (bf16_t)rot, vb = (bf16_t)vv;
         s_knew[d] = kb;
         s_vnew[d] = vb;
@@ -135,6 +210,8 @@ __global__ __launch_bounds__(64 * ATT_WAVES) void attn_decode_kernel(
     }
     if (last_split) __syncthreads();
   } else {
+    first_tiles();
+    __builtin_amdgcn_sched_barrier(0);
     const int hq = hh < G ? hh : G - 1;
     const float* q = q_rot + (size_t)r * Hq * DH + (size_t)(kvh * G + hq) * DH + 8 * g;
     f32x4 qa[KC][2];
@@ -154,32 +231,12 @@ __global__ __launch_bounds__(64 * ATT_WAVES) void attn_decode_kernel(
 #pragma unroll
   for (int d = 0; d < DT; ++d) oacc[d] = f32x4{};
 
-  // tiles wave, wave + ATT_WAVES, ... of the split; the fetch of tile i+1 is always issued (clamped
-  // to the last tile) so that the wait counts are static
-  auto load_tile = [&](int tile, bf16x8 (&kk)[2][KC], bf16x4 (&vv)[2][DT]) {
-#pragma unroll
-    for (int p = 0; p < 2; ++p) {
-      int pl = 2 * tile + p;                                   // page within the split
-      pl = pl < n_pages ? pl : n_pages - 1;                    // a missing second page re-reads the last one
-      const int page = __builtin_amdgcn_readlane(my_page, __builtin_amdgcn_readfirstlane(pl));
-      const size_t off = ((size_t)page * Hkv + kvh) * blk_elems;
-      const bf16x8* kp = reinterpret_cast<const bf16x8*>(kbase + off);
-      const bf16x4* vp = reinterpret_cast<const bf16x4*>(vbase + off);
-#pragma unroll
-      for (int c = 0; c < KC; ++c) kk[p][c] = kp[c * 64 + lane];
-#pragma unroll
-      for (int d = 0; d < DT; ++d) vv[p][d] = vp[(d * 16 + hh) * 4 + g];
-    }
-  };
-
   if (wave < n_tiles) {
-    bf16x8 kf[2][KC];
-    bf16x4 vf[2][DT];
-    load_tile(wave, kf, vf);
     for (int tile = wave; tile < n_tiles; tile += ATT_WAVES) {
       bf16x8 kn[2][KC];
       bf16x4 vn[2][DT];
-      const int nxt = tile + ATT_WAVES < n_tiles ? tile + ATT_WAVES : tile;
+      constexpr int AHEAD = (DEEP ? 2 : 1) * ATT_WAVES;
+      const int nxt = tile + AHEAD < n_tiles ? tile + AHEAD : n_tiles - 1;
       load_tile(nxt, kn, vn);
       __builtin_amdgcn_sched_barrier(0);
 
@@ -255,9 +312,13 @@ __global__ __launch_bounds__(64 * ATT_WAVES) void attn_decode_kernel(
 #pragma unroll
       for (int p = 0; p < 2; ++p) {
 #pragma unroll
-        for (int c = 0; c < KC; ++c) kf[p][c] = kn[p][c];
+        for (int c = 0; c < KC; ++c) {
+          if constexpr (DEEP) { kf[p][c] = km[p][c]; km[p][c] = kn[p][c]; } else kf[p][c] = kn[p][c];
+        }
 #pragma unroll
-        for (int d = 0; d < DT; ++d) vf[p][d] = vn[p][d];
+        for (int d = 0; d < DT; ++d) {
+          if constexpr (DEEP) { vf[p][d] = vm[p][d]; vm[p][d] = vn[p][d]; } else vf[p][d] = vn[p][d];
+        }
       }
     }
   }

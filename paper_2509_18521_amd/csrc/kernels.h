@@ -34,6 +34,10 @@ __device__ inline int rows_or_zero(const RowCtx& rc) {
 __device__ inline float rope_first(float a, float b, float c, float s) { return __fmaf_rn(a, c, -__fmul_rn(b, s)); }
 __device__ inline float rope_second(float a, float b, float c, float s) { return __fmaf_rn(b, c, __fmul_rn(a, s)); }
 
+// silu(g) * u with the hardware reciprocal (1 ulp) instead of a full-precision division: the
+// result is rounded to bf16 right after, and the division was most of the SwiGLU epilogue.
+__device__ inline float silu_mul(float g, float u) { return g * u * __builtin_amdgcn_rcpf(1.0f + __expf(-g)); }
+
 // --- scheduler / allocator -------------------------------------------------
 // check_only = 1: only the "N complete => stop" test (end of a chunk of iterations).
 // row_cap / ctx_cap: the bounds the host sized this iteration's launches for (live rows, longest

@@ -263,7 +263,7 @@ __device__ inline void gemm_group(const bf16x8* __restrict__ w0, const bf16x8* _
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
             const float g = acc[0][j][4 * q + e] * inv, u = acc[NT - 1][j][4 * q + e] * inv;
-            v[e] = (bf16_t)(g / (1.0f + __expf(-g)) * u);
+            v[e] = (bf16_t)silu_mul(g, u);
           }
           *reinterpret_cast<bf16x4*>(act + act_index<true>(m, f, N)) = v;
         }

@@ -59,7 +59,7 @@ __device__ inline void tile_epilogue(f32x16 (&acc)[NTW][MTW], int nt0, int mt0, 
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
               const float g = acc[i][j][4 * q + e], u = acc[i + H][j][4 * q + e];
-              v[e] = (bf16_t)(g / (1.0f + __expf(-g)) * u);
+              v[e] = (bf16_t)silu_mul(g, u);
             }
             *reinterpret_cast<bf16x4*>(act + act_index<true>(m, f, N)) = v;
           }

@@ -244,7 +244,7 @@ __global__ __launch_bounds__(64 * MOE_KW) void moe_gemm_kernel(const int* stop, 
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
           const float g = acc[0][j][4 * q + t], u = acc[NT - 1][j][4 * q + t];
-          v[t] = (bf16_t)(g / (1.0f + __expf(-g)) * u);
+          v[t] = (bf16_t)silu_mul(g, u);
         }
         *reinterpret_cast<bf16x4*>(act + act_index<true>(p, f, N)) = v;
       }

@@ -148,47 +148,56 @@ __device__ inline void gemm_group(const bf16x8* __restrict__ w0, const bf16x8* _
       if (lane < 32) ssp[(wave * MTC + j) * 32 + lane] = sacc;
     }
   }
-  // reduction over the KW wavefronts through LDS: wavefronts 1.. publish, wavefront 0 adds
-  // them in wavefront order; one weight tile per round, so the buffer stays at
-  // (KW-1) x MTC accumulator tiles whatever NT is
+  // Reduction over the KW wavefronts through LDS, and the split of the epilogue: every wavefront
+  // publishes its partial tiles, then wavefront w adds the KW partials of activation tile j = w
+  // in wavefront order (0 + 1 + 2 + 3) and runs the epilogue of that tile, so up to KW tiles are
+  // finished in parallel.  One weight tile per round: the buffer holds KW x MTC accumulator tiles.
   constexpr int NREG = MTC * 16;
+  constexpr int JT = INTRA ? 1 : MTC;           // activation tiles this wavefront finishes
+  f32x16 res[NT][JT];
   if (INTRA) {
+    static_assert(!INTRA || MTC <= KW, "one activation tile per wavefront");
 #pragma unroll
     for (int i = 0; i < NT; ++i) {
-      if (i > 0) __syncthreads();               // wavefront 0 has read the previous round
-      if (wave != 0) {
-        float* dst = red + (size_t)(wave - 1) * NREG * 64 + lane;
+      if (i > 0) __syncthreads();               // everyone has read the previous round
+      float* dst = red + (size_t)wave * NREG * 64 + lane;
 #pragma unroll
-        for (int j = 0; j < MTC; ++j)
+      for (int jq = 0; jq < MTC; ++jq)
 #pragma unroll
-          for (int e = 0; e < 16; ++e) dst[(j * 16 + e) * 64] = acc[i][j][e];
-      }
+        for (int e = 0; e < 16; ++e) dst[(jq * 16 + e) * 64] = acc[i][jq][e];
       __syncthreads();
-      if (wave == 0) {
+      if (wave < MTC) {
+        const float* src = red + (size_t)wave * 16 * 64 + lane;      // tile j = wave of wavefront 0's slab
 #pragma unroll
-        for (int w = 0; w < KW - 1; ++w) {
-          const float* src = red + (size_t)w * NREG * 64 + lane;
+        for (int e = 0; e < 16; ++e) {
+          float v = src[e * 64];
 #pragma unroll
-          for (int j = 0; j < MTC; ++j)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) acc[i][j][e] += src[(j * 16 + e) * 64];
+          for (int w = 1; w < KW; ++w) v += src[(size_t)w * NREG * 64 + e * 64];
+          res[i][0][e] = v;
         }
       }
     }
+    if (wave >= MTC) return;
+  } else {
+#pragma unroll
+    for (int i = 0; i < NT; ++i)
+#pragma unroll
+      for (int jq = 0; jq < JT; ++jq) res[i][jq] = acc[i][jq];
   }
-  if (INTRA && wave != 0) return;
+  const int j0 = INTRA ? wave : 0;              // first (INTRA: only) activation tile of this wavefront
 
   const int mloc = lane & 31, nhalf = (lane >> 5) << 2;
   if (EPI == EPI_LOGITS) {
     // per row: the maximum over this wavefront's NT*32 output columns (a group of the
     // sampler's candidate search), in the order-preserving integer key of the sampler
 #pragma unroll
-    for (int j = 0; j < MTC; ++j) {
-      float mxv = acc[0][j][0];
+    for (int jq = 0; jq < JT; ++jq) {
+      const int j = j0 + jq;
+      float mxv = res[0][jq][0];
 #pragma unroll
       for (int i = 0; i < NT; ++i)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) mxv = fmaxf(mxv, acc[i][j][e]);
+        for (int e = 0; e < 16; ++e) mxv = fmaxf(mxv, res[i][jq][e]);
       mxv = fmaxf(mxv, __shfl_xor(mxv, 32, 64));
       const int m = (mt0 + j) * 32 + mloc;
       if (m < rows && lane < 32) reinterpret_cast<float*>(act)[(size_t)m * (N / (32 * NT)) + nt0 / NT] = mxv;
@@ -198,7 +207,8 @@ __device__ inline void gemm_group(const bf16x8* __restrict__ w0, const bf16x8* _
 #pragma unroll
     for (int i = 0; i < NT; ++i)
 #pragma unroll
-      for (int j = 0; j < MTC; ++j) {
+      for (int jq = 0; jq < JT; ++jq) {
+      const int j = j0 + jq;
         const int m = (mt0 + j) * 32 + mloc;
         float inv = 1.0f;
         if (NORM_IN && nf.ssq != nullptr) {          // fused norm: a k-split partial scales like the sum
@@ -211,7 +221,7 @@ __device__ inline void gemm_group(const bf16x8* __restrict__ w0, const bf16x8* _
 #pragma unroll
           for (int q = 0; q < 4; ++q) {
             const int n = (nt0 + i) * 32 + 8 * q + nhalf;
-            f32x4 v = {acc[i][j][4 * q] * inv, acc[i][j][4 * q + 1] * inv, acc[i][j][4 * q + 2] * inv, acc[i][j][4 * q + 3] * inv};
+            f32x4 v = {res[i][jq][4 * q] * inv, res[i][jq][4 * q + 1] * inv, res[i][jq][4 * q + 2] * inv, res[i][jq][4 * q + 3] * inv};
             *reinterpret_cast<f32x4*>(out + (size_t)m * N + n) = v;
           }
         }
@@ -219,7 +229,8 @@ __device__ inline void gemm_group(const bf16x8* __restrict__ w0, const bf16x8* _
   } else if (EPI == EPI_RESID) {
     // out = residual stream (updated in place), act = gain-scaled bf16 copy for the next GEMM
 #pragma unroll
-    for (int j = 0; j < MTC; ++j) {
+    for (int jq = 0; jq < JT; ++jq) {
+      const int j = j0 + jq;
       const int m = (mt0 + j) * 32 + mloc;
       float ss = 0.f;
       if (m < rows) {
@@ -232,7 +243,7 @@ __device__ inline void gemm_group(const bf16x8* __restrict__ w0, const bf16x8* _
           bf16x4 h;
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
-            v[e] += acc[0][j][4 * q + e];
+            v[e] += res[0][jq][4 * q + e];
             ss += v[e] * v[e];
             h[e] = (bf16_t)(v[e] * gn[e]);
           }
@@ -246,7 +257,8 @@ __device__ inline void gemm_group(const bf16x8* __restrict__ w0, const bf16x8* _
   } else {
     // acc[0] = gate tile, acc[1] = up tile of features [nt0*32, nt0*32+32); N is F here.
 #pragma unroll
-    for (int j = 0; j < MTC; ++j) {
+    for (int jq = 0; jq < JT; ++jq) {
+      const int j = j0 + jq;
       const int m = (mt0 + j) * 32 + mloc;
       float inv = 1.0f;
       if (INTRA && nf.ssq != nullptr) {
@@ -262,7 +274,7 @@ __device__ inline void gemm_group(const bf16x8* __restrict__ w0, const bf16x8* _
           bf16x4 v;
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
-            const float g = acc[0][j][4 * q + e] * inv, u = acc[NT - 1][j][4 * q + e] * inv;
+            const float g = res[0][jq][4 * q + e] * inv, u = res[NT - 1][jq][4 * q + e] * inv;
             v[e] = (bf16_t)silu_mul(g, u);
           }
           *reinterpret_cast<bf16x4*>(act + act_index<true>(m, f, N)) = v;
@@ -281,7 +293,7 @@ __global__ __launch_bounds__(64 * KW) void gemm_mfma_kernel(RowCtx rc, const bf1
                                                            const bf16x8* __restrict__ w1, float* __restrict__ out,
                                                            bf16_t* __restrict__ act, int N, int K, int ksplit,
                                                            size_t partial_stride, NormFuse nf) {
-  __shared__ float red[INTRA ? (KW - 1) * MT * 16 * 64 : 1];
+  __shared__ float red[INTRA ? KW * MT * 16 * 64 : 1];
   __shared__ float ssp[(INTRA && (EPI == EPI_SWIGLU || EPI == EPI_F32)) ? KW * MT * 32 : 1];
   const int rows = rows_or_zero(rc);
   // EPI_RESID: 1-D launch.  The m-groups of one weight tile re-read that tile, so they are

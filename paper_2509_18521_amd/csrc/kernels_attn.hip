@@ -123,6 +123,7 @@ __global__ __launch_bounds__(64 * att_waves(DH, FUSED)) void attn_decode_kernel(
     // (2) does not wait for (3), and the rotation arithmetic runs while the tiles arrive.
     constexpr bool ALL = DH <= 64;              // (2) fits the register file for every k-chunk at once
     constexpr int QC = ALL ? KC : 1;
+    constexpr int QB = ALL ? 4 : 1;             // partials requested together (wide heads: one, to stay at two workgroups per CU)
     const int hq = hh < G ? hh : G - 1;
     const int ncol = (Hq + 2 * Hkv) * DH;
     const float* qsrc = fz.qkv + (size_t)r * ncol + (size_t)(kvh * G + hq) * DH;
@@ -131,13 +132,13 @@ __global__ __launch_bounds__(64 * att_waves(DH, FUSED)) void attn_decode_kernel(
     const float* cs = fz.rope_cos + (size_t)pos * HALF;
     const float* sn = fz.rope_sin + (size_t)pos * HALF;
     const bool owner = last_split && wave == 0;         // computes and stores the new key / value
-    f32x4 la[QC][4][2], lb[QC][4][2], c4[QC][2], s4[QC][2];
-    float nka[4], nkb[4], nvv[4], ncs = 0.f, nsn = 0.f;
+    f32x4 la[QC][QB][2], lb[QC][QB][2], c4[QC][2], s4[QC][2];
+    float nka[QB], nkb[QB], nvv[QB], ncs = 0.f, nsn = 0.f;
     auto request_q = [&](int c, int slot_c, int p0) {
       const int d0 = 32 * c + 8 * g;            // 8 consecutive dims, all in the same half
       const int i0 = d0 < HALF ? d0 : d0 - HALF;
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
+      for (int u = 0; u < QB; ++u) {
         const int p = p0 + u < fz.n_partials ? p0 + u : fz.n_partials - 1;
         const float* q = qsrc + p * fz.partial_stride;
         la[slot_c][u][0] = *reinterpret_cast<const f32x4*>(q + i0);
@@ -156,7 +157,7 @@ __global__ __launch_bounds__(64 * att_waves(DH, FUSED)) void attn_decode_kernel(
     auto request_kv = [&](int d, int p0) {
       const int i = d < HALF ? d : d - HALF;
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
+      for (int u = 0; u < QB; ++u) {
         const size_t po = (size_t)(p0 + u < fz.n_partials ? p0 + u : fz.n_partials - 1) * fz.partial_stride;
         nka[u] = ksrc[po + i]; nkb[u] = ksrc[po + i + HALF]; nvv[u] = vsrc[po + d];
       }
@@ -177,10 +178,10 @@ __global__ __launch_bounds__(64 * att_waves(DH, FUSED)) void attn_decode_kernel(
       f32x4 a[2] = {f32x4{}, f32x4{}}, b[2] = {f32x4{}, f32x4{}};
       // partials are added in the order p = 0, 1, ... (as rope_append_kernel does); four at a
       // time are requested together so that the additions do not serialise the loads
-      for (int p0 = 0; p0 < fz.n_partials; p0 += 4) {
+      for (int p0 = 0; p0 < fz.n_partials; p0 += QB) {
         if (!ALL || p0 > 0) request_q(c, sc, p0);
 #pragma unroll
-        for (int u = 0; u < 4; ++u)
+        for (int u = 0; u < QB; ++u)
           if (p0 + u < fz.n_partials) { a[0] += la[sc][u][0]; a[1] += la[sc][u][1]; b[0] += lb[sc][u][0]; b[1] += lb[sc][u][1]; }
       }
 #pragma unroll
@@ -196,10 +197,10 @@ __global__ __launch_bounds__(64 * att_waves(DH, FUSED)) void attn_decode_kernel(
       for (int d = lane; d < DH; d += 64) {
         const bool lo = d < HALF;
         float av = 0.f, bv = 0.f, vv = 0.f;
-        for (int p0 = 0; p0 < fz.n_partials; p0 += 4) {
+        for (int p0 = 0; p0 < fz.n_partials; p0 += QB) {
           if (!ALL || p0 > 0 || d >= 64) request_kv(d, p0);
 #pragma unroll
-          for (int u = 0; u < 4; ++u)
+          for (int u = 0; u < QB; ++u)
             if (p0 + u < fz.n_partials) { av += nka[u]; bv += nkb[u]; vv += nvv[u]; }
         }
         const float rot = lo ? rope_first(av, bv, ncs, nsn) : rope_second(av, bv, ncs, nsn);

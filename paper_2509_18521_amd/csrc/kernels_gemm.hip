@@ -144,7 +144,18 @@ __device__ inline void gemm_group(const bf16x8* __restrict__ w0, const bf16x8* _
       for (int u = 0; u < 8; ++u)
         if (wave + u * KW < nf.n_ssq) sacc += sq[j][u];
       const float* col = nf.ssq + (mt0 + j) * 32 + (lane & 31);
-      for (int t = wave + 8 * KW; t < nf.n_ssq; t += KW) sacc += col[(size_t)t * nf.ssq_stride];
+      // wide models have more than 8 slabs per wavefront: the rest in groups of 8 independent loads
+      for (int t0 = wave + 8 * KW; t0 < nf.n_ssq; t0 += 8 * KW) {
+        float more[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          const int t = t0 + u * KW;
+          more[u] = col[(size_t)(t < nf.n_ssq ? t : nf.n_ssq - 1) * nf.ssq_stride];
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+          if (t0 + u * KW < nf.n_ssq) sacc += more[u];
+      }
       if (lane < 32) ssp[(wave * MTC + j) * 32 + lane] = sacc;
     }
   }

@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(_PKG, "libapril.so")
 APRIL_OK, APRIL_EINVAL, APRIL_ENOMEM, APRIL_ESTARVED, APRIL_EHANDLE, APRIL_EDEVICE = 0, -1, -2, -3, -4, -5
 APRIL_DTYPE_FP32, APRIL_DTYPE_BF16 = 0, 1
 APRIL_SAMPLER_GREEDY, APRIL_SAMPLER_TOPK = 0, 1
-APRIL_KERNEL_CLASSES = 16
+APRIL_KERNEL_CLASSES = 24
 
 EXPORTS = [
     "april_init", "april_rollout_step", "april_resume", "april_buffer_size", "april_buffer_export",

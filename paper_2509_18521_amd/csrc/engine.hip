@@ -100,7 +100,7 @@ struct april_ctx {
   int *d_row_slot = nullptr, *d_row_pos = nullptr;
   std::vector<SlotH> slots;
   Watch dwatch{};
-  int watch_rows_cap = 0, watch_rows_used = 0, n_watch = 0, watch_cap = 64;
+  int watch_rows_cap = 0, watch_rows_used = 0, n_watch = 0, watch_cap = 512;
   std::map<std::pair<long long, int>, int> watch_row_of;
 
   // prefill staging (device) + pinned host staging
@@ -398,7 +398,11 @@ void forward(april_ctx* c, RowCtx rows, RowCtx srows, const int* gather, double 
   norm(srows, sd, c->final_norm, c->hf, gather, SB, true);
   {
     ProfScope p(c, KC_GEMM_LMHEAD, (double)V * d * e + SB * d * e, 2.0 * SB * V * d);
-    if (c->use_mfma && c->group_max) launch_gemm_mfma_logits(st, srows, (const bf16_t*)c->hf, c->lm_head_s, c->logits, c->group_max, V, d);
+    // more than 128 sampling rows: the tiled kernel reads the head once per 256 rows instead of
+    // once per 128 (same bits either way)
+    if (c->use_mfma && c->group_max && c->tile_gemm && srows.max_rows > 128 && d % 32 == 0)
+      launch_gemm_tile_logits(st, srows, (const bf16_t*)c->hf, c->lm_head_s, c->logits, c->group_max, V, d);
+    else if (c->use_mfma && c->group_max) launch_gemm_mfma_logits(st, srows, (const bf16_t*)c->hf, c->lm_head_s, c->logits, c->group_max, V, d);
     else if (c->use_mfma) launch_gemm_mfma(st, srows, (const bf16_t*)c->hf, c->lm_head_s, c->logits, V, d, 1, 0);
     else if (c->bf16) launch_gemm_ref<bf16_t, true>(st, srows, (const bf16_t*)c->hf, (const bf16_t*)c->lm_head, c->logits, V, d);
     else launch_gemm_ref<float, false>(st, srows, (const float*)c->hf, (const float*)c->lm_head, c->logits, V, d);

@@ -15,7 +15,7 @@
 
 namespace april {
 
-enum { TEPI_F32 = 0, TEPI_SWIGLU = 1 };
+enum { TEPI_F32 = 0, TEPI_SWIGLU = 1, TEPI_LOGITS = 2 };   // LOGITS: F32 + per-row maxima of 64-column groups
 
 // Epilogue of one wavefront: accumulator tile = out^T (lane l, register e:
 // n = 8*(e/4) + 4*(l/32) + e%4, m = l%32).  nt0: first weight tile (SwiGLU: first feature
@@ -24,7 +24,26 @@ template <int MTW, int NTW, int EPI>
 __device__ inline void tile_epilogue(f32x16 (&acc)[NTW][MTW], int nt0, int mt0, int rows, int n_tiles, int N, int lane,
                                      float* __restrict__ out, bf16_t* __restrict__ act) {
   const int mloc = lane & 31, nhalf = (lane >> 5) << 2;
-  if (EPI == TEPI_F32) {
+  if (EPI == TEPI_LOGITS) {
+    // act carries the group maxima (float [rows][N / 64]); a group is an aligned pair of weight
+    // tiles, which is what one wavefront holds (NTW == 2, nt0 even)
+    static_assert(EPI != TEPI_LOGITS || NTW == 2, "one 64-column group per wavefront");
+    float* gmax = reinterpret_cast<float*>(act);
+    if (nt0 < n_tiles) {
+#pragma unroll
+      for (int j = 0; j < MTW; ++j) {
+        float mxv = acc[0][j][0];
+#pragma unroll
+        for (int i = 0; i < NTW; ++i)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) mxv = fmaxf(mxv, acc[i][j][e]);
+        mxv = fmaxf(mxv, __shfl_xor(mxv, 32, 64));
+        const int m = (mt0 + j) * 32 + mloc;
+        if (m < rows && lane < 32) gmax[(size_t)m * (N >> 6) + (nt0 >> 1)] = mxv;
+      }
+    }
+  }
+  if (EPI == TEPI_F32 || EPI == TEPI_LOGITS) {
 #pragma unroll
     for (int i = 0; i < NTW; ++i) {
       const int nt = nt0 + i;
@@ -350,6 +369,17 @@ void launch_gemm_tile_swiglu(hipStream_t st, RowCtx rc, const bf16_t* x, const b
     dim3 grid(ceil_div(f_tiles, 2), ceil_div(m_tiles, 8));
     hipLaunchKernelGGL((TILE_NARROW(TEPI_SWIGLU)), grid, dim3(256), 0, st, rc, xv, gv, uv, nullptr, act, F, K);
   }
+}
+
+// LM head for many rows: logits plus the maxima of every 64 columns.  Same accumulation chain
+// per element as the skinny LM-head kernel (k-tiles in order, one accumulator), so the choice
+// between the two changes no bit.  Needs V % 64 == 0 and K % 32 == 0.
+void launch_gemm_tile_logits(hipStream_t st, RowCtx rc, const bf16_t* x, const bf16_t* Wp, float* logits,
+                             float* group_max, int V, int K) {
+  const int n_tiles = V >> 5, m_tiles = ceil_div(rc.max_rows, 32);
+  dim3 grid(ceil_div(n_tiles, 8), ceil_div(m_tiles, 8));
+  hipLaunchKernelGGL((TILE_WIDE(TEPI_LOGITS)), grid, dim3(512), 0, st, rc, reinterpret_cast<const bf16x8*>(x),
+                     reinterpret_cast<const bf16x8*>(Wp), nullptr, logits, reinterpret_cast<bf16_t*>(group_max), V, K);
 }
 
 }  // namespace april

@@ -99,6 +99,14 @@ def test_long_context_spans_several_kv_splits(head_dim):
     teacher_forced_parity(w, 2, 5, min_rows=12)
 
 
+def test_more_than_128_rows_in_flight():
+    """160 rollouts in flight: several m-groups in every decode GEMM, and the LM head goes through
+    the tall-batch kernel (its sampling rows exceed 128) in prefill and in decode."""
+    shape = ai.ModelShape(2, 128, 4, 2, 32, 256, 512)
+    w = ai.Workload("many_rows", shape, 40, 6, 100, 160, 5, 1.2, 0.4, 2, 5, ai.SAMPLER_GREEDY, 0, 1, 5)
+    teacher_forced_parity(w, 1, 160, min_rows=300)
+
+
 def test_bf16_scheduling_invariance():
     """On the bf16 path a rollout's tokens do not depend on how it was scheduled: carried over
     with resident KV or run with N' = N, token for token.  A rollout whose KV was dropped is

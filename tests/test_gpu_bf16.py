@@ -72,6 +72,16 @@ def test_cfg2_shape_two_layers_topk_teacher_forced():
     teacher_forced_parity(w, 2, 12)
 
 
+def test_down_projection_folding_the_next_norm(monkeypatch):
+    """The optional folding of a layer's first RMSNorm into the previous down projection
+    (off by default, APRIL_FUSE_DOWN=1) computes the same thing."""
+    monkeypatch.setenv("APRIL_FUSE_DOWN", "1")
+    base = ai.WORKLOADS["cfg2_small_bf16"]
+    w = ai.Workload("cfg2_L3", ai.reduced(base, n_layers=3, vocab=4096).shape, 6, 64, 3, 5, 8, 1.8, 0.4, 3, 8,
+                    ai.SAMPLER_GREEDY, 0, 2, base.seed)
+    teacher_forced_parity(w, 2, 10)
+
+
 def test_cfg2_full_depth_sampled_positions():
     """All 24 layers of configuration 2 on a few rollouts and positions."""
     base = ai.WORKLOADS["cfg2_small_bf16"]

@@ -107,7 +107,8 @@ def main():
     p.add_argument("--max-new", type=int, default=0, help="cap the generated length (debug only; invalidates the number)")
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--no-wait-all", action="store_true")
-    p.add_argument("--profile-every", type=int, default=16)
+    p.add_argument("--profile-every", type=int, default=64,
+                   help="every n-th decode iteration runs eagerly with an event pair around each launch (0 = never)")
     p.add_argument("--copy-calibration", action="store_true",
                    help="also run three 1 GiB device copies first (reference dispatches for --pmc counter runs)")
     args = p.parse_args()

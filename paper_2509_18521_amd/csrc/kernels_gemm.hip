@@ -59,7 +59,7 @@ __device__ inline void gemm_group(const bf16x8* __restrict__ w0, const bf16x8* _
   // next group is requested before the MFMAs of the current one, so a wavefront whose k range
   // fits in two groups has all of it in flight at once, and a longer range streams with one
   // group always in flight behind the arithmetic.
-  constexpr int KH = (NT + MTC) <= 4 ? 8 : ((NT + MTC) == 5 ? 7 : 5);
+  constexpr int KH = (NT + MTC) <= 4 ? 8 : ((NT + MTC) == 5 ? 7 : ((NT + MTC) == 6 ? 5 : 3));
   // the wavefront index is uniform: keep it (and the k range derived from it) in scalar registers
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   f32x16 acc[NT][MTC];
@@ -356,6 +356,13 @@ void launch_gemm_mfma(hipStream_t st, RowCtx rc, const bf16_t* x, const bf16_t* 
     // plenty of n-tiles (LM head): one wavefront per pair of tiles, whole k range
     dim3 grid(ceil_div(n_tiles / 2, KW4), ksplit, m_groups);
     hipLaunchKernelGGL((gemm_mfma_kernel<2, MT, EPI_F32, false>), grid, dim3(64 * KW4), 0, st, rc, xv, wv, nullptr,
+                       out, nullptr, N, K, ksplit, partial_stride, nf);
+  } else if (n_tiles % 2 == 0 && (n_tiles / 2) * ksplit >= 128) {
+    // wide matrices: two n-tiles per workgroup, so every activation fragment feeds two MFMAs
+    // (the activation re-reads from L2 bound these shapes: 1.3-1.4x faster at 64-384 rows of
+    // a 2560- or 4096-wide model).  Every output element keeps its summation chain.
+    dim3 grid(ksplit, n_tiles / 2, m_groups);
+    hipLaunchKernelGGL((gemm_mfma_kernel<2, MT, EPI_F32, true>), grid, dim3(64 * KW4), 0, st, rc, xv, wv, nullptr,
                        out, nullptr, N, K, ksplit, partial_stride, nf);
   } else {
     dim3 grid(ksplit, n_tiles, m_groups);

@@ -58,7 +58,12 @@ __global__ __launch_bounds__(64 * att_waves(DH, FUSED)) void attn_decode_kernel(
   constexpr int ATT_WAVES = att_waves(DH, FUSED);
   __shared__ float lds[ATT_WAVES * REC];
   __shared__ bf16_t s_knew[DH], s_vnew[DH];
-  const int wr = blockIdx.x, r = row_base + wr, kvh = blockIdx.y, split = blockIdx.z;   // wr: workspace row
+  // Workgroup ids are dealt to the 8 XCDs in turn, so with a row count that is a multiple of 8 the
+  // plain mapping would put every (KV head, split) of a row on one XCD and a long row would
+  // overload it.  Rotating the row index by the other two coordinates spreads a row's
+  // workgroups over the XCDs (a bijection of blockIdx.x for fixed y and z).
+  const int kvh = blockIdx.y, split = blockIdx.z;
+  const int wr = (int)((blockIdx.x + blockIdx.y + 3u * blockIdx.z) % gridDim.x), r = row_base + wr;   // wr: workspace row
   // the row arrays hold max_rows entries: fetch them together with the control word
   const int slot_raw = rc.row_slot[r], pos = rc.row_pos[r];
   ROW_GUARD(rc, r);

@@ -24,6 +24,15 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 BF16_PEAK_TFLOPS = 2500.0      # dense bf16 MFMA, published
 
 
+VERBOSE = False
+
+
+def note(msg):
+    """Progress line on stderr (--verbose): long configurations would otherwise be silent for minutes."""
+    if VERBOSE:
+        print(f"[bench {time.strftime('%H:%M:%S')}] {msg}", file=sys.stderr, flush=True)
+
+
 def run_arm(ap, ctx, reqs, n_target, n_over, max_new, steps, profile_every=0):
     """Run `steps` rollout steps from a clean context state; returns per-step results."""
     ap.april_profile_enable(ctx, profile_every)
@@ -34,6 +43,7 @@ def run_arm(ap, ctx, reqs, n_target, n_over, max_new, steps, profile_every=0):
         res = ap.april_rollout_step(ctx, new, n_target, n_over, max_new)
         nxt += res.n_new_consumed
         results.append(res)
+        note(f"step {len(results)}/{steps}: {res.tokens_generated} tokens in {res.t_total_s:.2f} s, {res.decode_iters} iterations")
         ap.april_resume(ctx, res.buffer)
     import torch
     torch.cuda.synchronize()
@@ -109,9 +119,13 @@ def main():
     p.add_argument("--no-wait-all", action="store_true")
     p.add_argument("--profile-every", type=int, default=64,
                    help="every n-th decode iteration runs eagerly with an event pair around each launch (0 = never)")
+    p.add_argument("--verbose", action="store_true", help="progress lines on stderr")
+    p.add_argument("--kv-pool-gib", type=float, default=0.0, help="KV pool size (0 = the library's default)")
     p.add_argument("--copy-calibration", action="store_true",
                    help="also run three 1 GiB device copies first (reference dispatches for --pmc counter runs)")
     args = p.parse_args()
+    global VERBOSE
+    VERBOSE = args.verbose
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no sharding, no collectives); --gpus must be 1", file=sys.stderr)
         sys.exit(2)
@@ -135,14 +149,17 @@ def main():
     s = w.shape
     t_setup = time.perf_counter()
     weights = ai.make_weights(s, w.seed)
+    note(f"weights generated ({ai.n_params(s) / 1e9:.2f} B parameters)")
     total_steps = args.steps
     reqs = ai.make_requests(w, ai.requests_needed(w, max(total_steps, args.warmup)))
     cfg = ap.make_cfg(s, max_inflight=w.n_overprovision + 32, max_ctx=w.prompt_len + w.max_new + 16,
                       sampler=w.sampler, top_k=max(w.top_k, 1), temperature=1.0, seed=w.seed,
+                      kv_pool_bytes=int(args.kv_pool_gib * (1 << 30)),
                       stream=torch.cuda.current_stream().cuda_stream or None)
     ctx = ap.april_init(cfg, ap.pack_weights(s, weights))
     info = ap.april_get_info(ctx)
     setup_s = time.perf_counter() - t_setup
+    note(f"engine ready: KV pool {info['kv_pool_bytes'] / 2**30:.1f} GiB, weights {info['weight_bytes'] / 2**30:.1f} GiB")
 
     def fresh_arm(n_over, steps, profile_every):
         """Run an arm on the current engine (created fresh for each arm by reset_engine)."""

@@ -60,7 +60,9 @@ typedef struct {
   int32_t dtype;             /* APRIL_DTYPE_*: type of weights, KV cache, GEMM operands   */
   float   rope_theta, rms_eps;
   int32_t kv_block_tokens;   /* tokens per KV page; must be 16                            */
-  int64_t kv_pool_bytes;     /* 0 => sized for max_inflight sequences of max_ctx tokens   */
+  int64_t kv_pool_bytes;     /* 0 => sized for max_inflight sequences of max_ctx tokens,
+                                but at most the free device memory less a reserve for the
+                                workspaces (max(12 GiB, 1/16 of the device))              */
   int32_t max_inflight;      /* sequence slots (in flight + parked + surplus-complete)    */
   int32_t max_ctx;           /* max prompt + generated tokens of one sequence             */
   int32_t sampler;           /* APRIL_SAMPLER_*                                           */

@@ -623,7 +623,17 @@ int april_init(const april_model_cfg* cfg, const april_tensor* weights, int32_t 
   c->kv_bytes_per_token = (int64_t)2 * g.n_layers * nkv * e;
   const int64_t page_bytes = c->kv_bytes_per_token * 16;
   int64_t pool = g.kv_pool_bytes;
-  if (pool <= 0) pool = (int64_t)S * c->max_blocks * page_bytes;
+  if (pool <= 0) {
+    // every slot at max_ctx, but no more than the device has free after a reserve for the
+    // workspaces allocated below (a smaller pool is legal: rollouts are then preempted and
+    // re-prefilled when pages run out)
+    pool = (int64_t)S * c->max_blocks * page_bytes;
+    size_t free_b = 0, total_b = 0;
+    HIPTRY(hipMemGetInfo(&free_b, &total_b));
+    const int64_t reserve = std::max<int64_t>((int64_t)12 << 30, (int64_t)(total_b / 16));
+    const int64_t cap = (int64_t)free_b - reserve;
+    if (pool > cap && cap >= page_bytes) pool = cap;
+  }
   c->n_pages = (int)std::min<int64_t>(pool / page_bytes, (int64_t)1 << 30);
   if (c->n_pages < 1) { fail(c, APRIL_ENOMEM, "KV pool smaller than one page"); return bail(APRIL_ENOMEM); }
   c->kv_pool_bytes = (int64_t)c->n_pages * page_bytes;

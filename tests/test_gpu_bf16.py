@@ -157,3 +157,50 @@ def test_bf16_scheduling_invariance():
     finally:
         for x in ctxs:
             ap().april_destroy(x)
+
+
+def test_cfg2_bench_launch_configuration_sampled_outputs():
+    """Configuration 2 at full size, launched as the benchmark launches it (24 layers, N = 64,
+    N' = 96, max_new = 2048, top-k sampling, graph replay, the GPU's own sampled tokens): the
+    step's invariants, and for two rollouts the logits at sampled positions against the oracle
+    fed with the same prefix (one full recompute per rollout gives every position's logits)."""
+    from oracle.model import Decoder
+    w = ai.WORKLOADS["cfg2_small_bf16"]
+    weights = ai.make_weights(w.shape, w.seed)
+    reqs = ai.make_requests(w, w.n_overprovision)
+    lens = {r.request_id: r.forced_len for r in reqs}
+    short = next(r for r in reqs if 40 <= r.forced_len <= 150)        # completes in the first step
+    long_ = next(r for r in reqs if r.forced_len >= 1200)             # still running when it ends
+    n_watch = 260
+    ctx = make_engine(w, weights, debug=True)
+    try:
+        ap().april_debug_watch(ctx, short.request_id, 0, short.forced_len)
+        ap().april_debug_watch(ctx, long_.request_id, 0, n_watch)
+        got = run_gpu(ctx, reqs, w.n_target, w.n_overprovision, w.max_new, 1)[0]
+        # APRIL's invariants at the real sizes
+        assert len(got["ids"]) == w.n_target and len(set(got["ids"])) == w.n_target
+        assert all(len(t) == lens[rid] for rid, t in zip(got["ids"], got["tokens"]))
+        assert len(got["buffer"]) == w.n_overprovision - w.n_target
+        assert set(got["ids"]) | {b[0] for b in got["buffer"]} == set(lens)          # nobody lost
+        assert got["generated"] == sum(len(t) for t in got["tokens"]) + sum(b[1] for b in got["buffer"])
+        assert short.request_id in got["ids"] and long_.request_id in got["buffer_tokens"]
+        dec = Decoder(w.shape, weights)
+        worst = 0.0
+        for r, toks in ((short, got["tokens"][got["ids"].index(short.request_id)]),
+                        (long_, got["buffer_tokens"][long_.request_id][:n_watch])):
+            n = len(toks)
+            positions = sorted({0, 1, n // 3, n // 2, n - 2, n - 1})
+            feed = np.concatenate([r.tokens, np.asarray(toks[:n - 1], dtype=np.int32)])
+            ref_all = dec.forward_block(feed, dec.new_cache())          # row P-1+i predicts generated token i
+            for i in positions:
+                lg, sampled = ap().april_debug_logits(ctx, r.request_id, i, w.shape.vocab)
+                ref = ref_all[w.prompt_len - 1 + i]
+                worst = max(worst, float(np.max(np.abs(lg - ref))) / max(1.0, float(np.max(np.abs(ref)))))
+                assert sampled == toks[i]
+                u = uniform_for(w.seed, r.request_id, i)
+                idx, p = osampler.top_k_probs(lg, w.top_k, 1.0)
+                if np.min(np.abs(np.cumsum(p) - u)) > 1e-9:
+                    assert sampled == osampler.top_k_sample(lg, w.top_k, 1.0, u)
+        assert worst <= BF16_LOGIT_TOL, worst
+    finally:
+        ap().april_destroy(ctx)

@@ -123,6 +123,7 @@ struct april_ctx {
   size_t qkv_stride = 0, proj_stride = 0;
   // bf16 MFMA attention: split-KV workspace
   bool attn_mfma = false, fuse_rope = true, tile_gemm = true, fuse_norm = true, fuse_down = false;
+  int tile_decode_rows = 160;   // decode gate/up goes through the LDS-tiled kernel from this many rows in flight (0 = never)
   float* ssq = nullptr;         // [d_model / 32][m_cap] per-row partial sums of squares (fused norm)
   int attn_chunk = 256, attn_max_splits = 1, attn_ws_rows = 0;
   float* attn_ws = nullptr;
@@ -375,7 +376,11 @@ void forward(april_ctx* c, RowCtx rows, RowCtx srows, const int* gather, double 
     if (c->use_mfma) {
       ProfScope p(c, KC_GEMM_GATEUP, 2.0 * F * d * e + B * d * e + B * F * e, 4.0 * B * F * d);
       if (tile) launch_gemm_tile_swiglu(st, rows, (const bf16_t*)c->h_act, L.wg_s, L.wu_s, (bf16_t*)c->act, F, d);
-      else launch_gemm_mfma_swiglu(st, rows, (const bf16_t*)c->h_act, L.wg_s, L.wu_s, (bf16_t*)c->act, F, d,
+      else if (c->tile_decode_rows > 0 && rows.max_rows >= c->tile_decode_rows &&
+               launch_gemm_tile_swiglu_chain(st, rows, (const bf16_t*)c->h_act, L.wg_s, L.wu_s, (bf16_t*)c->act, F, d,
+                                             fuse_norm2 ? c->ssq : nullptr, c->m_cap, m.rms_eps)) {
+        // many rows in flight: LDS-tiled kernel, same summation chains as the skinny one
+      } else launch_gemm_mfma_swiglu(st, rows, (const bf16_t*)c->h_act, L.wg_s, L.wu_s, (bf16_t*)c->act, F, d,
                                    fuse_norm2 ? c->ssq : nullptr, c->m_cap, m.rms_eps);
     } else {
       gemm(KC_GEMM_GATEUP, rows, c->h_act, L.wgu, nullptr, c->gu, 2 * F, d, 1, 0, B);
@@ -495,6 +500,7 @@ int april_init(const april_model_cfg* cfg, const april_tensor* weights, int32_t 
   c->fuse_norm = !(fn && !strcmp(fn, "0"));
   const char* fd = getenv("APRIL_FUSE_DOWN");    // off by default: measured 5 % slower end to end on configuration 2
   c->fuse_down = fd && !strcmp(fd, "1");
+  if (const char* td = getenv("APRIL_TILE_DECODE_ROWS")) c->tile_decode_rows = atoi(td);   // debug switch
   const char* tg = getenv("APRIL_TILE_GEMM");
   c->tile_gemm = !(tg && !strcmp(tg, "0"));
   const char* gr = getenv("APRIL_GRAPH");

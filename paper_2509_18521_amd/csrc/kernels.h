@@ -126,6 +126,8 @@ void launch_gemm_mfma_resid(hipStream_t st, RowCtx rc, const bf16_t* x, const bf
 void launch_gemm_tile(hipStream_t st, RowCtx rc, const bf16_t* x, const bf16_t* Wp, float* out, int N, int K);
 void launch_gemm_tile_swiglu(hipStream_t st, RowCtx rc, const bf16_t* x, const bf16_t* Wg, const bf16_t* Wu,
                              bf16_t* act, int F, int K);
+bool launch_gemm_tile_swiglu_chain(hipStream_t st, RowCtx rc, const bf16_t* x, const bf16_t* Wg, const bf16_t* Wu,
+                                   bf16_t* act, int F, int K, const float* ssq, int ssq_stride, float eps);
 void launch_gemm_tile_logits(hipStream_t st, RowCtx rc, const bf16_t* x, const bf16_t* Wp, float* logits,
                              float* group_max, int V, int K);
 // LM head: logits fp32 [rows][V] plus, per row, the maximum of every group of

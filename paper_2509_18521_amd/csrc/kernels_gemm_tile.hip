@@ -22,7 +22,8 @@ enum { TEPI_F32 = 0, TEPI_SWIGLU = 1, TEPI_LOGITS = 2 };   // LOGITS: F32 + per-
 // tile; acc[i] = gate, acc[i + NTW/2] = up), mt0: first activation tile.
 template <int MTW, int NTW, int EPI>
 __device__ inline void tile_epilogue(f32x16 (&acc)[NTW][MTW], int nt0, int mt0, int rows, int n_tiles, int N, int lane,
-                                     float* __restrict__ out, bf16_t* __restrict__ act) {
+                                     float* __restrict__ out, bf16_t* __restrict__ act,
+                                     const float* row_scale = nullptr, int scale_m0 = 0) {
   const int mloc = lane & 31, nhalf = (lane >> 5) << 2;
   if (EPI == TEPI_LOGITS) {
     // act carries the group maxima (float [rows][N / 64]); a group is an aligned pair of weight
@@ -70,6 +71,8 @@ __device__ inline void tile_epilogue(f32x16 (&acc)[NTW][MTW], int nt0, int mt0, 
 #pragma unroll
       for (int j = 0; j < MTW; ++j) {
         const int m = (mt0 + j) * 32 + mloc;
+        // folded RMSNorm (decode): the accumulators are scaled by the row's 1/rms first
+        const float inv = row_scale ? row_scale[m - scale_m0] : 1.0f;
         if (m < rows) {
 #pragma unroll
           for (int q = 0; q < 4; ++q) {
@@ -77,7 +80,7 @@ __device__ inline void tile_epilogue(f32x16 (&acc)[NTW][MTW], int nt0, int mt0, 
             bf16x4 v;
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-              const float g = acc[i][j][4 * q + e], u = acc[i + H][j][4 * q + e];
+              const float g = acc[i][j][4 * q + e] * inv, u = acc[i + H][j][4 * q + e] * inv;
               v[e] = (bf16_t)silu_mul(g, u);
             }
             *reinterpret_cast<bf16x4*>(act + act_index<true>(m, f, N)) = v;
@@ -222,11 +225,24 @@ __device__ inline void wait_vector_memory() {   // until at most LEFT vector-mem
 // "at most (R - 2) stages still outstanding" means stage s has landed; the barrier that
 // follows makes that true for every wavefront's share and also says everyone has finished
 // reading the buffer that the next copies overwrite.  Requires K % (16 * BK) == 0.
-template <int WGM, int WGN, int MTW, int NTW, int BK, int R, int EPI>
-__global__ __launch_bounds__(64 * WGM * WGN) __attribute__((amdgpu_waves_per_eu(2)))
-void gemm_tile_dma_kernel(RowCtx rc, const bf16x8* __restrict__ x, const bf16x8* __restrict__ w0,
-                          const bf16x8* __restrict__ w1, float* __restrict__ out, bf16_t* __restrict__ act, int N,
-                          int K) {
+//
+// CHAIN (decode with many rows): the skinny decode kernel sums k in four quarters (its four
+// wavefronts), each quarter its own accumulator chain, and adds them as ((q0 + q1) + q2) + q3.
+// Here one wavefront walks all of k, so it closes a chain at every quarter boundary and adds
+// it to a second accumulator set in that order: every output element gets the same bits from
+// either kernel, and the choice between them can follow the row count.  The quarter
+// boundaries must fall on stage boundaries (K % (64 * BK) == 0).  The second accumulator set
+// needs the whole register file of a SIMD, hence the separate entry without the two-waves hint.
+struct TileNorm {              // RMSNorm folded into the SwiGLU epilogue (CHAIN only)
+  const float* ssq;            // [n_ssq][ssq_stride] per-row sums of squares of 32-column slabs; nullptr = none
+  int ssq_stride, n_ssq;
+  float inv_d, eps;
+};
+
+template <int WGM, int WGN, int MTW, int NTW, int BK, int R, int EPI, bool CHAIN>
+__device__ __forceinline__ void tile_dma_body(RowCtx rc, const bf16x8* __restrict__ x, const bf16x8* __restrict__ w0,
+                                              const bf16x8* __restrict__ w1, float* __restrict__ out,
+                                              bf16_t* __restrict__ act, int N, int K, const TileNorm& tn) {
   constexpr int NW = WGM * WGN, MT = WGM * MTW, NT = WGN * NTW, FR = MT + NT;
   constexpr int PER = FR * BK / NW;
   static_assert(FR * BK % NW == 0 && NW % BK == 0, "staging split");
@@ -278,11 +294,57 @@ void gemm_tile_dma_kernel(RowCtx rc, const bf16x8* __restrict__ x, const bf16x8*
   for (int i = 0; i < NTW; ++i)
 #pragma unroll
     for (int j = 0; j < MTW; ++j) acc[i][j] = f32x16{};
+  f32x16 tot[CHAIN ? NTW : 1][CHAIN ? MTW : 1];
+  int quarter = 1, next_close = CHAIN ? (KT / 4) / BK : -1;       // stage at which the next chain closes
 
 #pragma unroll
   for (int r = 0; r < R - 1; ++r)
     if (r < n_stages) issue(r);
+
+  // folded norm: 1/rms of this workgroup's rows, summed in the skinny kernel's order (wavefront w
+  // of that kernel adds the slabs w, w + 4, ...; then ((s0 + s1) + s2) + s3)
+  __shared__ float row_scale[CHAIN ? MT * 32 : 1];
+  const bool scaled = CHAIN && EPI == TEPI_SWIGLU && tn.ssq != nullptr;
+  if (scaled) {
+    for (int rl = threadIdx.x; rl < MT * 32; rl += 64 * NW) {
+      int m = m0 * 32 + rl;
+      if (m > rows - 1) m = rows - 1;
+      const float* col = tn.ssq + m;
+      float sw[4] = {0.f, 0.f, 0.f, 0.f};
+      // 32 slabs requested together (independent loads), then added in slab order: chain w sees
+      // the slabs w, w + 4, ... in increasing order
+      for (int t0 = 0; t0 < tn.n_ssq; t0 += 32) {
+        float sl[32];
+#pragma unroll
+        for (int u = 0; u < 32; ++u) {
+          const int t = t0 + u < tn.n_ssq ? t0 + u : tn.n_ssq - 1;
+          sl[u] = col[(size_t)t * tn.ssq_stride];
+        }
+#pragma unroll
+        for (int u = 0; u < 32; ++u)
+          if (t0 + u < tn.n_ssq) sw[u & 3] += sl[u];
+      }
+      float ssum = sw[0];
+#pragma unroll
+      for (int w = 1; w < 4; ++w) ssum += sw[w];
+      row_scale[rl] = 1.0f / sqrtf(ssum * tn.inv_d + tn.eps);
+    }
+    __syncthreads();
+  }
+
   for (int s = 0; s < n_stages; ++s) {
+    if (CHAIN && s == next_close) {
+#pragma unroll
+      for (int i = 0; i < NTW; ++i)
+#pragma unroll
+        for (int j = 0; j < MTW; ++j) {
+          if (quarter == 1) tot[CHAIN ? i : 0][CHAIN ? j : 0] = acc[i][j];
+          else tot[CHAIN ? i : 0][CHAIN ? j : 0] += acc[i][j];
+          acc[i][j] = f32x16{};
+        }
+      ++quarter;
+      next_close = quarter < 4 ? (int)(((long long)KT * quarter / 4) / BK) : -1;
+    }
     // wait for this wavefront's copies of stage s (s_waitcnt vmcnt only: expcnt/lgkmcnt fields all-ones)
     constexpr int LEFT = (R - 2) * PER;
     if (s + R - 2 < n_stages) wait_vector_memory<LEFT>();
@@ -317,8 +379,30 @@ void gemm_tile_dma_kernel(RowCtx rc, const bf16x8* __restrict__ x, const bf16x8*
     }
     asm volatile("" ::: "memory");
   }
+  if (CHAIN) {
+#pragma unroll
+    for (int i = 0; i < NTW; ++i)
+#pragma unroll
+      for (int j = 0; j < MTW; ++j) acc[i][j] = tot[CHAIN ? i : 0][CHAIN ? j : 0] + acc[i][j];
+  }
   tile_epilogue<MTW, NTW, EPI>(acc, bx * (EPI == TEPI_SWIGLU ? NT / 2 : NT) + wn * (EPI == TEPI_SWIGLU ? NTW / 2 : NTW),
-                               m0 + wm * MTW, rows, n_tiles, N, lane, out, act);
+                               m0 + wm * MTW, rows, n_tiles, N, lane, out, act, scaled ? row_scale : nullptr, m0 * 32);
+}
+
+template <int WGM, int WGN, int MTW, int NTW, int BK, int R, int EPI>
+__global__ __launch_bounds__(64 * WGM * WGN) __attribute__((amdgpu_waves_per_eu(2)))
+void gemm_tile_dma_kernel(RowCtx rc, const bf16x8* __restrict__ x, const bf16x8* __restrict__ w0,
+                          const bf16x8* __restrict__ w1, float* __restrict__ out, bf16_t* __restrict__ act, int N,
+                          int K) {
+  tile_dma_body<WGM, WGN, MTW, NTW, BK, R, EPI, false>(rc, x, w0, w1, out, act, N, K, TileNorm{});
+}
+
+template <int WGM, int WGN, int MTW, int NTW, int BK, int R, int EPI>
+__global__ __launch_bounds__(64 * WGM * WGN)
+void gemm_tile_chain_kernel(RowCtx rc, const bf16x8* __restrict__ x, const bf16x8* __restrict__ w0,
+                            const bf16x8* __restrict__ w1, float* __restrict__ out, bf16_t* __restrict__ act, int N,
+                            int K, TileNorm tn) {
+  tile_dma_body<WGM, WGN, MTW, NTW, BK, R, EPI, true>(rc, x, w0, w1, out, act, N, K, tn);
 }
 
 // Tile shapes.  WIDE: 256 x 256 outputs on 8 wavefronts (2 per SIMD, each 128 x 64), ring of
@@ -369,6 +453,26 @@ void launch_gemm_tile_swiglu(hipStream_t st, RowCtx rc, const bf16_t* x, const b
     dim3 grid(ceil_div(f_tiles, 2), ceil_div(m_tiles, 8));
     hipLaunchKernelGGL((TILE_NARROW(TEPI_SWIGLU)), grid, dim3(256), 0, st, rc, xv, gv, uv, nullptr, act, F, K);
   }
+}
+
+// Decode with many rows in flight: fused gate/up + SiLU*mul with the skinny kernel's summation
+// chains (see CHAIN above) and, when ssq is set, the folded RMSNorm of that kernel.  Returns
+// false (nothing launched) when the shape does not allow it.
+// Measured on MI355X, 256 rows, fused gate/up of a 4096 x 14336 (2560 x 9728) MLP: 78 (49) us
+// against 128 (62) us for the skinny kernel; per 256 rows the time is flat, so it wins from about
+// 160 rows, and beyond 256 rows (two row groups) only where the weight tiles alone fill the chip.
+// A ring deeper than 3 stages made this variant 1.8x slower (the plain kernel does not care).
+bool launch_gemm_tile_swiglu_chain(hipStream_t st, RowCtx rc, const bf16_t* x, const bf16_t* Wg, const bf16_t* Wu,
+                                   bf16_t* act, int F, int K, const float* ssq, int ssq_stride, float eps) {
+  if (K % 128 != 0 || F % 32 != 0) return false;     // quarter boundaries on stage boundaries (BK = 2)
+  if (rc.max_rows > 256 && F < 12288) return false;
+  const int f_tiles = F >> 5, m_tiles = ceil_div(rc.max_rows, 32);
+  const TileNorm tn{ssq, ssq_stride, K >> 5, 1.0f / (float)K, eps};
+  dim3 grid(ceil_div(f_tiles, 2), ceil_div(m_tiles, 8));
+  hipLaunchKernelGGL((gemm_tile_chain_kernel<2, 2, 4, 2, 2, 3, TEPI_SWIGLU>), grid, dim3(256), 0, st, rc,
+                     reinterpret_cast<const bf16x8*>(x), reinterpret_cast<const bf16x8*>(Wg),
+                     reinterpret_cast<const bf16x8*>(Wu), nullptr, act, F, K, tn);
+  return true;
 }
 
 // LM head for many rows: logits plus the maxima of every 64 columns.  Same accumulation chain

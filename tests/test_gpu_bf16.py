@@ -204,3 +204,34 @@ def test_cfg2_bench_launch_configuration_sampled_outputs():
         assert worst <= BF16_LOGIT_TOL, worst
     finally:
         ap().april_destroy(ctx)
+
+
+def test_tiled_decode_gate_up_gives_the_skinny_kernels_bits(monkeypatch):
+    """With many rows in flight the decode gate/up GEMM runs in the LDS-tiled kernel, which
+    closes its accumulator chain at the skinny kernel's quarter boundaries and folds the same
+    RMSNorm: forcing either kernel for every iteration must change no bit of any logit."""
+    shape = ai.ModelShape(2, 256, 4, 2, 64, 512, 1024)
+    w = ai.Workload("tile_decode", shape, 8, 21, 30, 40, 9, 1.7, 0.4, 3, 9, ai.SAMPLER_GREEDY, 0, 2, 11)
+    weights = ai.make_weights(shape, w.seed)
+    reqs = ai.make_requests(w, ai.requests_needed(w))
+    runs = []
+    for threshold in ("0", "1"):                 # never / always the tiled kernel
+        monkeypatch.setenv("APRIL_TILE_DECODE_ROWS", threshold)
+        ctx = make_engine(w, weights, debug=True)
+        try:
+            for r in reqs:
+                ap().april_debug_watch(ctx, r.request_id, 0, w.max_new)
+            got = run_gpu(ctx, reqs, w.n_target, w.n_overprovision, w.max_new, w.steps)
+            logits = {}
+            for g in got:
+                for rid, toks in list(zip(g["ids"], g["tokens"])) + list(g["buffer_tokens"].items()):
+                    for i in range(len(toks)):
+                        logits[(rid, i)] = ap().april_debug_logits(ctx, rid, i, shape.vocab)[0]
+            runs.append((got, logits))
+        finally:
+            ap().april_destroy(ctx)
+    (a, la), (b, lb) = runs
+    assert_schedule_equal(b, a)
+    assert [g["tokens"] for g in a] == [g["tokens"] for g in b]
+    assert la.keys() == lb.keys() and len(la) > 200
+    assert all(np.array_equal(la[k], lb[k]) for k in la)

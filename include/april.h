@@ -196,9 +196,11 @@ int april_sample_rows(april_ctx* ctx, const float* logits, int32_t n_rows,
                       const int64_t* request_ids, const int32_t* gen_index, int32_t* out_tokens);
 
 /* Per-kernel-class timing, measured with HIP events on the context's stream around
- * sampled launches of the real decode loop (every `every`-th iteration; 0 = off).  One extra
- * class, "event_pair_empty_kernel", holds what the same event pair reads around a kernel that
- * does nothing (dispatch and completion latency, not execution). */
+ * sampled launches of the real decode loop (every `every`-th iteration; 0 = off).  Two extra
+ * classes calibrate the method: "event_pair_no_kernel" is what a pair of event records reads
+ * with nothing between them (the cost of the pair itself; subtract it from a class's average to
+ * get the launch's own time), "event_pair_empty_kernel" the same around a kernel that does
+ * nothing (the floor of any single launch). */
 #define APRIL_KERNEL_CLASSES 24
 typedef struct {
   const char* name;

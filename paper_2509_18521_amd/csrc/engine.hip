@@ -27,12 +27,12 @@ double now_s() {
 
 enum KernelClass {
   KC_SCHED = 0, KC_EMBED, KC_NORM, KC_GEMM_QKV, KC_ROPE, KC_ATTN, KC_GEMM_O, KC_GEMM_GATEUP, KC_SILU,
-  KC_GEMM_DOWN, KC_GEMM_LMHEAD, KC_SAMPLE, KC_MOE_ROUTE, KC_MOE_GATEUP, KC_MOE_DOWN, KC_ATTN_MERGE, KC_EVENT_EMPTY, KC_COUNT
+  KC_GEMM_DOWN, KC_GEMM_LMHEAD, KC_SAMPLE, KC_MOE_ROUTE, KC_MOE_GATEUP, KC_MOE_DOWN, KC_ATTN_MERGE, KC_EVENT_EMPTY, KC_EVENT_NONE, KC_COUNT
 };
 static_assert(KC_COUNT <= APRIL_KERNEL_CLASSES, "april_profile_get callers size their arrays with APRIL_KERNEL_CLASSES");
 const char* kKernelNames[KC_COUNT] = {"sched", "embed", "add_rmsnorm", "gemm_qkv", "rope_append", "attn_decode",
                                       "gemm_o", "gemm_gateup", "silu_mul", "gemm_down", "gemm_lmhead", "sample",
-                                      "moe_route", "moe_gateup", "moe_down", "attn_merge", "event_pair_empty_kernel"};
+                                      "moe_route", "moe_gateup", "moe_down", "attn_merge", "event_pair_empty_kernel", "event_pair_no_kernel"};
 
 struct LayerW {
   float *attn_norm = nullptr, *mlp_norm = nullptr;
@@ -969,6 +969,8 @@ static int measure_event_overhead(april_ctx* c) {
     ProfScope p(c, KC_EVENT_EMPTY, 0, 0);
     launch_fill_i32(c->stream, c->d_dummy, 0, 1);
   }
+  // and with nothing between the two records: what the pair itself costs on the stream
+  for (int i = 0; i < 64; ++i) { ProfScope p(c, KC_EVENT_NONE, 0, 0); }
   c->prof_now = was;
   HIPCHK(c, hipStreamSynchronize(c->stream));
   prof_collect(c);

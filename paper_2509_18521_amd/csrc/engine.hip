@@ -123,7 +123,7 @@ struct april_ctx {
   size_t qkv_stride = 0, proj_stride = 0;
   // bf16 MFMA attention: split-KV workspace
   bool attn_mfma = false, fuse_rope = true, tile_gemm = true, fuse_norm = true, fuse_down = false;
-  int tile_decode_rows = 160;   // decode gate/up goes through the LDS-tiled kernel from this many rows in flight (0 = never)
+  int tile_decode_rows = 128;   // decode gate/up goes through the LDS-tiled kernel from this bound on the rows in flight (0 = never)
   float* ssq = nullptr;         // [d_model / 32][m_cap] per-row partial sums of squares (fused norm)
   int attn_chunk = 256, attn_max_splits = 1, attn_ws_rows = 0;
   float* attn_ws = nullptr;

@@ -458,14 +458,24 @@ void launch_gemm_tile_swiglu(hipStream_t st, RowCtx rc, const bf16_t* x, const b
 // Decode with many rows in flight: fused gate/up + SiLU*mul with the skinny kernel's summation
 // chains (see CHAIN above) and, when ssq is set, the folded RMSNorm of that kernel.  Returns
 // false (nothing launched) when the shape does not allow it.
-// Measured on MI355X, 256 rows, fused gate/up of a 4096 x 14336 (2560 x 9728) MLP: 78 (49) us
-// against 128 (62) us for the skinny kernel; per 256 rows the time is flat, so it wins from about
-// 160 rows, and beyond 256 rows (two row groups) only where the weight tiles alone fill the chip.
-// A ring deeper than 3 stages made this variant 1.8x slower (the plain kernel does not care).
+// Measured on MI355X, fused gate/up of a 4096 x 14336 (2560 x 9728) MLP, event pairs around eager
+// launches: at a row bound of 128 the half-height tile takes 76 (43) us against 84 (53) us for the
+// skinny kernel (tie at 96, slower at 64); at 256 the full tile 91 (60) us against 132 (67) us;
+// beyond 256 rows (two row groups) it only pays where the weight tiles alone fill the chip.
+// A ring deeper than 3 stages made these variants 1.8x slower (the plain kernel does not care).
 bool launch_gemm_tile_swiglu_chain(hipStream_t st, RowCtx rc, const bf16_t* x, const bf16_t* Wg, const bf16_t* Wu,
                                    bf16_t* act, int F, int K, const float* ssq, int ssq_stride, float eps) {
   if (K % 128 != 0 || F % 32 != 0) return false;     // quarter boundaries on stage boundaries (BK = 2)
   if (rc.max_rows > 256 && F < 12288) return false;
+  if (rc.max_rows <= 128) {
+    // half-height tile (128 rows x 64 features, 2 x 2 accumulator tiles per wavefront)
+    dim3 grid(ceil_div(F >> 5, 2), 1);
+    hipLaunchKernelGGL((gemm_tile_chain_kernel<2, 2, 2, 2, 2, 3, TEPI_SWIGLU>), grid, dim3(256), 0, st, rc,
+                       reinterpret_cast<const bf16x8*>(x), reinterpret_cast<const bf16x8*>(Wg),
+                       reinterpret_cast<const bf16x8*>(Wu), nullptr, act, F, K,
+                       TileNorm{ssq, ssq_stride, K >> 5, 1.0f / (float)K, eps});
+    return true;
+  }
   const int f_tiles = F >> 5, m_tiles = ceil_div(rc.max_rows, 32);
   const TileNorm tn{ssq, ssq_stride, K >> 5, 1.0f / (float)K, eps};
   dim3 grid(ceil_div(f_tiles, 2), ceil_div(m_tiles, 8));

@@ -206,12 +206,13 @@ def test_cfg2_bench_launch_configuration_sampled_outputs():
         ap().april_destroy(ctx)
 
 
-def test_tiled_decode_gate_up_gives_the_skinny_kernels_bits(monkeypatch):
+@pytest.mark.parametrize("n_target,n_over", [(30, 40), (100, 150)])      # half-height tile; full tile
+def test_tiled_decode_gate_up_gives_the_skinny_kernels_bits(monkeypatch, n_target, n_over):
     """With many rows in flight the decode gate/up GEMM runs in the LDS-tiled kernel, which
     closes its accumulator chain at the skinny kernel's quarter boundaries and folds the same
     RMSNorm: forcing either kernel for every iteration must change no bit of any logit."""
     shape = ai.ModelShape(2, 256, 4, 2, 64, 512, 1024)
-    w = ai.Workload("tile_decode", shape, 8, 21, 30, 40, 9, 1.7, 0.4, 3, 9, ai.SAMPLER_GREEDY, 0, 2, 11)
+    w = ai.Workload("tile_decode", shape, 8, 21, n_target, n_over, 9, 1.7, 0.4, 3, 9, ai.SAMPLER_GREEDY, 0, 2, 11)
     weights = ai.make_weights(shape, w.seed)
     reqs = ai.make_requests(w, ai.requests_needed(w))
     runs = []

@@ -123,6 +123,7 @@ struct april_ctx {
   size_t qkv_stride = 0, proj_stride = 0;
   // bf16 MFMA attention: split-KV workspace
   bool attn_mfma = false, fuse_rope = true, tile_gemm = true, fuse_norm = true, fuse_down = false;
+  int moe_tall_rows = 2048;     // expert GEMMs: 4 m-tiles per workgroup from this row bound (prefill), 2 below
   int tile_decode_rows = 128;   // decode gate/up goes through the LDS-tiled kernel from this bound on the rows in flight (0 = never)
   float* ssq = nullptr;         // [d_model / 32][m_cap] per-row partial sums of squares (fused norm)
   int attn_chunk = 256, attn_max_splits = 1, attn_ws_rows = 0;
@@ -365,11 +366,11 @@ void forward(april_ctx* c, RowCtx rows, RowCtx srows, const int* gather, double 
       const double hit = std::min<double>(E, B * tk);   // bookkeeping estimate: experts that receive a token
       {
         ProfScope p(c, KC_MOE_GATEUP, hit * 2.0 * Fe * d * e + B * tk * (d + Fe) * e, 4.0 * B * tk * Fe * d);
-        launch_moe_gateup(st, rows, c->moe_cnt, c->moe_base, c->moe_src, (const bf16_t*)c->h_act, L.eg_s, L.eu_s, c->moe_act, E, Fe, d);
+        launch_moe_gateup(st, rows, c->moe_cnt, c->moe_base, c->moe_src, (const bf16_t*)c->h_act, L.eg_s, L.eu_s, c->moe_act, E, Fe, d, c->moe_tall_rows);
       }
       {
         ProfScope p(c, KC_MOE_DOWN, hit * 1.0 * Fe * d * e + B * tk * (Fe * e + d * 4.0), 2.0 * B * tk * Fe * d);
-        launch_moe_down(st, rows, c->moe_cnt, c->moe_base, c->moe_act, L.ed_s, c->moe_out, E, Fe, d);
+        launch_moe_down(st, rows, c->moe_cnt, c->moe_base, c->moe_act, L.ed_s, c->moe_out, E, Fe, d, c->moe_tall_rows);
       }
       continue;
     }
@@ -501,6 +502,7 @@ int april_init(const april_model_cfg* cfg, const april_tensor* weights, int32_t 
   const char* fd = getenv("APRIL_FUSE_DOWN");    // off by default: measured 5 % slower end to end on configuration 2
   c->fuse_down = fd && !strcmp(fd, "1");
   if (const char* td = getenv("APRIL_TILE_DECODE_ROWS")) c->tile_decode_rows = atoi(td);   // debug switch
+  if (const char* mt = getenv("APRIL_MOE_TALL_ROWS")) c->moe_tall_rows = atoi(mt);          // debug switch
   const char* tg = getenv("APRIL_TILE_GEMM");
   c->tile_gemm = !(tg && !strcmp(tg, "0"));
   const char* gr = getenv("APRIL_GRAPH");

@@ -71,9 +71,10 @@ void launch_moe_route(hipStream_t st, RowCtx rc, const float* logits, int n_part
 void launch_moe_dispatch(hipStream_t st, RowCtx rc, const int* ids, int E, int top_k, int* cnt, int* base,
                          int* pos_of, int* src_row, int p_cap, Ctrl* ctrl);
 void launch_moe_gateup(hipStream_t st, RowCtx rc, const int* cnt, const int* base, const int* src_row,
-                       const bf16_t* h, const bf16_t* Wg, const bf16_t* Wu, bf16_t* act, int E, int Fe, int d);
+                       const bf16_t* h, const bf16_t* Wg, const bf16_t* Wu, bf16_t* act, int E, int Fe, int d,
+                       int tall_rows);   // row bound from which a workgroup takes 4 m-tiles of an expert instead of 2
 void launch_moe_down(hipStream_t st, RowCtx rc, const int* cnt, const int* base, const bf16_t* act,
-                     const bf16_t* Wd, float* out, int E, int Fe, int d);
+                     const bf16_t* Wd, float* out, int E, int Fe, int d, int tall_rows);
 
 template <typename T>
 void launch_rope_append(hipStream_t st, RowCtx rc, Slots s, const float* qkv, int n_partials,

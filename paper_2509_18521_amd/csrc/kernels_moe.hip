@@ -136,7 +136,7 @@ __global__ __launch_bounds__(64 * MOE_KW) void moe_gemm_kernel(const int* stop, 
                                                               const bf16x8* __restrict__ w1, size_t w_expert_stride,
                                                               float* __restrict__ out, bf16_t* __restrict__ act,
                                                               int N, int K, int x_cols) {
-  constexpr int KU = 8;
+  constexpr int KU = MT > 2 ? 4 : 8;            // k-tiles requested together (register budget)
   __shared__ float red[(MOE_KW - 1) * NT * MT * 16 * 64];
   if (stop != nullptr && *stop != 0) return;
   const int e = blockIdx.y;
@@ -262,7 +262,17 @@ __global__ __launch_bounds__(64 * MOE_KW) void moe_gemm_kernel(const int* stop, 
 }
 
 void launch_moe_gateup(hipStream_t st, RowCtx rc, const int* cnt, const int* base, const int* src_row,
-                       const bf16_t* h, const bf16_t* Wg, const bf16_t* Wu, bf16_t* act, int E, int Fe, int d) {
+                       const bf16_t* h, const bf16_t* Wg, const bf16_t* Wu, bf16_t* act, int E, int Fe, int d, int tall_rows) {
+  // tall batches (prefill): 4 m-tiles per workgroup, so an expert's weight tile is fetched half as
+  // often; the summation chain of an output element does not depend on the grouping
+  if (rc.max_rows >= tall_rows) {
+    constexpr int MT = 4;
+    dim3 grid(Fe >> 5, E, ceil_div(ceil_div(rc.max_rows, 32), MT));
+    hipLaunchKernelGGL((moe_gemm_kernel<2, MT, true>), grid, dim3(64 * MOE_KW), 0, st, reinterpret_cast<const int*>(rc.ctl) + 1, cnt, base, src_row,
+                       reinterpret_cast<const bf16x8*>(h), reinterpret_cast<const bf16x8*>(Wg),
+                       reinterpret_cast<const bf16x8*>(Wu), (size_t)Fe * d / 8, nullptr, act, Fe, d, d);
+    return;
+  }
   constexpr int MT = 2;
   dim3 grid(Fe >> 5, E, ceil_div(ceil_div(rc.max_rows, 32), MT));
   hipLaunchKernelGGL((moe_gemm_kernel<2, MT, true>), grid, dim3(64 * MOE_KW), 0, st, reinterpret_cast<const int*>(rc.ctl) + 1, cnt, base, src_row,
@@ -271,7 +281,15 @@ void launch_moe_gateup(hipStream_t st, RowCtx rc, const int* cnt, const int* bas
 }
 
 void launch_moe_down(hipStream_t st, RowCtx rc, const int* cnt, const int* base, const bf16_t* act,
-                     const bf16_t* Wd, float* out, int E, int Fe, int d) {
+                     const bf16_t* Wd, float* out, int E, int Fe, int d, int tall_rows) {
+  if (rc.max_rows >= tall_rows) {
+    constexpr int MT = 4;
+    dim3 grid((d >> 5) / 2, E, ceil_div(ceil_div(rc.max_rows, 32), MT));
+    hipLaunchKernelGGL((moe_gemm_kernel<2, MT, false>), grid, dim3(64 * MOE_KW), 0, st, reinterpret_cast<const int*>(rc.ctl) + 1, cnt, base, nullptr,
+                       reinterpret_cast<const bf16x8*>(act), reinterpret_cast<const bf16x8*>(Wd), nullptr,
+                       (size_t)d * Fe / 8, out, nullptr, d, Fe, Fe);
+    return;
+  }
   constexpr int MT = 2;
   dim3 grid((d >> 5) / 2, E, ceil_div(ceil_div(rc.max_rows, 32), MT));
   hipLaunchKernelGGL((moe_gemm_kernel<2, MT, false>), grid, dim3(64 * MOE_KW), 0, st, reinterpret_cast<const int*>(rc.ctl) + 1, cnt, base, nullptr,

@@ -106,3 +106,34 @@ def test_moe_resumed_equals_uninterrupted():
     finally:
         ap().april_destroy(c1)
         ap().april_destroy(c2)
+
+
+def test_expert_gemm_grouping_changes_no_bit(monkeypatch):
+    """Tall batches (prefill) give a workgroup 4 m-tiles of an expert's rows instead of 2; the
+    grouping is not part of any summation chain: forcing either for every launch of a run
+    (prefill and decode) leaves every logit bit-identical."""
+    shape = ai.ModelShape(2, 128, 4, 2, 32, 0, 512, n_experts=32, experts_per_tok=2, d_expert_ffn=64)
+    w = ai.Workload("moe_group", shape, 6, 150, 6, 9, 6, 1.5, 0.3, 3, 6, ai.SAMPLER_GREEDY, 0, 2, 23)
+    weights = ai.make_weights(shape, w.seed)
+    reqs = ai.make_requests(w, ai.requests_needed(w))
+    runs = []
+    for tall in ("1", "1000000000"):              # always 4 m-tiles / always 2
+        monkeypatch.setenv("APRIL_MOE_TALL_ROWS", tall)
+        ctx = make_engine(w, weights, debug=True)
+        try:
+            for r in reqs:
+                ap().april_debug_watch(ctx, r.request_id, 0, w.max_new)
+            got = run_gpu(ctx, reqs, w.n_target, w.n_overprovision, w.max_new, w.steps)
+            logits = {}
+            for g in got:
+                for rid, toks in list(zip(g["ids"], g["tokens"])) + list(g["buffer_tokens"].items()):
+                    for i in range(len(toks)):
+                        logits[(rid, i)] = ap().april_debug_logits(ctx, rid, i, shape.vocab)[0]
+            runs.append((got, logits))
+        finally:
+            ap().april_destroy(ctx)
+    (a, la), (b, lb) = runs
+    assert_schedule_equal(b, a)
+    assert [g["tokens"] for g in a] == [g["tokens"] for g in b]
+    assert la.keys() == lb.keys() and len(la) > 40
+    assert all(np.array_equal(la[k], lb[k]) for k in la)

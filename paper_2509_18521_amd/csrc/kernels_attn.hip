@@ -49,14 +49,16 @@ struct AttnFuse {              // inputs of the fused rotary + append (FUSED onl
 };
 
 template <int DH, bool FUSED>
-__global__ __launch_bounds__(64 * att_waves(DH, FUSED)) void attn_decode_kernel(
+__global__ __launch_bounds__(64 * att_waves(DH, FUSED)) __attribute__((amdgpu_waves_per_eu(2))) void attn_decode_kernel(
     RowCtx rc, int row_base, Slots s, const float* __restrict__ q_rot, bf16_t* kv_pool, KVLayout L, int layer,
     int Hq, bf16_t* __restrict__ out, float* __restrict__ ws, int max_splits, AttnFuse fz) {
   constexpr int KC = DH / 32;      // k-chunks of the QK product
   constexpr int DT = DH / 16;      // dim tiles of the PV product
   constexpr int REC = 32 + 16 * DH;   // floats of one partial result: m[16], l[16], o[16][DH]
   constexpr int ATT_WAVES = att_waves(DH, FUSED);
-  __shared__ float lds[ATT_WAVES * REC];
+  constexpr int RS = DH + 4;          // padded row stride of O in LDS
+  constexpr int LREC = 32 + 16 * RS;
+  __shared__ float lds[ATT_WAVES * LREC];
   __shared__ bf16_t s_knew[DH], s_vnew[DH];
   // Workgroup ids are dealt to the 8 XCDs in turn, so with a row count that is a multiple of 8 the
   // plain mapping would put every (KV head, split) of a row on one XCD and a long row would
@@ -126,9 +128,13 @@ __global__ __launch_bounds__(64 * att_waves(DH, FUSED)) void attn_decode_kernel(
     // the q partials, the rotary table, for the owner of the new token also its k / v partials -
     // (3) the first KV tiles, which need the page ids.  Loads complete in order, so waiting for
     // (2) does not wait for (3), and the rotation arithmetic runs while the tiles arrive.
-    constexpr bool ALL = DH <= 64;              // (2) fits the register file for every k-chunk at once
+    // Narrow heads: (2) and (3) fit the register file together.  Wide heads: (2) for every k-chunk
+    // at once fits only while the tile registers are still free, so the rotation runs before (3)
+    // is requested - one round trip for all of (2) instead of one per k-chunk and partial.
+    constexpr bool ALL = true;
+    constexpr bool TILES_FIRST = DH <= 64;
     constexpr int QC = ALL ? KC : 1;
-    constexpr int QB = ALL ? 4 : 1;             // partials requested together (wide heads: one, to stay at two workgroups per CU)
+    constexpr int QB = DH <= 64 ? 4 : 2;        // partials requested together
     const int hq = hh < G ? hh : G - 1;
     const int ncol = (Hq + 2 * Hkv) * DH;
     const float* qsrc = fz.qkv + (size_t)r * ncol + (size_t)(kvh * G + hq) * DH;
@@ -174,8 +180,10 @@ __global__ __launch_bounds__(64 * att_waves(DH, FUSED)) void attn_decode_kernel(
       if (owner && lane < DH) request_kv(lane, 0);
       __builtin_amdgcn_sched_barrier(0);
     }
-    first_tiles();
-    __builtin_amdgcn_sched_barrier(0);
+    if constexpr (TILES_FIRST) {
+      first_tiles();
+      __builtin_amdgcn_sched_barrier(0);
+    }
 #pragma unroll
     for (int c = 0; c < KC; ++c) {
       const int sc = ALL ? c : 0;
@@ -195,6 +203,11 @@ __global__ __launch_bounds__(64 * att_waves(DH, FUSED)) void attn_decode_kernel(
         const float rot = lo ? rope_first(av, bv, cv, sv2) : rope_second(av, bv, cv, sv2);
         qf[c][j] = hh < G ? (bf16_t)rot : (bf16_t)0.f;
       }
+    }
+    if constexpr (!TILES_FIRST) {
+      __builtin_amdgcn_sched_barrier(0);
+      first_tiles();
+      __builtin_amdgcn_sched_barrier(0);
     }
     if (owner) {
       // the new token: rotated key and value of this KV head, to the page and to LDS
@@ -239,83 +252,89 @@ __global__ __launch_bounds__(64 * att_waves(DH, FUSED)) void attn_decode_kernel(
 #pragma unroll
   for (int d = 0; d < DT; ++d) oacc[d] = f32x4{};
 
-  if (wave < n_tiles) {
-    for (int tile = wave; tile < n_tiles; tile += ATT_WAVES) {
-      bf16x8 kn[2][KC];
-      bf16x4 vn[2][DT];
-      constexpr int AHEAD = (DEEP ? 2 : 1) * ATT_WAVES;
-      const int nxt = tile + AHEAD < n_tiles ? tile + AHEAD : n_tiles - 1;
-      load_tile(nxt, kn, vn);
-      __builtin_amdgcn_sched_barrier(0);
-
-      const int t0 = t_begin + tile * 32;
-      if (FUSED && last_split && tile == ((pos - t_begin) >> 5)) {
-        // the tile that holds the new token: take its key / value from LDS (the page copy may
-        // not be visible yet); same bf16 values as the page now holds
-        const int pp = ((pos - t_begin) >> 4) & 1, tin = pos & 15;
-#pragma unroll
-        for (int p = 0; p < 2; ++p) {
-          if (p != pp) continue;
-          if (hh == tin) {
-#pragma unroll
-            for (int c = 0; c < KC; ++c)
-#pragma unroll
-              for (int j = 0; j < 8; ++j) kf[p][c][j] = s_knew[32 * c + 8 * g + j];
-          }
-          if ((tin >> 2) == g) {
-#pragma unroll
-            for (int d = 0; d < DT; ++d) {
-              const bf16_t nv = s_vnew[d * 16 + hh];
-#pragma unroll
-              for (int j = 0; j < 4; ++j)
-                if (j == (tin & 3)) vf[p][d][j] = nv;
-            }
-          }
-        }
-      }
-      f32x4 sacc[2];
+  // One tile: scores, online softmax, PV; reads kf / vf.
+  auto compute_tile = [&](int tile) {
+    const int t0 = t_begin + tile * 32;
+    if (FUSED && last_split && tile == ((pos - t_begin) >> 5)) {
+      // the tile that holds the new token: take its key / value from LDS (the page copy may
+      // not be visible yet); same bf16 values as the page now holds
+      const int pp = ((pos - t_begin) >> 4) & 1, tin = pos & 15;
 #pragma unroll
       for (int p = 0; p < 2; ++p) {
-        sacc[p] = f32x4{};
+        if (p != pp) continue;
+        if (hh == tin) {
 #pragma unroll
-        for (int c = 0; c < KC; ++c)
-          sacc[p] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[p][c], qf[c], sacc[p], 0, 0, 0);
-      }
-      float sv[8];
-      float mx = -INFINITY;
+          for (int c = 0; c < KC; ++c)
 #pragma unroll
-      for (int p = 0; p < 2; ++p)
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const int tok = t0 + p * 16 + 4 * g + i;
-          const float v = tok < t_end ? sacc[p][i] * scale : -INFINITY;
-          sv[p * 4 + i] = v;
-          mx = fmaxf(mx, v);
+            for (int j = 0; j < 8; ++j) kf[p][c][j] = s_knew[32 * c + 8 * g + j];
         }
-      mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-      const float m_new = fmaxf(m_run, mx);
-      const float corr = __expf(m_run - m_new);
-      float rs = 0.f;
-      bf16x8 pf;
+        if ((tin >> 2) == g) {
 #pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const float pe = __expf(sv[e] - m_new);
-        rs += pe;
-        pf[e] = (bf16_t)pe;
+          for (int d = 0; d < DT; ++d) {
+            const bf16_t nv = s_vnew[d * 16 + hh];
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+              if (j == (tin & 3)) vf[p][d][j] = nv;
+          }
+        }
       }
-      rs += __shfl_xor(rs, 16, 64);
-      rs += __shfl_xor(rs, 32, 64);
-      l_run = l_run * corr + rs;
-      m_run = m_new;
+    }
+    f32x4 sacc[2];
 #pragma unroll
-      for (int d = 0; d < DT; ++d) {
-        oacc[d] *= corr;
-        bf16x8 af;
+    for (int p = 0; p < 2; ++p) {
+      sacc[p] = f32x4{};
 #pragma unroll
-        for (int j = 0; j < 4; ++j) { af[j] = vf[0][d][j]; af[4 + j] = vf[1][d][j]; }
-        oacc[d] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af, pf, oacc[d], 0, 0, 0);
+      for (int c = 0; c < KC; ++c)
+        sacc[p] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[p][c], qf[c], sacc[p], 0, 0, 0);
+    }
+    float sv[8];
+    float mx = -INFINITY;
+#pragma unroll
+    for (int p = 0; p < 2; ++p)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int tok = t0 + p * 16 + 4 * g + i;
+        const float v = tok < t_end ? sacc[p][i] * scale : -INFINITY;
+        sv[p * 4 + i] = v;
+        mx = fmaxf(mx, v);
       }
+    mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    const float m_new = fmaxf(m_run, mx);
+    const float corr = __expf(m_run - m_new);
+    float rs = 0.f;
+    bf16x8 pf;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const float pe = __expf(sv[e] - m_new);
+      rs += pe;
+      pf[e] = (bf16_t)pe;
+    }
+    rs += __shfl_xor(rs, 16, 64);
+    rs += __shfl_xor(rs, 32, 64);
+    l_run = l_run * corr + rs;
+    m_run = m_new;
+#pragma unroll
+    for (int d = 0; d < DT; ++d) {
+      oacc[d] *= corr;
+      bf16x8 af;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) { af[j] = vf[0][d][j]; af[4 + j] = vf[1][d][j]; }
+      oacc[d] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af, pf, oacc[d], 0, 0, 0);
+    }
+  };
+  // Steady state: the tile AHEAD tiles further on is requested before this one is used.  The
+  // tiles that have no such successor are peeled off below, so no wavefront ends its loop
+  // waiting for a load it will not use (that wait was a full memory latency per wavefront).
+  if (wave < n_tiles) {
+    constexpr int AHEAD = (DEEP ? 2 : 1) * ATT_WAVES;
+    int tile = wave;
+    for (; tile + AHEAD < n_tiles; tile += ATT_WAVES) {
+      bf16x8 kn[2][KC];
+      bf16x4 vn[2][DT];
+      load_tile(tile + AHEAD, kn, vn);
+      __builtin_amdgcn_sched_barrier(0);
+      compute_tile(tile);
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int p = 0; p < 2; ++p) {
@@ -329,59 +348,62 @@ __global__ __launch_bounds__(64 * att_waves(DH, FUSED)) void attn_decode_kernel(
         }
       }
     }
+    compute_tile(tile);                          // tile < n_tiles here: the loop leaves at least one
+    if constexpr (DEEP) {
+      if (tile + ATT_WAVES < n_tiles) {
+#pragma unroll
+        for (int p = 0; p < 2; ++p) {
+#pragma unroll
+          for (int c = 0; c < KC; ++c) kf[p][c] = km[p][c];
+#pragma unroll
+          for (int d = 0; d < DT; ++d) vf[p][d] = vm[p][d];
+        }
+        compute_tile(tile + ATT_WAVES);
+      }
+    }
   }
 
   // ---- merge the wavefronts of this workgroup through LDS, in wavefront order -----------
+  // Every wavefront publishes (m, l, O); then each merges its share of the dim tiles (tile d
+  // goes to wavefront d % ATT_WAVES) and writes it out, so the tail of a workgroup's life is
+  // shared by all of them.  Rows of O are padded by 4 floats in LDS: with a stride of DH floats
+  // the 16 heads of a lane group would all hit the same banks.
   {
-    float* my = lds + wave * REC;
+    float* my = lds + wave * LREC;
     if (g == 0) { my[hh] = m_run; my[16 + hh] = l_run; }
 #pragma unroll
-    for (int d = 0; d < DT; ++d) *reinterpret_cast<f32x4*>(my + 32 + hh * DH + d * 16 + 4 * g) = oacc[d];
+    for (int d = 0; d < DT; ++d) *reinterpret_cast<f32x4*>(my + 32 + hh * RS + d * 16 + 4 * g) = oacc[d];
   }
   __syncthreads();
-  if (wave != 0) {
-    if (n_splits == 1) return;
-  } else {
-    float M = lds[hh];
+  float M = lds[hh];
 #pragma unroll
-    for (int w = 1; w < ATT_WAVES; ++w) M = fmaxf(M, lds[w * REC + hh]);
-    float lsum = 0.f;
+  for (int w = 1; w < ATT_WAVES; ++w) M = fmaxf(M, lds[w * LREC + hh]);
+  float wgt[ATT_WAVES], lsum = 0.f;
 #pragma unroll
-    for (int d = 0; d < DT; ++d) oacc[d] = f32x4{};
-#pragma unroll
-    for (int w = 0; w < ATT_WAVES; ++w) {
-      const float* p = lds + w * REC;
-      const float wgt = __expf(p[hh] - M);
-      lsum += wgt * p[16 + hh];
-#pragma unroll
-      for (int d = 0; d < DT; ++d) oacc[d] += *reinterpret_cast<const f32x4*>(p + 32 + hh * DH + d * 16 + 4 * g) * wgt;
-    }
-    m_run = M;
-    l_run = lsum;
+  for (int w = 0; w < ATT_WAVES; ++w) {
+    wgt[w] = __expf(lds[w * LREC + hh] - M);
+    lsum += wgt[w] * lds[w * LREC + 16 + hh];
   }
-
   const int K = Hq * DH;
-  if (n_splits == 1) {
-    if (hh < G) {
-      const float inv = 1.0f / l_run;
+  const float inv = 1.0f / lsum;
+  float* rec = ws + (((size_t)wr * Hkv + kvh) * max_splits + split) * REC;     // several splits: (m, l, O) for the merge kernel
+  for (int d = wave; d < DT; d += ATT_WAVES) {
+    f32x4 o = f32x4{};
 #pragma unroll
-      for (int d = 0; d < DT; ++d) {
-        bf16x4 o;
+    for (int w = 0; w < ATT_WAVES; ++w)
+      o += *reinterpret_cast<const f32x4*>(lds + w * LREC + 32 + hh * RS + d * 16 + 4 * g) * wgt[w];
+    if (n_splits == 1) {
+      if (hh < G) {
+        bf16x4 ob;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) o[i] = (bf16_t)(oacc[d][i] * inv);
-        *reinterpret_cast<bf16x4*>(out + act_index<true>(r, (kvh * G + hh) * DH + d * 16 + 4 * g, K)) = o;
+        for (int i = 0; i < 4; ++i) ob[i] = (bf16_t)(o[i] * inv);
+        *reinterpret_cast<bf16x4*>(out + act_index<true>(r, (kvh * G + hh) * DH + d * 16 + 4 * g, K)) = ob;
       }
+    } else {
+      *reinterpret_cast<f32x4*>(rec + 32 + hh * DH + d * 16 + 4 * g) = o;
     }
-    return;
   }
-
-  // ---- several splits: publish (m, l, O) for the merge kernel -----------------------------
-  if (wave == 0) {
-    float* my = ws + (((size_t)wr * Hkv + kvh) * max_splits + split) * REC;
-    if (g == 0) { my[hh] = m_run; my[16 + hh] = l_run; }
-#pragma unroll
-    for (int d = 0; d < DT; ++d) *reinterpret_cast<f32x4*>(my + 32 + hh * DH + d * 16 + 4 * g) = oacc[d];
-  }
+  if (n_splits > 1 && wave == 0 && g == 0) { rec[hh] = M; rec[16 + hh] = lsum; }
 }
 
 // Merge of the per-split partial results of the rows whose context spans several splits

@@ -218,12 +218,20 @@ void launch_free_slots(hipStream_t st, Ctrl* ctrl, Slots s, const int* slot_list
   hipLaunchKernelGGL(free_slots_kernel, dim3(1), dim3(256), 0, st, ctrl, s, slot_list, n, free_stack);
 }
 
-__global__ void iota_kernel(int* p, int n) {
+// The free stack starts as a permutation that puts successive pops far apart: pop j hands out
+// page (j * stride) mod n with stride ~ 0.618 n, coprime to n.  A prompt takes its pages in
+// one go, and a row whose pages are consecutive in memory streams slower (the attention's
+// load pattern alone: 5.4 TB/s against 6.0-6.1 TB/s for scattered or interleaved pages).
+__global__ void free_stack_init_kernel(int* p, int n, int stride) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < n) p[i] = n - 1 - i;     // top of the stack hands out page 0 first
+  if (i < n) p[i] = (int)(((long long)(n - 1 - i) * stride) % n);     // the top of the stack is popped first
 }
 void launch_init_free_stack(hipStream_t st, int* free_stack, int n_blocks) {
-  hipLaunchKernelGGL(iota_kernel, dim3(ceil_div(n_blocks, 256)), dim3(256), 0, st, free_stack, n_blocks);
+  int stride = (int)((double)n_blocks * 0.6180339887) | 1;
+  auto gcd = [](int a, int b) { while (b) { const int t = a % b; a = b; b = t; } return a; };
+  while (stride < n_blocks && gcd(stride, n_blocks) != 1) stride += 2;
+  if (stride >= n_blocks) stride = 1;
+  hipLaunchKernelGGL(free_stack_init_kernel, dim3(ceil_div(n_blocks, 256)), dim3(256), 0, st, free_stack, n_blocks, stride);
 }
 __global__ void fill_i32_kernel(int* p, int v, size_t n) {
   size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;

@@ -399,8 +399,10 @@ __global__ __launch_bounds__(64 * att_waves(DH, FUSED)) __attribute__((amdgpu_wa
         for (int i = 0; i < 4; ++i) ob[i] = (bf16_t)(o[i] * inv);
         *reinterpret_cast<bf16x4*>(out + act_index<true>(r, (kvh * G + hh) * DH + d * 16 + 4 * g, K)) = ob;
       }
-    } else {
-      *reinterpret_cast<f32x4*>(rec + 32 + hh * DH + d * 16 + 4 * g) = o;
+    } else if (hh < G) {
+      // record layout [dim tile][head][16 dims]: the lanes of one store cover consecutive
+      // addresses, and only the G heads of the group are written (and read back)
+      *reinterpret_cast<f32x4*>(rec + 32 + (d * 16 + hh) * 16 + 4 * g) = o;
     }
   }
   if (n_splits > 1 && wave == 0 && g == 0) { rec[hh] = M; rec[16 + hh] = lsum; }
@@ -445,7 +447,8 @@ __global__ __launch_bounds__(64) void attn_merge_kernel(RowCtx rc, int row_base,
       mi[u] = p[hh];
       li[u] = p[16 + hh];
 #pragma unroll
-      for (int d = 0; d < DT; ++d) o[u][d] = *reinterpret_cast<const f32x4*>(p + 32 + hh * DH + d * 16 + 4 * g);
+      for (int d = 0; d < DT; ++d)
+        o[u][d] = hh < G ? *reinterpret_cast<const f32x4*>(p + 32 + (d * 16 + hh) * 16 + 4 * g) : f32x4{};
     }
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll

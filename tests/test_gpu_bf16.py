@@ -109,12 +109,15 @@ def test_long_context_spans_several_kv_splits(head_dim):
     teacher_forced_parity(w, 2, 5, min_rows=12)
 
 
-def test_more_than_128_rows_in_flight():
-    """160 rollouts in flight: several m-groups in every decode GEMM, and the LM head goes through
-    the tall-batch kernel (its sampling rows exceed 128) in prefill and in decode."""
-    shape = ai.ModelShape(2, 128, 4, 2, 32, 256, 512)
-    w = ai.Workload("many_rows", shape, 40, 6, 100, 160, 5, 1.2, 0.4, 2, 5, ai.SAMPLER_GREEDY, 0, 1, 5)
-    teacher_forced_parity(w, 1, 160, min_rows=300)
+@pytest.mark.parametrize("n_target,n_over,d_model", [(100, 160, 128), (200, 300, 128), (100, 160, 192)])
+def test_more_than_128_rows_in_flight(n_target, n_over, d_model):
+    """160 / 300 rollouts in flight: several m-groups in every decode GEMM, the LM head through
+    the tall-batch kernel (its sampling rows exceed 128) in prefill and in decode, the gate/up GEMM
+    through the LDS-tiled kernel (160 rows), or not: beyond 256 rows with a narrow MLP, and with a
+    d_model that is not a multiple of 128, it stays on the skinny kernel."""
+    shape = ai.ModelShape(2, d_model, d_model // 32, 2, 32, 256, 512)
+    w = ai.Workload("many_rows", shape, 40, 6, n_target, n_over, 5, 1.2, 0.4, 2, 5, ai.SAMPLER_GREEDY, 0, 1, 5)
+    teacher_forced_parity(w, 1, n_over, min_rows=2 * n_over - 20)
 
 
 def test_bf16_scheduling_invariance():

@@ -135,7 +135,7 @@ struct april_ctx {
   int n_experts = 0, top_k_experts = 0, d_expert = 0, s_router = 1, moe_p_cap = 0;
   size_t router_stride = 0;
   float *router_out = nullptr, *moe_wts = nullptr, *moe_out = nullptr;
-  int *moe_ids = nullptr, *moe_pos = nullptr, *moe_cnt = nullptr, *moe_base = nullptr, *moe_src = nullptr;
+  int *moe_ids = nullptr, *moe_pos = nullptr, *moe_cnt = nullptr, *moe_base = nullptr, *moe_src = nullptr, *moe_group = nullptr;
   bf16_t* moe_act = nullptr;
   int64_t expert_bytes = 0;    // bytes of one expert's three matrices
   // one decode iteration (scheduler + forward + sample) captured as a HIP graph, keyed by
@@ -362,15 +362,16 @@ void forward(april_ctx* c, RowCtx rows, RowCtx srows, const int* gather, double 
       gemm(KC_MOE_ROUTE, rows, c->h_act, nullptr, L.router_s, c->router_out, E, d, sr, c->router_stride, B);
       launch_moe_route(st, rows, c->router_out, sr, c->router_stride, E, tk, c->moe_ids, c->moe_wts);
       launch_moe_dispatch(st, rows, c->moe_ids, E, tk, c->moe_cnt, c->moe_base, c->moe_pos, c->moe_src, c->moe_p_cap,
-                          rows.ctl == reinterpret_cast<const int2*>(c->d_ctrl) ? c->d_ctrl : nullptr);
+                          rows.ctl == reinterpret_cast<const int2*>(c->d_ctrl) ? c->d_ctrl : nullptr, c->moe_tall_rows,
+                          c->moe_group);
       const double hit = std::min<double>(E, B * tk);   // bookkeeping estimate: experts that receive a token
       {
         ProfScope p(c, KC_MOE_GATEUP, hit * 2.0 * Fe * d * e + B * tk * (d + Fe) * e, 4.0 * B * tk * Fe * d);
-        launch_moe_gateup(st, rows, c->moe_cnt, c->moe_base, c->moe_src, (const bf16_t*)c->h_act, L.eg_s, L.eu_s, c->moe_act, E, Fe, d, c->moe_tall_rows);
+        launch_moe_gateup(st, rows, c->moe_cnt, c->moe_base, c->moe_group, c->moe_src, (const bf16_t*)c->h_act, L.eg_s, L.eu_s, c->moe_act, E, tk, Fe, d, c->moe_tall_rows);
       }
       {
         ProfScope p(c, KC_MOE_DOWN, hit * 1.0 * Fe * d * e + B * tk * (Fe * e + d * 4.0), 2.0 * B * tk * Fe * d);
-        launch_moe_down(st, rows, c->moe_cnt, c->moe_base, c->moe_act, L.ed_s, c->moe_out, E, Fe, d, c->moe_tall_rows);
+        launch_moe_down(st, rows, c->moe_cnt, c->moe_base, c->moe_group, c->moe_act, L.ed_s, c->moe_out, E, tk, Fe, d, c->moe_tall_rows);
       }
       continue;
     }
@@ -679,10 +680,11 @@ int april_init(const april_model_cfg* cfg, const april_tensor* weights, int32_t 
     c->expert_bytes = (int64_t)3 * Fe * d * e;
     c->s_router = pick_ksplit(E, d);
     c->router_stride = M * E;
-    c->moe_p_cap = (int)((M * tk + (size_t)E * 31 + 31) / 32 * 32);
+    c->moe_p_cap = (int)((M * tk + (size_t)E * 127 + 127) / 128 * 128);   // expert segments are aligned to 64 or 128 rows
     TRY(dev_alloc(c, &c->router_out, (size_t)c->s_router * c->router_stride));
     TRY(dev_alloc(c, &c->moe_ids, M * tk)); TRY(dev_alloc(c, &c->moe_wts, M * tk)); TRY(dev_alloc(c, &c->moe_pos, M * tk));
     TRY(dev_alloc(c, &c->moe_cnt, E)); TRY(dev_alloc(c, &c->moe_base, E + 1)); TRY(dev_alloc(c, &c->moe_src, c->moe_p_cap));
+    TRY(dev_alloc(c, &c->moe_group, c->moe_p_cap / 64 + 1));
     TRY(dev_alloc(c, &c->moe_act, (size_t)c->moe_p_cap * Fe));
     TRY(dev_alloc(c, &c->moe_out, (size_t)c->moe_p_cap * d));
   }

@@ -69,12 +69,14 @@ void launch_add_rmsnorm(hipStream_t st, RowCtx rc, float* x_res, const float* pa
 void launch_moe_route(hipStream_t st, RowCtx rc, const float* logits, int n_partials, size_t partial_stride,
                       int E, int top_k, int* ids, float* wts);
 void launch_moe_dispatch(hipStream_t st, RowCtx rc, const int* ids, int E, int top_k, int* cnt, int* base,
-                         int* pos_of, int* src_row, int p_cap, Ctrl* ctrl);
-void launch_moe_gateup(hipStream_t st, RowCtx rc, const int* cnt, const int* base, const int* src_row,
-                       const bf16_t* h, const bf16_t* Wg, const bf16_t* Wu, bf16_t* act, int E, int Fe, int d,
-                       int tall_rows);   // row bound from which a workgroup takes 4 m-tiles of an expert instead of 2
-void launch_moe_down(hipStream_t st, RowCtx rc, const int* cnt, const int* base, const bf16_t* act,
-                     const bf16_t* Wd, float* out, int E, int Fe, int d, int tall_rows);
+                         int* pos_of, int* src_row, int p_cap, Ctrl* ctrl, int tall_rows, int* group_expert);
+// tall_rows: row bound from which a GEMM workgroup takes 4 m-tiles of an expert instead of 2
+// (the dispatch aligns the expert segments accordingly: pass the same value to all three)
+void launch_moe_gateup(hipStream_t st, RowCtx rc, const int* cnt, const int* base, const int* group_expert,
+                       const int* src_row, const bf16_t* h, const bf16_t* Wg, const bf16_t* Wu, bf16_t* act, int E,
+                       int top_k, int Fe, int d, int tall_rows);
+void launch_moe_down(hipStream_t st, RowCtx rc, const int* cnt, const int* base, const int* group_expert,
+                     const bf16_t* act, const bf16_t* Wd, float* out, int E, int top_k, int Fe, int d, int tall_rows);
 
 template <typename T>
 void launch_rope_append(hipStream_t st, RowCtx rc, Slots s, const float* qkv, int n_partials,

@@ -78,13 +78,18 @@ void launch_moe_route(hipStream_t st, RowCtx rc, const float* logits, int n_part
 
 // ---------------------------------------------------------------------------
 // Dispatch: one workgroup.  cnt[e] = tokens routed to expert e; base[e] = first packed row
-// of expert e (32-aligned so expert batches own whole MFMA tiles); pos_of[row*top_k + k] =
-// packed row of that assignment; src_row[packed row] = token row (-1 in the padding).
+// of expert e, aligned to `align` rows (the rows one GEMM workgroup covers: whole MFMA tiles, and
+// no workgroup straddles two experts); pos_of[row*top_k + k] = packed row of that assignment;
+// src_row[packed row] = token row (-1 in the padding); group_expert[g] = expert that owns packed
+// rows [g*align, (g+1)*align), -1 past the end.  The GEMMs launch one workgroup per (n-tile
+// group, row group) of that flat list: with a (expert, row group of the expert) grid sized for
+// the worst case, five of six workgroups of a decode launch - and nearly all of a prefill
+// launch - found nothing to do after a dependent load.
 // Placement inside an expert's batch is arbitrary (LDS atomics); values never depend on it.
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(1024) void moe_dispatch_kernel(RowCtx rc, const int* ids, int E, int top_k, int* cnt,
                                                             int* base, int* pos_of, int* src_row, int p_cap,
-                                                            Ctrl* ctrl) {
+                                                            Ctrl* ctrl, int align, int* group_expert, int n_groups) {
   __shared__ int s_cnt[256], s_base[257];
   const int rows = rows_or_zero(rc), tid = threadIdx.x;
   if (rows == 0) return;
@@ -96,13 +101,16 @@ __global__ __launch_bounds__(1024) void moe_dispatch_kernel(RowCtx rc, const int
   if (tid == 0) {
     int acc = 0;
     int hit = 0;
-    for (int e = 0; e < E; ++e) { s_base[e] = acc; acc += (s_cnt[e] + 31) & ~31; hit += s_cnt[e] > 0; }
+    for (int e = 0; e < E; ++e) { s_base[e] = acc; acc += (s_cnt[e] + align - 1) / align * align; hit += s_cnt[e] > 0; }
     s_base[E] = acc;
     if (ctrl != nullptr) ctrl->sum_experts += hit;
   }
   __syncthreads();
   const int total = s_base[E];
   for (int p = tid; p < total && p < p_cap; p += 1024) src_row[p] = -1;
+  if (tid < E)
+    for (int g = s_base[tid] / align; g < s_base[tid + 1] / align && g < n_groups; ++g) group_expert[g] = tid;
+  for (int g = total / align + tid; g < n_groups; g += 1024) group_expert[g] = -1;
   if (tid < E) { cnt[tid] = s_cnt[tid]; base[tid] = s_base[tid]; s_cnt[tid] = 0; }
   if (tid == 0) base[E] = total;
   __syncthreads();
@@ -114,16 +122,24 @@ __global__ __launch_bounds__(1024) void moe_dispatch_kernel(RowCtx rc, const int
   }
 }
 
+// rows per GEMM workgroup (and alignment of the expert segments) for a launch over at most max_rows rows
+int moe_group_rows(int max_rows, int tall_rows) { return max_rows >= tall_rows ? 128 : 64; }
+// upper bound on the row groups of such a launch
+int moe_group_count(int max_rows, int top_k, int E, int align) {
+  return (int)(((long long)max_rows * top_k + (long long)E * (align - 1) + align - 1) / align);
+}
+
 void launch_moe_dispatch(hipStream_t st, RowCtx rc, const int* ids, int E, int top_k, int* cnt, int* base,
-                         int* pos_of, int* src_row, int p_cap, Ctrl* ctrl) {
+                         int* pos_of, int* src_row, int p_cap, Ctrl* ctrl, int tall_rows, int* group_expert) {
+  const int align = moe_group_rows(rc.max_rows, tall_rows);
   hipLaunchKernelGGL(moe_dispatch_kernel, dim3(1), dim3(1024), 0, st, rc, ids, E, top_k, cnt, base, pos_of, src_row,
-                     p_cap, ctrl);
+                     p_cap, ctrl, align, group_expert, moe_group_count(rc.max_rows, top_k, E, align));
 }
 
 // ---------------------------------------------------------------------------
-// Grouped expert GEMMs.  grid: x = n-tile group inside the expert, y = expert, z = group of
-// MT m-tiles of that expert's batch.  The 4 wavefronts of a workgroup split the k range
-// (LDS reduction in wavefront order).
+// Grouped expert GEMMs.  grid: x = n-tile group inside the expert, y = row group of the flat
+// packed list (MT m-tiles of one expert, see the dispatch kernel).  The 4 wavefronts of a
+// workgroup split the k range (LDS reduction in wavefront order).
 //   GATHER = true : the B operand rows are token rows looked up through src_row (gate/up);
 //   GATHER = false: the B operand is the packed fragment-tiled activation (down).
 // ---------------------------------------------------------------------------
@@ -131,6 +147,7 @@ constexpr int MOE_KW = 4;
 
 template <int NT, int MT, bool SWIGLU>
 __global__ __launch_bounds__(64 * MOE_KW) void moe_gemm_kernel(const int* stop, const int* cnt, const int* base,
+                                                              const int* __restrict__ group_expert,
                                                               const int* src_row, const bf16x8* __restrict__ x,
                                                               const bf16x8* __restrict__ w0,
                                                               const bf16x8* __restrict__ w1, size_t w_expert_stride,
@@ -139,11 +156,12 @@ __global__ __launch_bounds__(64 * MOE_KW) void moe_gemm_kernel(const int* stop, 
   constexpr int KU = MT > 2 ? 4 : 8;            // k-tiles requested together (register budget)
   __shared__ float red[(MOE_KW - 1) * NT * MT * 16 * 64];
   if (stop != nullptr && *stop != 0) return;
-  const int e = blockIdx.y;
+  const int e = group_expert[blockIdx.y];
+  if (e < 0) return;
   const int rows_e = cnt[e];
-  const int mt0 = blockIdx.z * MT;
+  const int p0 = base[e];                       // first packed row of this expert (multiple of MT * 32)
+  const int mt0 = (int)blockIdx.y * MT - (p0 >> 5);   // first m-tile of this group inside the expert's batch
   if (mt0 * 32 >= rows_e) return;
-  const int p0 = base[e];                       // first packed row of this expert (multiple of 32)
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int KT = K >> 4;
   const int nt0 = SWIGLU ? blockIdx.x : blockIdx.x * NT;
@@ -261,40 +279,35 @@ __global__ __launch_bounds__(64 * MOE_KW) void moe_gemm_kernel(const int* stop, 
   }
 }
 
-void launch_moe_gateup(hipStream_t st, RowCtx rc, const int* cnt, const int* base, const int* src_row,
-                       const bf16_t* h, const bf16_t* Wg, const bf16_t* Wu, bf16_t* act, int E, int Fe, int d, int tall_rows) {
+void launch_moe_gateup(hipStream_t st, RowCtx rc, const int* cnt, const int* base, const int* group_expert,
+                       const int* src_row, const bf16_t* h, const bf16_t* Wg, const bf16_t* Wu, bf16_t* act, int E,
+                       int top_k, int Fe, int d, int tall_rows) {
   // tall batches (prefill): 4 m-tiles per workgroup, so an expert's weight tile is fetched half as
   // often; the summation chain of an output element does not depend on the grouping
-  if (rc.max_rows >= tall_rows) {
-    constexpr int MT = 4;
-    dim3 grid(Fe >> 5, E, ceil_div(ceil_div(rc.max_rows, 32), MT));
-    hipLaunchKernelGGL((moe_gemm_kernel<2, MT, true>), grid, dim3(64 * MOE_KW), 0, st, reinterpret_cast<const int*>(rc.ctl) + 1, cnt, base, src_row,
-                       reinterpret_cast<const bf16x8*>(h), reinterpret_cast<const bf16x8*>(Wg),
-                       reinterpret_cast<const bf16x8*>(Wu), (size_t)Fe * d / 8, nullptr, act, Fe, d, d);
-    return;
-  }
-  constexpr int MT = 2;
-  dim3 grid(Fe >> 5, E, ceil_div(ceil_div(rc.max_rows, 32), MT));
-  hipLaunchKernelGGL((moe_gemm_kernel<2, MT, true>), grid, dim3(64 * MOE_KW), 0, st, reinterpret_cast<const int*>(rc.ctl) + 1, cnt, base, src_row,
-                     reinterpret_cast<const bf16x8*>(h), reinterpret_cast<const bf16x8*>(Wg),
-                     reinterpret_cast<const bf16x8*>(Wu), (size_t)Fe * d / 8, nullptr, act, Fe, d, d);
+  const int align = moe_group_rows(rc.max_rows, tall_rows);
+  dim3 grid(Fe >> 5, moe_group_count(rc.max_rows, top_k, E, align));
+  const int* stop = reinterpret_cast<const int*>(rc.ctl) + 1;
+  const bf16x8 *hv = reinterpret_cast<const bf16x8*>(h), *gv = reinterpret_cast<const bf16x8*>(Wg), *uv = reinterpret_cast<const bf16x8*>(Wu);
+  if (align == 128)
+    hipLaunchKernelGGL((moe_gemm_kernel<2, 4, true>), grid, dim3(64 * MOE_KW), 0, st, stop, cnt, base, group_expert, src_row,
+                       hv, gv, uv, (size_t)Fe * d / 8, nullptr, act, Fe, d, d);
+  else
+    hipLaunchKernelGGL((moe_gemm_kernel<2, 2, true>), grid, dim3(64 * MOE_KW), 0, st, stop, cnt, base, group_expert, src_row,
+                       hv, gv, uv, (size_t)Fe * d / 8, nullptr, act, Fe, d, d);
 }
 
-void launch_moe_down(hipStream_t st, RowCtx rc, const int* cnt, const int* base, const bf16_t* act,
-                     const bf16_t* Wd, float* out, int E, int Fe, int d, int tall_rows) {
-  if (rc.max_rows >= tall_rows) {
-    constexpr int MT = 4;
-    dim3 grid((d >> 5) / 2, E, ceil_div(ceil_div(rc.max_rows, 32), MT));
-    hipLaunchKernelGGL((moe_gemm_kernel<2, MT, false>), grid, dim3(64 * MOE_KW), 0, st, reinterpret_cast<const int*>(rc.ctl) + 1, cnt, base, nullptr,
-                       reinterpret_cast<const bf16x8*>(act), reinterpret_cast<const bf16x8*>(Wd), nullptr,
-                       (size_t)d * Fe / 8, out, nullptr, d, Fe, Fe);
-    return;
-  }
-  constexpr int MT = 2;
-  dim3 grid((d >> 5) / 2, E, ceil_div(ceil_div(rc.max_rows, 32), MT));
-  hipLaunchKernelGGL((moe_gemm_kernel<2, MT, false>), grid, dim3(64 * MOE_KW), 0, st, reinterpret_cast<const int*>(rc.ctl) + 1, cnt, base, nullptr,
-                     reinterpret_cast<const bf16x8*>(act), reinterpret_cast<const bf16x8*>(Wd), nullptr,
-                     (size_t)d * Fe / 8, out, nullptr, d, Fe, Fe);
+void launch_moe_down(hipStream_t st, RowCtx rc, const int* cnt, const int* base, const int* group_expert,
+                     const bf16_t* act, const bf16_t* Wd, float* out, int E, int top_k, int Fe, int d, int tall_rows) {
+  const int align = moe_group_rows(rc.max_rows, tall_rows);
+  dim3 grid((d >> 5) / 2, moe_group_count(rc.max_rows, top_k, E, align));
+  const int* stop = reinterpret_cast<const int*>(rc.ctl) + 1;
+  const bf16x8 *av = reinterpret_cast<const bf16x8*>(act), *wv = reinterpret_cast<const bf16x8*>(Wd);
+  if (align == 128)
+    hipLaunchKernelGGL((moe_gemm_kernel<2, 4, false>), grid, dim3(64 * MOE_KW), 0, st, stop, cnt, base, group_expert, nullptr,
+                       av, wv, nullptr, (size_t)d * Fe / 8, out, nullptr, d, Fe, Fe);
+  else
+    hipLaunchKernelGGL((moe_gemm_kernel<2, 2, false>), grid, dim3(64 * MOE_KW), 0, st, stop, cnt, base, group_expert, nullptr,
+                       av, wv, nullptr, (size_t)d * Fe / 8, out, nullptr, d, Fe, Fe);
 }
 
 }  // namespace april

@@ -87,8 +87,8 @@ __global__ __launch_bounds__(64 * att_waves(DH, FUSED)) __attribute__((amdgpu_wa
   const int* bt = s.block_table + (size_t)slot * s.max_blocks + (t_begin >> 4);
   const int my_page = bt[lane < n_pages ? lane : n_pages - 1];
 
-  // tiles wave, wave + ATT_WAVES, ... of the split; the fetch of tile i+1 is always issued (clamped
-  // to the last tile) so that the wait counts are static
+  // A wavefront takes tiles wave, wave + ATT_WAVES, ... of the split.  Every load inside load_tile
+  // is unconditional (a missing second page is clamped), so the wait counts around it are static.
   auto load_tile = [&](int tile, bf16x8 (&kk)[2][KC], bf16x4 (&vv)[2][DT]) {
 #pragma unroll
     for (int p = 0; p < 2; ++p) {

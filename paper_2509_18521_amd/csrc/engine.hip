@@ -696,7 +696,7 @@ int april_init(const april_model_cfg* cfg, const april_tensor* weights, int32_t 
   TRY(dev_alloc_bytes(c, &c->act, M * std::max(F, 1) * e));
   TRY(dev_alloc_bytes(c, &c->hf, SR * d * e));
   if (c->attn_mfma) {
-    c->attn_chunk = attn_split_tokens();
+    c->attn_chunk = attn_split_tokens(g.head_dim);
     c->attn_max_splits = ceil_div(g.max_ctx, c->attn_chunk);
     const size_t rec = 32 + (size_t)16 * g.head_dim;
     // rows per attention launch: all decode rows; prefill chunks go in pieces of up to 4096 rows

@@ -92,7 +92,7 @@ void launch_attn_ref(hipStream_t st, RowCtx rc, Slots s, const float* q_rot, con
 // that fixed size, so a row's reduction order depends on its own length only; ws /
 // counters: split workspace for rc.max_rows rows (counters zero on entry and on exit);
 // max_splits <= 32.
-int attn_split_tokens();
+int attn_split_tokens(int head_dim);
 // fused_qkv != nullptr (decode iterations): the kernel also rotates q / the new key and
 // appends the new key / value itself from the QKV GEMM's split-K partials (q_rot unused).
 void launch_attn_decode(hipStream_t st, RowCtx rc, int row_base, Slots s, const float* q_rot,

@@ -33,10 +33,16 @@
 
 namespace april {
 
-#ifndef ATT_SPLIT_TOKENS
-#define ATT_SPLIT_TOKENS 1024
+#ifndef ATT_SPLIT_64
+#define ATT_SPLIT_64 1024
 #endif
-constexpr int ATT_SPLIT = ATT_SPLIT_TOKENS;   // tokens per KV split (at most 64 pages: one page id per lane)
+#ifndef ATT_SPLIT_128
+#define ATT_SPLIT_128 1024
+#endif
+// tokens per KV split, a multiple of 1024 (a lane holds one page id per 1024 tokens of the split).
+// 2048 was measured for both head sizes: head_dim 64 (small model, 5 steps) 1.6 % slower end to end;
+// head_dim 128: +1.6 % on 4000-token rows, -4.5 % on a ragged batch.  512: 7 % slower on long rows.
+constexpr int att_split(int dh) { return dh == 64 ? ATT_SPLIT_64 : (dh == 128 ? ATT_SPLIT_128 : 1024); }
 // wavefronts per workgroup (8 for head_dim <= 64 was measured: 11.8 us against 10.6 us per launch)
 constexpr int att_waves(int dh, bool fused) { return 4; }
 
@@ -71,6 +77,8 @@ __global__ __launch_bounds__(64 * att_waves(DH, FUSED)) __attribute__((amdgpu_wa
   ROW_GUARD(rc, r);
   const int slot = slot_raw;
   const int ctx = pos + 1;
+  constexpr int ATT_SPLIT = att_split(DH), PR = ATT_SPLIT / 1024;
+  static_assert(ATT_SPLIT % 1024 == 0 && PR >= 1, "split length");
   const int n_splits = (ctx + ATT_SPLIT - 1) / ATT_SPLIT;
   if (split >= n_splits) return;
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), hh = lane & 15, g = lane >> 4;
@@ -85,7 +93,9 @@ __global__ __launch_bounds__(64 * att_waves(DH, FUSED)) __attribute__((amdgpu_wa
   // page ids of this split: lane i holds page i (one vector load instead of a scalar
   // load per tile inside the loop)
   const int* bt = s.block_table + (size_t)slot * s.max_blocks + (t_begin >> 4);
-  const int my_page = bt[lane < n_pages ? lane : n_pages - 1];
+  int my_page[PR];
+#pragma unroll
+  for (int q = 0; q < PR; ++q) { const int i = q * 64 + lane; my_page[q] = bt[i < n_pages ? i : n_pages - 1]; }
 
   // A wavefront takes tiles wave, wave + ATT_WAVES, ... of the split.  Every load inside load_tile
   // is unconditional (a missing second page is clamped), so the wait counts around it are static.
@@ -94,7 +104,11 @@ __global__ __launch_bounds__(64 * att_waves(DH, FUSED)) __attribute__((amdgpu_wa
     for (int p = 0; p < 2; ++p) {
       int pl = 2 * tile + p;                                   // page within the split
       pl = pl < n_pages ? pl : n_pages - 1;                    // a missing second page re-reads the last one
-      const int page = __builtin_amdgcn_readlane(my_page, __builtin_amdgcn_readfirstlane(pl));
+      const int pls = __builtin_amdgcn_readfirstlane(pl);
+      int page = __builtin_amdgcn_readlane(my_page[0], pls & 63);
+#pragma unroll
+      for (int q = 1; q < PR; ++q)
+        if ((pls >> 6) == q) page = __builtin_amdgcn_readlane(my_page[q], pls & 63);
       const size_t off = ((size_t)page * Hkv + kvh) * blk_elems;
       const bf16x8* kp = reinterpret_cast<const bf16x8*>(kbase + off);
       const bf16x4* vp = reinterpret_cast<const bf16x4*>(vbase + off);
@@ -420,6 +434,7 @@ __global__ __launch_bounds__(64) void attn_merge_kernel(RowCtx rc, int row_base,
   const int wr = blockIdx.x, r = row_base + wr, kvh = blockIdx.y;
   const int pos = rc.row_pos[r];
   ROW_GUARD(rc, r);
+  constexpr int ATT_SPLIT = att_split(DH);
   const int n_splits = (pos + ATT_SPLIT) / ATT_SPLIT;          // ceil((pos + 1) / ATT_SPLIT)
   if (n_splits == 1) return;
   const int lane = threadIdx.x, hh = lane & 15, g = lane >> 4;
@@ -471,7 +486,7 @@ __global__ __launch_bounds__(64) void attn_merge_kernel(RowCtx rc, int row_base,
   }
 }
 
-int attn_split_tokens() { return ATT_SPLIT; }
+int attn_split_tokens(int head_dim) { return att_split(head_dim); }
 
 void launch_attn_decode(hipStream_t st, RowCtx rc, int row_base, Slots s, const float* q_rot, bf16_t* kv_pool,
                         KVLayout kvl, int layer, int n_q_heads, bf16_t* out, float* ws,

@@ -117,7 +117,7 @@ def main():
     p.add_argument("--max-new", type=int, default=0, help="cap the generated length (debug only; invalidates the number)")
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--no-wait-all", action="store_true")
-    p.add_argument("--profile-every", type=int, default=64,
+    p.add_argument("--profile-every", type=int, default=128,
                    help="every n-th decode iteration runs eagerly with an event pair around each launch (0 = never)")
     p.add_argument("--verbose", action="store_true", help="progress lines on stderr")
     p.add_argument("--kv-pool-gib", type=float, default=0.0, help="KV pool size (0 = the library's default)")

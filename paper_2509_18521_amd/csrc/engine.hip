@@ -142,6 +142,9 @@ struct april_ctx {
   // the launch geometry (row bound, attention split bound)
   bool use_graph = true;
   std::map<std::pair<int, int>, hipGraphExec_t> iter_graphs;
+  std::vector<int> it_rows, it_gs, it_ctx;   // per-iteration bounds of the batch being enqueued
+  int graph_iters = 4;                       // iterations per replayed graph when consecutive ones share their bounds
+                                             // (a graph boundary costs about 4 us on the device: 45.6 -> 45.7 k tokens/s)
 
   // pending resume
   std::vector<Entry> pending;
@@ -504,6 +507,7 @@ int april_init(const april_model_cfg* cfg, const april_tensor* weights, int32_t 
   c->fuse_down = fd && !strcmp(fd, "1");
   if (const char* td = getenv("APRIL_TILE_DECODE_ROWS")) c->tile_decode_rows = atoi(td);   // debug switch
   if (const char* mt = getenv("APRIL_MOE_TALL_ROWS")) c->moe_tall_rows = atoi(mt);          // debug switch
+  if (const char* gi = getenv("APRIL_GRAPH_ITERS")) c->graph_iters = std::max(1, std::min(16, atoi(gi)));
   const char* tg = getenv("APRIL_TILE_GEMM");
   c->tile_gemm = !(tg && !strcmp(tg, "0"));
   const char* gr = getenv("APRIL_GRAPH");
@@ -1240,8 +1244,9 @@ int april_rollout_step(april_ctx* c, const april_request* new_reqs, int32_t n_ne
       *ctx_cap = std::min(c->max_ctx, ctx_prefix_max[n_alive] + it);
     };
     // one captured graph per (row bound, KV-split bound), replayed by every iteration that fits it
-    auto graph_for = [&](int rows_cap, int gs, int ctx_grid, hipGraphExec_t* out) -> int {
-      const std::pair<int, int> key{rows_cap, gs};
+    // n_iters iterations (each: scheduler + forward + sampler) in one graph
+    auto graph_for = [&](int rows_cap, int gs, int ctx_grid, int n_iters, hipGraphExec_t* out) -> int {
+      const std::pair<int, int> key{rows_cap | (n_iters << 24), gs};
       auto it = c->iter_graphs.find(key);
       if (it == c->iter_graphs.end()) {
         hipGraph_t graph = nullptr;
@@ -1249,8 +1254,10 @@ int april_rollout_step(april_ctx* c, const april_request* new_reqs, int32_t n_ne
         RowCtx grc{c->d_row_slot, c->d_row_pos, reinterpret_cast<const int2*>(c->d_ctrl), rows_cap};
         c->step_max_ctx = ctx_grid;
         HIPCHK(c, hipStreamBeginCapture(st, hipStreamCaptureModeThreadLocal));
-        launch_sched(st, c->d_ctrl, c->ds, c->d_row_slot, c->d_row_pos, c->d_free_stack, blk, 0, rows_cap, ctx_grid);
-        forward(c, grc, grc, nullptr, 0, 0);
+        for (int q = 0; q < n_iters; ++q) {
+          launch_sched(st, c->d_ctrl, c->ds, c->d_row_slot, c->d_row_pos, c->d_free_stack, blk, 0, rows_cap, ctx_grid);
+          forward(c, grc, grc, nullptr, 0, 0);
+        }
         HIPCHK(c, hipStreamEndCapture(st, &graph));
         hipGraphExec_t exec = nullptr;
         HIPCHK(c, hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0));
@@ -1266,17 +1273,29 @@ int april_rollout_step(april_ctx* c, const april_request* new_reqs, int32_t n_ne
     while (!stopped) {
       int todo = exact ? T_bound - launched : std::min(chunk, T_bound - launched);
       if (todo < 0) todo = 0;
+      // bounds of every iteration of this batch (bounds_at wants increasing iterations)
+      c->it_rows.resize(todo); c->it_gs.resize(todo); c->it_ctx.resize(todo);
+      for (int k = 0; k < todo; ++k) {
+        int rows_cap = 0, ctx_cap = 0;
+        bounds_at(launched + k + 1, &rows_cap, &ctx_cap);
+        const int gs = c->attn_mfma ? std::min(c->attn_max_splits, std::max(1, ceil_div(ctx_cap, c->attn_chunk))) : 1;
+        c->it_rows[k] = rows_cap; c->it_gs[k] = gs; c->it_ctx[k] = c->attn_mfma ? gs * c->attn_chunk : c->max_ctx;
+      }
+      auto profiled = [&](int it) { return c->prof_every > 0 && (it % c->prof_every) == 0; };
       for (int k = 0; k < todo; ++k) {
         const int it = launched + k + 1;
-        int rows_cap = 0, ctx_cap = 0;
-        bounds_at(it, &rows_cap, &ctx_cap);
-        const int gs = c->attn_mfma ? std::min(c->attn_max_splits, std::max(1, ceil_div(ctx_cap, c->attn_chunk))) : 1;
-        const int ctx_grid = c->attn_mfma ? gs * c->attn_chunk : c->max_ctx;
-        c->prof_now = c->prof_every > 0 && (it % c->prof_every) == 0 && c->snaps_used < c->snaps_cap;
+        const int rows_cap = c->it_rows[k], gs = c->it_gs[k], ctx_grid = c->it_ctx[k];
+        c->prof_now = profiled(it) && c->snaps_used < c->snaps_cap;
         if (c->use_graph && !c->prof_now) {
+          // runs of iterations with the same bounds replay one graph of GRAPH_ITERS iterations
+          int run = 1;
+          while (run < c->graph_iters && k + run < todo && c->it_rows[k + run] == rows_cap && c->it_gs[k + run] == gs &&
+                 !profiled(it + run)) ++run;
+          const int n_it = run == c->graph_iters ? run : 1;
           hipGraphExec_t exec = nullptr;
-          { int rc = graph_for(rows_cap, gs, ctx_grid, &exec); if (rc != APRIL_OK) return rc; }
+          { int rc = graph_for(rows_cap, gs, ctx_grid, n_it, &exec); if (rc != APRIL_OK) return rc; }
           HIPCHK(c, hipGraphLaunch(exec, st));
+          k += n_it - 1;
           continue;
         }
         drc.max_rows = rows_cap;

@@ -459,6 +459,33 @@ extern "C" {
 
 const char* april_last_error(const april_ctx* ctx) { return ctx ? ctx->err.c_str() : g_init_error.c_str(); }
 
+// The graph of n_iters decode iterations (each: scheduler + forward + sampler) sized for at most
+// rows_cap live rows and gs KV splits; instantiated on first use and kept for the context's life.
+static int iter_graph(april_ctx* c, int rows_cap, int gs, int n_iters, hipGraphExec_t* out) {
+  const std::pair<int, int> key{rows_cap | (n_iters << 24), gs};
+  auto it = c->iter_graphs.find(key);
+  if (it == c->iter_graphs.end()) {
+    hipStream_t st = c->stream;
+    const int ctx_grid = c->attn_mfma ? gs * c->attn_chunk : c->max_ctx;
+    hipGraph_t graph = nullptr;
+    c->prof_now = false;
+    RowCtx grc{c->d_row_slot, c->d_row_pos, reinterpret_cast<const int2*>(c->d_ctrl), rows_cap};
+    c->step_max_ctx = ctx_grid;
+    HIPCHK(c, hipStreamBeginCapture(st, hipStreamCaptureModeThreadLocal));
+    for (int q = 0; q < n_iters; ++q) {
+      launch_sched(st, c->d_ctrl, c->ds, c->d_row_slot, c->d_row_pos, c->d_free_stack, 16, 0, rows_cap, ctx_grid);
+      forward(c, grc, grc, nullptr, 0, 0);
+    }
+    HIPCHK(c, hipStreamEndCapture(st, &graph));
+    hipGraphExec_t exec = nullptr;
+    HIPCHK(c, hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0));
+    HIPCHK(c, hipGraphDestroy(graph));
+    it = c->iter_graphs.emplace(key, exec).first;
+  }
+  *out = it->second;
+  return APRIL_OK;
+}
+
 int april_init(const april_model_cfg* cfg, const april_tensor* weights, int32_t n_weights, april_ctx** out) {
   if (!cfg || !weights || !out) return fail(nullptr, APRIL_EINVAL, "null argument");
   *out = nullptr;
@@ -728,6 +755,22 @@ int april_init(const april_model_cfg* cfg, const april_tensor* weights, int32_t 
     TRY(dev_alloc(c, &c->dwatch.sampled, c->watch_rows_cap)); TRY(dev_alloc(c, &c->dwatch.filled, c->watch_rows_cap));
   }
   HIPTRY(hipStreamSynchronize(c->stream));
+  // Graphs of the decode iteration for every (row bound, KV splits) a step can meet, when they
+  // are few (small models, where an instantiation inside a step would show): otherwise on first use.
+  if (c->use_graph) {
+    std::vector<int> row_bounds;
+    for (int rb = 32; rb < c->n_slots; rb += 32) row_bounds.push_back(rb);
+    row_bounds.push_back(c->n_slots);
+    const int n_gs = c->attn_mfma ? c->attn_max_splits : 1;
+    if ((int)row_bounds.size() * n_gs * (c->graph_iters > 1 ? 2 : 1) <= 48) {
+      for (int rb : row_bounds)
+        for (int gs = 1; gs <= n_gs; ++gs) {
+          hipGraphExec_t exec = nullptr;
+          if (iter_graph(c, rb, gs, 1, &exec) != APRIL_OK) return bail(APRIL_EDEVICE);
+          if (c->graph_iters > 1 && iter_graph(c, rb, gs, c->graph_iters, &exec) != APRIL_OK) return bail(APRIL_EDEVICE);
+        }
+    }
+  }
   *out = c;
   return APRIL_OK;
 #undef TRY
@@ -1244,29 +1287,6 @@ int april_rollout_step(april_ctx* c, const april_request* new_reqs, int32_t n_ne
       *ctx_cap = std::min(c->max_ctx, ctx_prefix_max[n_alive] + it);
     };
     // one captured graph per (row bound, KV-split bound), replayed by every iteration that fits it
-    // n_iters iterations (each: scheduler + forward + sampler) in one graph
-    auto graph_for = [&](int rows_cap, int gs, int ctx_grid, int n_iters, hipGraphExec_t* out) -> int {
-      const std::pair<int, int> key{rows_cap | (n_iters << 24), gs};
-      auto it = c->iter_graphs.find(key);
-      if (it == c->iter_graphs.end()) {
-        hipGraph_t graph = nullptr;
-        c->prof_now = false;
-        RowCtx grc{c->d_row_slot, c->d_row_pos, reinterpret_cast<const int2*>(c->d_ctrl), rows_cap};
-        c->step_max_ctx = ctx_grid;
-        HIPCHK(c, hipStreamBeginCapture(st, hipStreamCaptureModeThreadLocal));
-        for (int q = 0; q < n_iters; ++q) {
-          launch_sched(st, c->d_ctrl, c->ds, c->d_row_slot, c->d_row_pos, c->d_free_stack, blk, 0, rows_cap, ctx_grid);
-          forward(c, grc, grc, nullptr, 0, 0);
-        }
-        HIPCHK(c, hipStreamEndCapture(st, &graph));
-        hipGraphExec_t exec = nullptr;
-        HIPCHK(c, hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0));
-        HIPCHK(c, hipGraphDestroy(graph));
-        it = c->iter_graphs.emplace(key, exec).first;
-      }
-      *out = it->second;
-      return APRIL_OK;
-    };
     bool stopped = false;
     int launched = 1;
     const int chunk = 32;
@@ -1293,7 +1313,7 @@ int april_rollout_step(april_ctx* c, const april_request* new_reqs, int32_t n_ne
                  !profiled(it + run)) ++run;
           const int n_it = run == c->graph_iters ? run : 1;
           hipGraphExec_t exec = nullptr;
-          { int rc = graph_for(rows_cap, gs, ctx_grid, n_it, &exec); if (rc != APRIL_OK) return rc; }
+          { int rc = iter_graph(c, rows_cap, gs, n_it, &exec); if (rc != APRIL_OK) return rc; }
           HIPCHK(c, hipGraphLaunch(exec, st));
           k += n_it - 1;
           continue;

@@ -2,19 +2,19 @@
 import os
 import subprocess
 import sys
+from concurrent.futures import ThreadPoolExecutor
 
 PKG = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libapril.so")
+OBJ_DIR = os.path.join(PKG, "_build")
 SOURCES = ["engine.hip", "kernels_basic.hip", "kernels_gemm.hip", "kernels_gemm_tile.hip", "kernels_attn.hip", "kernels_moe.hip", "kernels_sample.hip"]
-FLAGS = ["-O3", "--offload-arch=gfx950", "-fPIC", "-shared", "-std=c++17",
+FLAGS = ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wno-unused-command-line-argument", "-Wno-unused-value", "-Wno-unused-result"]
 
 
-def build(verbose=True):
-    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc] + FLAGS + [os.path.join(CSRC, s) for s in SOURCES] + ["-o", LIB]
+def _run(cmd, verbose):
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
@@ -23,9 +23,20 @@ def build(verbose=True):
         raise RuntimeError("hipcc failed:\n" + out)
     if verbose and out.strip():
         print(out)
+
+
+def build(verbose=True, only=None):
+    """Compiles every source (or the ones named in `only`; the other objects must exist) and links."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    os.makedirs(OBJ_DIR, exist_ok=True)
+    objs = {s: os.path.join(OBJ_DIR, s.replace(".hip", ".o")) for s in SOURCES}
+    todo = [s for s in SOURCES if only is None or s in only or not os.path.exists(objs[s])]
+    with ThreadPoolExecutor(max_workers=min(8, len(todo) or 1)) as ex:
+        list(ex.map(lambda s: _run([hipcc] + FLAGS + ["-c", os.path.join(CSRC, s), "-o", objs[s]], verbose), todo))
+    _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC"] + [objs[s] for s in SOURCES] + ["-o", LIB], verbose)
     return LIB
 
 
 if __name__ == "__main__":
-    build()
+    build(only=sys.argv[1:] or None)
     print("built", LIB)

@@ -15,8 +15,8 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 // Sequence slot states.
 enum : int { SLOT_FREE = 0, SLOT_LIVE = 1, SLOT_DONE = 2, SLOT_PARKED = 3, SLOT_PREFILL = 4, SLOT_PREEMPTED = 5 };
 
-// Device-resident control block of the early-termination scheduler (Section 2.2:
-// "stop generation once N rollouts are completed" is decided here, on device).
+// Device-resident control block of the early-termination scheduler (Section 2.2, second
+// item of the method: the step ends as soon as N rollouts are complete; decided here, on device).
 struct Ctrl {
   int n_rows;       // live rollouts of the current decode iteration   } read together by every
   int stop;         // 1: the step is over, every later kernel is a no-op } kernel as one int2

@@ -100,7 +100,7 @@ struct april_ctx {
   int *d_row_slot = nullptr, *d_row_pos = nullptr;
   std::vector<SlotH> slots;
   Watch dwatch{};
-  int watch_rows_cap = 0, watch_rows_used = 0, n_watch = 0, watch_cap = 512;
+  int watch_rows_cap = 0, watch_rows_used = 0, n_watch = 0, watch_cap = 2048;
   std::map<std::pair<long long, int>, int> watch_row_of;
 
   // prefill staging (device) + pinned host staging
@@ -143,6 +143,8 @@ struct april_ctx {
   bool use_graph = true;
   std::map<std::pair<int, int>, hipGraphExec_t> iter_graphs;
   std::vector<int> it_rows, it_gs, it_ctx;   // per-iteration bounds of the batch being enqueued
+  int debug_fail_step = -1, debug_fail_iter = -1;   // APRIL_DEBUG_FAIL_AT=step:iteration, see april_rollout_step (one shot)
+  int steps_started = 0;
   int graph_iters = 4;                       // iterations per replayed graph when consecutive ones share their bounds
                                              // (a graph boundary costs about 4 us on the device: 45.6 -> 45.7 k tokens/s)
 
@@ -534,6 +536,9 @@ int april_init(const april_model_cfg* cfg, const april_tensor* weights, int32_t 
   c->fuse_down = fd && !strcmp(fd, "1");
   if (const char* td = getenv("APRIL_TILE_DECODE_ROWS")) c->tile_decode_rows = atoi(td);   // debug switch
   if (const char* mt = getenv("APRIL_MOE_TALL_ROWS")) c->moe_tall_rows = atoi(mt);          // debug switch
+  if (const char* fa = getenv("APRIL_DEBUG_FAIL_AT")) {                                       // debug switch
+    if (sscanf(fa, "%d:%d", &c->debug_fail_step, &c->debug_fail_iter) != 2) c->debug_fail_step = c->debug_fail_iter = -1;
+  }
   if (const char* gi = getenv("APRIL_GRAPH_ITERS")) c->graph_iters = std::max(1, std::min(16, atoi(gi)));
   const char* tg = getenv("APRIL_TILE_GEMM");
   c->tile_gemm = !(tg && !strcmp(tg, "0"));
@@ -748,7 +753,7 @@ int april_init(const april_model_cfg* cfg, const april_tensor* weights, int32_t 
 
   // ---- parity-mode capture ----------------------------------------------------------
   if (g.debug_logits) {
-    c->watch_rows_cap = (int)std::max<int64_t>(16, std::min<int64_t>(4096, ((int64_t)512 << 20) / ((int64_t)V * 4)));
+    c->watch_rows_cap = (int)std::max<int64_t>(16, std::min<int64_t>(8192, ((int64_t)512 << 20) / ((int64_t)V * 4)));
     TRY(dev_alloc(c, &c->dwatch.req, c->watch_cap)); TRY(dev_alloc(c, &c->dwatch.first, c->watch_cap));
     TRY(dev_alloc(c, &c->dwatch.count, c->watch_cap)); TRY(dev_alloc(c, &c->dwatch.row0, c->watch_cap));
     TRY(dev_alloc(c, &c->dwatch.logits, (size_t)c->watch_rows_cap * V));
@@ -882,7 +887,8 @@ int april_buffer_import(april_ctx* c, const april_partial* in, int32_t n, april_
     if (in[i].n_prompt + in[i].limit > c->max_ctx)
       return fail(c, APRIL_EINVAL, "april_buffer_import: entry %d exceeds max_ctx", i);
     const bool done = in[i].n_generated >= in[i].limit;
-    if ((in[i].done != 0) != done && in[i].done)
+    // below its limit a rollout can only be complete through the EOS token
+    if (in[i].done && !done && (c->cfg.eos_token < 0 || in[i].n_generated == 0))
       return fail(c, APRIL_EINVAL, "april_buffer_import: entry %d flagged done below its limit", i);
   }
   april_buffer* b = new_buffer(c);
@@ -1124,14 +1130,16 @@ int april_rollout_step(april_ctx* c, const april_request* new_reqs, int32_t n_ne
     pool_ample = need <= c->free_pages_host;
   }
 
-  // ---- commit admission ---------------------------------------------------------------
-  struct Fl { int slot; };
-  std::vector<int> inflight;            // slots in flight this step
+  // ---- commit admission (host bookkeeping only: nothing here can fail) -------------------
+  std::vector<int> inflight;            // slots in flight this step: resumed ones first, then new ones
   std::vector<int> prefill_slots;       // need (re-)prefill
   std::vector<Entry> deliver;           // surplus-complete from the last step, ascending id
   int64_t prefill_tokens = 0, reprefill_tokens = 0;
   int n_resident = 0;
   std::vector<Entry> stay;              // buffered rollouts that could not be admitted (KV pool)
+  struct Upload { int slot; std::vector<int> tokens; std::vector<int> forced; bool has_forced; };
+  std::vector<Upload> uploads;          // token arrays the device still needs
+  std::vector<std::pair<int, Entry>> token_level;   // (slot, entry as resumed) of entries that came without a slot
   for (int i : stay_idx) stay.push_back(pend[i]);
   for (int i : deliver_idx) deliver.push_back(pend[i]);
   for (int i : resume_idx) {
@@ -1146,8 +1154,9 @@ int april_rollout_step(april_ctx* c, const april_request* new_reqs, int32_t n_ne
       sh.state = SLOT_PARKED;
       std::vector<int> all(e.prompt);
       all.insert(all.end(), e.generated.begin(), e.generated.end());
-      HIPCHK(c, hipMemcpyAsync(c->ds.tokens + (size_t)s * c->max_ctx, all.data(), all.size() * sizeof(int), hipMemcpyHostToDevice, st));
-      HIPCHK(c, hipStreamSynchronize(st));
+      // parity mode: the slot's previous occupant may have left teacher-forced tokens behind
+      uploads.push_back({s, std::move(all), std::vector<int>(), c->ds.forced != nullptr});
+      token_level.push_back({s, e});
     }
     SlotH& sh = c->slots[s];
     sh.n_resumes += 1;
@@ -1155,6 +1164,7 @@ int april_rollout_step(april_ctx* c, const april_request* new_reqs, int32_t n_ne
     else { sh.state = SLOT_PREFILL; prefill_slots.push_back(s); reprefill_tokens += sh.prompt_len + sh.gen; }
     inflight.push_back(s);
   }
+  const int n_resumed_inflight = (int)inflight.size();
   for (int i = 0; i < n_admit; ++i) {
     const april_request& r = new_reqs[i];
     const int s = alloc_slot(c);
@@ -1163,20 +1173,34 @@ int april_rollout_step(april_ctx* c, const april_request* new_reqs, int32_t n_ne
     sh.req = r.request_id; sh.prompt.assign(r.tokens, r.tokens + r.n_tokens); sh.prompt_len = r.n_tokens;
     sh.limit = r.forced_len > 0 ? std::min(r.forced_len, max_new) : max_new;
     sh.state = SLOT_PREFILL;
-    HIPCHK(c, hipMemcpyAsync(c->ds.tokens + (size_t)s * c->max_ctx, r.tokens, (size_t)r.n_tokens * sizeof(int), hipMemcpyHostToDevice, st));
-    if (c->ds.forced) {
-      std::vector<int> f(c->max_ctx, -1);
-      if (r.forced_tokens) for (int k = 0; k < r.n_forced_tokens && k < c->max_ctx; ++k) f[k] = r.forced_tokens[k];
-      HIPCHK(c, hipMemcpyAsync(c->ds.forced + (size_t)s * c->max_ctx, f.data(), (size_t)c->max_ctx * sizeof(int), hipMemcpyHostToDevice, st));
-      HIPCHK(c, hipStreamSynchronize(st));
-    }
+    Upload u{s, sh.prompt, std::vector<int>(), c->ds.forced != nullptr};
+    if (c->ds.forced && r.forced_tokens) u.forced.assign(r.forced_tokens, r.forced_tokens + std::min(r.n_forced_tokens, c->max_ctx));
+    uploads.push_back(std::move(u));
     prefill_slots.push_back(s);
     prefill_tokens += r.n_tokens;
     inflight.push_back(s);
   }
-  HIPCHK(c, hipStreamSynchronize(st));
   pend.clear();
   c->have_pending = false;
+  c->steps_started += 1;
+
+  // From here on the step is transactional: `body` runs it; if it fails, `rollback` below hands
+  // every resumed rollout back to the pending set (tokens generated so far kept, KV dropped) and
+  // forgets the newly admitted requests, which the caller still owns (a failed call consumes
+  // none of new_reqs).  Nothing a previous step left in the buffer is lost (Section 2.2: no
+  // rollout is discarded).
+  bool device_touched = false;          // the step has started to change per-slot device state
+  april_buffer* nb = nullptr;
+  auto body = [&]() -> int {
+  for (Upload& u : uploads) {
+    HIPCHK(c, hipMemcpyAsync(c->ds.tokens + (size_t)u.slot * c->max_ctx, u.tokens.data(), u.tokens.size() * sizeof(int), hipMemcpyHostToDevice, st));
+    if (u.has_forced) {
+      launch_fill_i32(st, c->ds.forced + (size_t)u.slot * c->max_ctx, -1, (size_t)c->max_ctx);
+      if (!u.forced.empty())
+        HIPCHK(c, hipMemcpyAsync(c->ds.forced + (size_t)u.slot * c->max_ctx, u.forced.data(), u.forced.size() * sizeof(int), hipMemcpyHostToDevice, st));
+    }
+  }
+  HIPCHK(c, hipStreamSynchronize(st));   // the upload sources are pageable host vectors
 
   // ---- run ------------------------------------------------------------------------------
   double t_prefill = 0, t_decode = 0;
@@ -1184,6 +1208,7 @@ int april_rollout_step(april_ctx* c, const april_request* new_reqs, int32_t n_ne
   long long iters = 0, sum_live = 0, sum_ctx = 0, it1_live = 0, it1_ctx = 0, sum_experts = 0, it1_experts = 0;
   std::vector<int> snap(7 * c->n_slots);
   if (D < N_target) {
+    device_touched = true;
     { int rc = upload_slot_tables(c); if (rc != APRIL_OK) return rc; }
     Ctrl& hc = *c->h_ctrl;
     hc.n_rows = 0; hc.finished = D; hc.n_target = N_target; hc.stop = 0; hc.iter = 0; hc.stop_iter = -1;
@@ -1218,7 +1243,10 @@ int april_rollout_step(april_ctx* c, const april_request* new_reqs, int32_t n_ne
       HIPCHK(c, hipMemcpyAsync(c->d_list_a, h_list, prefill_slots.size() * sizeof(int), hipMemcpyHostToDevice, st));
       HIPCHK(c, hipMemcpyAsync(c->d_list_b, h_need, prefill_slots.size() * sizeof(int), hipMemcpyHostToDevice, st));
       launch_alloc_prefill(st, c->d_ctrl, c->ds, c->d_list_a, c->d_list_b, (int)prefill_slots.size(), c->d_free_stack);
+      // the prefill must not run on block tables that were not filled: look at the error flag now
+      HIPCHK(c, hipMemcpyAsync(c->h_ctrl, c->d_ctrl, sizeof(Ctrl), hipMemcpyDeviceToHost, st));
       HIPCHK(c, hipStreamSynchronize(st));
+      if (c->h_ctrl->error) return fail(c, APRIL_ENOMEM, "KV page stack underflow on device (prefill pages)");
     }
     // iteration 1: resident rollouts decode, the others are (re-)prefilled
     const int NOCAP = 0x7fffffff;
@@ -1306,11 +1334,14 @@ int april_rollout_step(april_ctx* c, const april_request* new_reqs, int32_t n_ne
         const int it = launched + k + 1;
         const int rows_cap = c->it_rows[k], gs = c->it_gs[k], ctx_grid = c->it_ctx[k];
         c->prof_now = profiled(it) && c->snaps_used < c->snaps_cap;
-        if (c->use_graph && !c->prof_now) {
+        // debug switch (tests of the failure path): this iteration's scheduler pass is told a row
+        // bound of zero, so the device raises its bounds error and ends the step
+        const bool fail_here = c->steps_started == c->debug_fail_step && it == c->debug_fail_iter;
+        if (c->use_graph && !c->prof_now && !fail_here) {
           // runs of iterations with the same bounds replay one graph of GRAPH_ITERS iterations
           int run = 1;
           while (run < c->graph_iters && k + run < todo && c->it_rows[k + run] == rows_cap && c->it_gs[k + run] == gs &&
-                 !profiled(it + run)) ++run;
+                 !profiled(it + run) && !(c->steps_started == c->debug_fail_step && it + run == c->debug_fail_iter)) ++run;
           const int n_it = run == c->graph_iters ? run : 1;
           hipGraphExec_t exec = nullptr;
           { int rc = iter_graph(c, rows_cap, gs, n_it, &exec); if (rc != APRIL_OK) return rc; }
@@ -1322,7 +1353,9 @@ int april_rollout_step(april_ctx* c, const april_request* new_reqs, int32_t n_ne
         c->step_max_ctx = ctx_grid;
         {
           ProfScope p(c, KC_SCHED, 0, 0);
-          launch_sched(st, c->d_ctrl, c->ds, c->d_row_slot, c->d_row_pos, c->d_free_stack, blk, 0, rows_cap, ctx_grid);
+          launch_sched(st, c->d_ctrl, c->ds, c->d_row_slot, c->d_row_pos, c->d_free_stack, blk, 0,
+                       fail_here ? 0 : rows_cap, ctx_grid);
+          if (fail_here) c->debug_fail_step = -1;      // one shot
         }
         double B = 0, C = 0;
         if (c->prof_now) {
@@ -1390,7 +1423,7 @@ int april_rollout_step(april_ctx* c, const april_request* new_reqs, int32_t n_ne
 
   // delivery order: surplus of the last step (ascending id), then this step's finishers
   c->r_req.clear(); c->r_tokens.clear(); c->r_ntok.clear(); c->r_nres.clear(); c->r_tok_ptrs.clear();
-  april_buffer* nb = new_buffer(c);
+  nb = new_buffer(c);
   std::vector<int> release;             // slots whose rollout is returned now
   int delivered = 0;
   auto deliver_slot = [&](int s) -> int {
@@ -1464,6 +1497,66 @@ int april_rollout_step(april_ctx* c, const april_request* new_reqs, int32_t n_ne
   out->t_decode_s = t_decode;
   out->t_total_s = now_s() - t_begin;
   return APRIL_OK;
+  };   // body
+
+  const int rc = body();
+  if (rc == APRIL_OK) return rc;
+
+  // ---- rollback of a failed step ----------------------------------------------------------
+  const std::string first_error = c->err;
+  c->prof_now = false;
+  c->prof_recs.clear(); c->ev_used = 0; c->snaps_used = 0;
+  {
+    hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(st, &cs) == hipSuccess && cs != hipStreamCaptureStatusNone) {
+      hipGraph_t g = nullptr;
+      hipStreamEndCapture(st, &g);
+      if (g) hipGraphDestroy(g);
+    }
+  }
+  if (nb) { retire_buffer(c, nb); nb = nullptr; }
+  c->r_req.clear(); c->r_tokens.clear(); c->r_ntok.clear(); c->r_nres.clear(); c->r_tok_ptrs.clear();
+  const int S = c->n_slots;
+  bool dev_ok = hipStreamSynchronize(st) == hipSuccess;
+  std::vector<int> dgen(S), dstate(S), dnb(S);
+  if (device_touched) {
+    dev_ok = dev_ok && hipMemcpy(dgen.data(), c->ds.gen, S * sizeof(int), hipMemcpyDeviceToHost) == hipSuccess &&
+             hipMemcpy(dstate.data(), c->ds.state, S * sizeof(int), hipMemcpyDeviceToHost) == hipSuccess &&
+             hipMemcpy(dnb.data(), c->ds.n_blocks, S * sizeof(int), hipMemcpyDeviceToHost) == hipSuccess &&
+             hipMemcpy(c->h_ctrl, c->d_ctrl, sizeof(Ctrl), hipMemcpyDeviceToHost) == hipSuccess;
+    if (dev_ok) {
+      // the device's view is the current one: progress made before the failure is kept, the KV
+      // of every rollout that was in flight is released (after an error it is not trusted)
+      c->free_pages_host = c->h_ctrl->free_top;
+      for (int s : inflight) c->slots[s].n_blocks = dnb[s];
+      dev_ok = free_slot_pages(c, inflight) == APRIL_OK;
+    }
+    // (if the device is gone the host mirrors are at least kept consistent)
+    for (int s : inflight) { c->slots[s].n_blocks = 0; c->slots[s].kv_len = 0; }
+  }
+  for (Entry& e : deliver) c->pending.push_back(std::move(e));
+  for (Entry& e : stay) c->pending.push_back(std::move(e));
+  for (int k = 0; k < (int)inflight.size(); ++k) {
+    const int s = inflight[k];
+    SlotH& sh = c->slots[s];
+    if (k >= n_resumed_inflight) { sh = SlotH(); continue; }        // a new request: not consumed, the caller still has it
+    const bool have_dev = device_touched && dev_ok;
+    if (!have_dev) {
+      // nothing ran on the device for this step: entries that came as tokens go back as tokens
+      auto tl = std::find_if(token_level.begin(), token_level.end(), [&](const std::pair<int, Entry>& x) { return x.first == s; });
+      if (tl != token_level.end()) { c->pending.push_back(tl->second); sh = SlotH(); continue; }
+    }
+    Entry e;
+    e.req = sh.req; e.slot = s; e.limit = sh.limit;
+    if (have_dev) { sh.gen = dgen[s]; e.done = dstate[s] == SLOT_DONE ? 1 : 0; }
+    sh.n_resumes -= 1;
+    e.n_resumes = sh.n_resumes;
+    sh.state = e.done ? SLOT_DONE : SLOT_PARKED;
+    c->pending.push_back(std::move(e));
+  }
+  c->have_pending = !c->pending.empty();
+  c->err = first_error;
+  return rc;
 }
 
 }  // extern "C"

@@ -28,8 +28,8 @@ template <typename T> __device__ inline T from_f32(float v) { return (T)v; }
 // Scheduler: early termination, live-batch compaction, KV page allocation.
 // One workgroup.  Runs at the start of every decode iteration:
 //   - if the step already stopped: nothing;
-//   - if finished >= N: raise stop, remember the iteration count (Section 2.2,
-//     "stop generation once N rollouts are completed");
+//   - if finished >= N: raise stop, remember the iteration count (early termination,
+//     Section 2.2, second item of the method);
 //   - else rebuild the dense list of live rollouts (slot order) and give a fresh
 //     KV page to every live rollout whose next position opens a new page.  If the
 //     free pages do not cover that demand, the youngest live rollout (largest request

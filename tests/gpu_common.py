@@ -95,3 +95,44 @@ def assert_schedule_equal(got, want):
 def top2_margin(logits):
     p = np.partition(np.asarray(logits, dtype=np.float64), -2)
     return float(p[-1] - p[-2])
+
+
+# ---------------------------------------------------------------------------
+# Teacher forcing with tokens of the test's own choosing.  The schedule does not depend on
+# the token values, and logits parity holds for any fed sequence, so wide models with
+# hundreds of rollouts in flight can be compared without the oracle generating token by
+# token: request r uses prompt r mod P and is forced the tokens of "class" r mod P, so the
+# oracle needs one block forward per class (row P_len - 1 + i predicts generated token i).
+# ---------------------------------------------------------------------------
+def class_forced_tokens(w, n_classes, seed_tag=303):
+    rng = np.random.default_rng([w.seed, seed_tag])
+    return rng.integers(0, w.shape.vocab, size=(n_classes, w.max_new), dtype=np.int32)
+
+
+def run_oracle_schedule(reqs, forced, n_target, n_over, max_new, steps):
+    """Scheduling half of the oracle alone (integers), fed the forced tokens."""
+    from oracle.scheduler import Rollout, rollout_step
+    rolls = [Rollout(request_id=r.request_id, prompt_len=len(r.tokens), forced_len=r.forced_len) for r in reqs]
+    buf, nxt, out = [], 0, []
+    for _ in range(steps):
+        o = rollout_step(buf, rolls[nxt:], n_target, n_over, max_new,
+                         next_token=lambda r: int(forced[r.request_id][r.gen]))
+        buf = o.buffer
+        nxt += o.n_new_consumed
+        out.append(dict(ids=[r.request_id for r in o.completed], tokens=[list(r.tokens) for r in o.completed],
+                        n_resumes=[r.n_resumes for r in o.completed], consumed=o.n_new_consumed,
+                        iters=o.decode_iters, generated=o.tokens_generated,
+                        buffer=[(r.request_id, r.gen, int(r.done)) for r in o.buffer],
+                        buffer_tokens={r.request_id: list(r.tokens) for r in o.buffer},
+                        sum_live=sum(o.live_per_iter)))
+    return out
+
+
+def class_reference_logits(dec, prompts, class_tokens, n_gen):
+    """Oracle logits of every class: ref[c][i] = logits that predict generated token i."""
+    ref = []
+    for c in range(len(prompts)):
+        feed = np.concatenate([prompts[c], class_tokens[c][:n_gen - 1]])
+        rows = dec.forward_block(feed, dec.new_cache())
+        ref.append(rows[len(prompts[c]) - 1:])
+    return ref

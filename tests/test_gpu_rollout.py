@@ -260,6 +260,57 @@ def test_error_paths():
         A.april_destroy(ctx)
 
 
+def test_failed_step_loses_no_rollout(monkeypatch):
+    """A step that fails after admission (here: the device-side bounds check of the scheduler,
+    forced from the host in the second step's sixth iteration - every kernel still exits normally)
+    must not lose a rollout: the ones that were resumed go back to the pending set with the tokens
+    they have (their KV is dropped), the new requests are not consumed, and repeating the call
+    goes on from there.  Every request is delivered exactly once, with the tokens an undisturbed
+    run gives it (fp32 path: re-prefilled and resident agree bit for bit)."""
+    w = small_fp32_workload()
+    weights = ai.make_weights(w.shape, w.seed)
+    reqs = ai.make_requests(w, ai.requests_needed(w))
+    A = ap()
+    ref_ctx = make_engine(w, weights)
+    try:
+        want = run_gpu(ref_ctx, reqs, w.n_target, w.n_overprovision, w.max_new, 4)
+    finally:
+        A.april_destroy(ref_ctx)
+    want_tokens = {rid: t for g in want for rid, t in zip(g["ids"], g["tokens"])}
+    monkeypatch.setenv("APRIL_DEBUG_FAIL_AT", "2:6")
+    ctx = make_engine(w, weights)
+    monkeypatch.delenv("APRIL_DEBUG_FAIL_AT")
+    try:
+        nxt, steps, failed, delivered, last_buffer = 0, 0, 0, {}, []
+        pages_total = A.april_get_info(ctx)["kv_blocks_total"]
+        while steps < 4:
+            try:
+                res = A.april_rollout_step(ctx, req_dicts(reqs[nxt:]), w.n_target, w.n_overprovision, w.max_new)
+            except A.AprilError as e:
+                assert e.code == A.APRIL_EDEVICE and failed == 0 and steps == 1
+                failed += 1
+                continue                       # the same call again: nothing new was consumed
+            steps += 1
+            nxt += res.n_new_consumed
+            for rid, t in zip(res.request_id, res.tokens):
+                assert rid not in delivered
+                delivered[rid] = t.tolist()
+            last_buffer = [p["request_id"] for p in A.april_buffer_export(ctx, res.buffer)]
+            if steps == 2:
+                assert res.reprefill_tokens > 0          # the resumed rollouts came back without KV
+            A.april_resume(ctx, res.buffer)
+        assert failed == 1
+        assert len(delivered) == 4 * w.n_target
+        # nobody lost: every admitted request is delivered or still buffered
+        assert sorted(list(delivered) + last_buffer) == list(range(nxt))
+        common = set(delivered) & set(want_tokens)
+        assert len(common) >= 3 * w.n_target
+        for rid in common:
+            assert delivered[rid] == want_tokens[rid], rid
+    finally:
+        A.april_destroy(ctx)
+
+
 def test_kv_pool_exhaustion_preempts_youngest_and_reprefills():
     """A KV pool far smaller than the worst case of the step: admission stops when prompt
     pages do not fit, the youngest decoding rollouts are preempted on the device, come back

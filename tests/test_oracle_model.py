@@ -206,6 +206,31 @@ def test_moe_single_expert_is_dense_and_full_topk_is_softmax_mixture():
     assert np.allclose(om.moe_mlp(h, R, G, U, D, 2), want2, atol=1e-13)
 
 
+def test_moe_equal_router_rows_keep_the_lower_expert_index():
+    """Tie rule of the routing: experts 1 and 3 have the same router row, so their
+    probabilities are equal bit for bit; with room for only one of them the lower index is
+    kept.  Closed form: the mixture over the kept experts with renormalised weights."""
+    rng = np.random.default_rng(12)
+    E, d, F = 4, 8, 6
+    h = rng.standard_normal(d)
+    R = rng.standard_normal((E, d))
+    R[3] = R[1]
+    # make the tied pair the second-largest probability: scale the others
+    logits = R @ h
+    R[0] = R[0] * 0 + h * (logits[1] + 2.0) / (h @ h)        # expert 0: strictly larger logit
+    R[2] = R[2] * 0 + h * (logits[1] - 2.0) / (h @ h)        # expert 2: strictly smaller
+    G, U, D = (rng.standard_normal(sh) for sh in ((E, F, d), (E, F, d), (E, d, F)))
+    r = np.exp(R @ h) / np.exp(R @ h).sum()
+    assert r[1] == r[3] and r[0] > r[1] > r[2]
+    want = sum(r[e] / (r[0] + r[1]) * om.swiglu(h, G[e], U[e], D[e]) for e in (0, 1))
+    assert np.allclose(om.moe_mlp(h, R, G, U, D, 2), want, atol=1e-13)
+    wrong = sum(r[e] / (r[0] + r[3]) * om.swiglu(h, G[e], U[e], D[e]) for e in (0, 3))
+    assert not np.allclose(wrong, want, atol=1e-6)
+    # with room for both, both are kept
+    want3 = sum(r[e] / (r[0] + r[1] + r[3]) * om.swiglu(h, G[e], U[e], D[e]) for e in (0, 1, 3))
+    assert np.allclose(om.moe_mlp(h, R, G, U, D, 3), want3, atol=1e-13)
+
+
 def test_silu_and_swiglu_values():
     assert om.silu(0.0) == 0.0
     assert math.isclose(om.silu(1.0), 1.0 / (1.0 + math.exp(-1.0)))

@@ -95,8 +95,9 @@ def class_parity(w, steps, min_rows, skip_positions=None):
                 rows += 1
                 assert sampled == osampler.greedy(lg)
         print(f"{w.name}: rows={rows} skipped={skipped} worst={worst:.4g} at {worst_at}")
-        assert rows >= min_rows, f"compared {rows} rows, skipped {skipped} of {rows + skipped}"
-        assert worst <= BF16_LOGIT_TOL, (worst, worst_at, f"skipped {skipped} of {rows + skipped}")
+        share = f"skipped {skipped} of {rows + skipped} positions ({skipped / max(rows + skipped, 1):.0%})"
+        assert rows >= min_rows, f"compared only {rows} rows; {share}"
+        assert worst <= BF16_LOGIT_TOL, f"worst {worst:.4g} at {worst_at}; {share}"
         return got
     finally:
         ap().april_destroy(ctx)

@@ -195,6 +195,17 @@ int april_debug_logits(april_ctx* ctx, int64_t request_id, int32_t gen_index,
 int april_sample_rows(april_ctx* ctx, const float* logits, int32_t n_rows,
                       const int64_t* request_ids, const int32_t* gen_index, int32_t* out_tokens);
 
+/* april_sample_rows for callers that cannot allocate device memory (code under HIP graph
+ * capture rules, tight serving loops, harnesses that forbid hipMalloc): same arguments, same
+ * result, but every temporary (row keys, result staging, control word, the per-row maxima of
+ * 64-logit groups) lives in a static device array of 4 MiB + 16.25 KiB that the library holds on
+ * every GPU it runs on until the process ends; the call makes no hipMalloc / hipFree.
+ * Limits: n_rows <= 1024 and n_rows * (vocab / 64) <= 1048576 (APRIL_EINVAL beyond).
+ * All calls on one GPU share that array and it keeps the last call's contents: calls that
+ * overlap on one GPU (other threads, other contexts) race; serialise them. */
+int april_sample_rows_noalloc(april_ctx* ctx, const float* logits, int32_t n_rows,
+                              const int64_t* request_ids, const int32_t* gen_index, int32_t* out_tokens);
+
 /* Per-kernel-class timing, measured with HIP events on the context's stream around
  * sampled launches of the real decode loop (every `every`-th iteration; 0 = off).  Two extra
  * classes calibrate the method: "event_pair_no_kernel" is what a pair of event records reads

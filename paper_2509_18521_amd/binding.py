@@ -23,7 +23,7 @@ APRIL_KERNEL_CLASSES = 24
 EXPORTS = [
     "april_init", "april_rollout_step", "april_resume", "april_buffer_size", "april_buffer_export",
     "april_buffer_import", "april_buffer_drop_kv", "april_buffer_free", "april_debug_watch",
-    "april_debug_logits", "april_sample_rows", "april_profile_enable", "april_profile_get",
+    "april_debug_logits", "april_sample_rows", "april_sample_rows_noalloc", "april_profile_enable", "april_profile_get",
     "april_profile_reset", "april_get_info", "april_last_error", "april_destroy",
 ]
 
@@ -112,6 +112,7 @@ def load_library():
     lib.april_debug_logits.argtypes = [vp, C.c_int64, C.c_int32, C.POINTER(C.c_float), C.POINTER(C.c_int32)]
     lib.april_sample_rows.argtypes = [vp, vp, C.c_int32, C.POINTER(C.c_int64), C.POINTER(C.c_int32),
                                       C.POINTER(C.c_int32)]
+    lib.april_sample_rows_noalloc.argtypes = lib.april_sample_rows.argtypes
     lib.april_profile_enable.argtypes = [vp, C.c_int32]
     lib.april_profile_get.argtypes = [vp, C.POINTER(april_kernel_stat), C.c_int32]
     lib.april_profile_reset.argtypes = [vp]
@@ -284,6 +285,16 @@ def april_sample_rows(ctx, logits_device_ptr: int, n_rows: int, request_ids, gen
     out = np.empty(n_rows, dtype=np.int32)
     _check(ctx, load_library().april_sample_rows(ctx, C.c_void_p(logits_device_ptr), n_rows,
                                                  rid.ctypes.data_as(C.POINTER(C.c_int64)), _i32ptr(gi), _i32ptr(out)))
+    return out
+
+
+def april_sample_rows_noalloc(ctx, logits_device_ptr: int, n_rows: int, request_ids, gen_index) -> np.ndarray:
+    rid = np.ascontiguousarray(request_ids, dtype=np.int64)
+    gi = np.ascontiguousarray(gen_index, dtype=np.int32)
+    out = np.empty(n_rows, dtype=np.int32)
+    _check(ctx, load_library().april_sample_rows_noalloc(ctx, C.c_void_p(logits_device_ptr), n_rows,
+                                                         rid.ctypes.data_as(C.POINTER(C.c_int64)), _i32ptr(gi),
+                                                         _i32ptr(out)))
     return out
 
 

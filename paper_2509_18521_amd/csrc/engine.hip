@@ -58,6 +58,19 @@ struct Entry {
 
 }  // namespace
 
+// Scratch of april_sample_rows_noalloc: staging of the row keys and of the result, the control
+// word, and the group maxima the sampler's candidate search needs.  One copy per GPU, held
+// until the process ends; host code only ever uses the device address looked up at april_init.
+constexpr size_t NOALLOC_MAX_ROWS = 1024;
+constexpr size_t NOALLOC_MAX_GROUP_MAX = (size_t)1 << 20;        // floats: n_rows * (vocab / 64) may not exceed this
+constexpr size_t NOALLOC_OFF_CTL = 0, NOALLOC_OFF_REQ = 256, NOALLOC_OFF_GEN = NOALLOC_OFF_REQ + 8 * NOALLOC_MAX_ROWS,
+                 NOALLOC_OFF_OUT = NOALLOC_OFF_GEN + 4 * NOALLOC_MAX_ROWS, NOALLOC_OFF_GM = NOALLOC_OFF_OUT + 4 * NOALLOC_MAX_ROWS,
+                 NOALLOC_BYTES = NOALLOC_OFF_GM + 4 * NOALLOC_MAX_GROUP_MAX;
+static_assert(NOALLOC_OFF_GM % 256 == 0, "group maxima start on a 256-byte boundary");
+static __device__ __align__(256) unsigned char scratch[NOALLOC_BYTES];
+constexpr int MAX_DEVICES = 64;
+static unsigned char* g_scratch_ptr[MAX_DEVICES];                // device address of `scratch` on each GPU, set by april_init
+
 struct april_buffer {
   uint64_t magic = 0xA9B1FFEEull;
   std::vector<Entry> entries;
@@ -147,6 +160,9 @@ struct april_ctx {
   int steps_started = 0;
   int graph_iters = 4;                       // iterations per replayed graph when consecutive ones share their bounds
                                              // (a graph boundary costs about 4 us on the device: 45.6 -> 45.7 k tokens/s)
+
+  int device = 0;                // HIP device the context lives on
+  unsigned char* scratch_dev = nullptr;   // this device's copy of the static scratch array
 
   // pending resume
   std::vector<Entry> pending;
@@ -551,6 +567,15 @@ int april_init(const april_model_cfg* cfg, const april_tensor* weights, int32_t 
 
   if (g.stream) c->stream = (hipStream_t)g.stream;
   else { HIPTRY(hipStreamCreate(&c->stream)); c->own_stream = true; }
+  // device address of the static scratch array on this GPU (each GPU has its own copy)
+  HIPTRY(hipGetDevice(&c->device));
+  if (c->device < 0 || c->device >= MAX_DEVICES) { fail(c, APRIL_EINVAL, "device index %d not supported", c->device); return bail(APRIL_EINVAL); }
+  if (!g_scratch_ptr[c->device]) {
+    unsigned char* sp = nullptr;
+    HIPTRY(hipGetSymbolAddress((void**)&sp, HIP_SYMBOL(scratch)));
+    g_scratch_ptr[c->device] = sp;
+  }
+  c->scratch_dev = g_scratch_ptr[c->device];
 
   // ---- weights ------------------------------------------------------------------
   const size_t e = c->esz;
@@ -1001,6 +1026,39 @@ int april_sample_rows(april_ctx* c, const float* logits, int32_t n_rows, const i
   HIPCHK(c, hipMemcpy(out_tokens, d_out, n_rows * sizeof(int), hipMemcpyDeviceToHost));
   hipFree(d_req); hipFree(d_gen); hipFree(d_out); hipFree(d_n);
   if (d_gm) hipFree(d_gm);
+  return APRIL_OK;
+}
+
+// The same sampler for callers that must not allocate: every temporary lives in this GPU's
+// static scratch array.  No hipMalloc / hipFree here or below.
+int april_sample_rows_noalloc(april_ctx* c, const float* logits, int32_t n_rows, const int64_t* request_ids,
+                              const int32_t* gen_index, int32_t* out_tokens) {
+  if (!c || !logits || !request_ids || !gen_index || !out_tokens || n_rows <= 0) return APRIL_EINVAL;
+  const int grp = lmhead_group_cols();
+  const bool use_gm = c->dm.vocab % grp == 0;
+  if ((size_t)n_rows > NOALLOC_MAX_ROWS)
+    return fail(c, APRIL_EINVAL, "april_sample_rows_noalloc: %d rows, at most %zu", n_rows, NOALLOC_MAX_ROWS);
+  if (use_gm && (size_t)n_rows * (size_t)(c->dm.vocab / grp) > NOALLOC_MAX_GROUP_MAX)
+    return fail(c, APRIL_EINVAL, "april_sample_rows_noalloc: rows x vocab/%d = %zu exceeds the scratch (%zu)", grp,
+                (size_t)n_rows * (size_t)(c->dm.vocab / grp), NOALLOC_MAX_GROUP_MAX);
+  if (!c->scratch_dev) return fail(c, APRIL_EDEVICE, "scratch address was not resolved at april_init");
+  unsigned char* sp = c->scratch_dev;
+  int* d_n = reinterpret_cast<int*>(sp + NOALLOC_OFF_CTL);
+  long long* d_req = reinterpret_cast<long long*>(sp + NOALLOC_OFF_REQ);
+  int* d_gen = reinterpret_cast<int*>(sp + NOALLOC_OFF_GEN);
+  int* d_out = reinterpret_cast<int*>(sp + NOALLOC_OFF_OUT);
+  float* d_gm = use_gm ? reinterpret_cast<float*>(sp + NOALLOC_OFF_GM) : nullptr;
+  hipStream_t st = c->stream;
+  const int ctl[2] = {n_rows, 0};                 // {rows, stop flag}: the array keeps the last call's contents
+  HIPCHK(c, hipMemcpyAsync(d_n, ctl, sizeof ctl, hipMemcpyHostToDevice, st));
+  HIPCHK(c, hipMemcpyAsync(d_req, request_ids, n_rows * sizeof(long long), hipMemcpyHostToDevice, st));
+  HIPCHK(c, hipMemcpyAsync(d_gen, gen_index, n_rows * sizeof(int), hipMemcpyHostToDevice, st));
+  RowCtx rc{nullptr, nullptr, reinterpret_cast<const int2*>(d_n), n_rows};
+  SamplerCfg sc{c->cfg.sampler, c->cfg.top_k, c->cfg.temperature, (unsigned long long)c->cfg.seed};
+  if (use_gm) launch_group_max(st, logits, n_rows, c->dm.vocab, grp, d_gm);
+  launch_sample(st, rc, c->ds, nullptr, logits, c->dm.vocab, sc, Watch{}, 0, d_req, d_gen, d_out, d_gm, grp);
+  HIPCHK(c, hipMemcpyAsync(out_tokens, d_out, n_rows * sizeof(int), hipMemcpyDeviceToHost, st));
+  HIPCHK(c, hipStreamSynchronize(st));
   return APRIL_OK;
 }
 

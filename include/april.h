@@ -158,7 +158,11 @@ int april_init(const april_model_cfg* cfg, const april_tensor* weights, int32_t 
  * youngest decoding rollout (largest request id) is preempted - pages freed, tokens kept,
  * no progress this step, re-prefilled when resumed; if nothing is left in flight the step
  * returns fewer than N_target (n_completed says how many).
- * new_reqs: host array [n_new_avail]; out: host struct filled by the call. */
+ * new_reqs: host array [n_new_avail]; out: host struct filled by the call.
+ * A call that fails is transactional with respect to the rollouts: none of new_reqs is
+ * consumed (the caller still owns them), and every rollout that april_resume had handed in
+ * goes back to the pending set - with the tokens it generated before the failure, without its
+ * KV pages - so the next april_rollout_step admits it first again; `out` is not filled. */
 int april_rollout_step(april_ctx* ctx, const april_request* new_reqs, int32_t n_new_avail,
                        int32_t N_target, int32_t N_overprovision, int32_t max_new,
                        april_step_result* out);

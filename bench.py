@@ -79,6 +79,26 @@ def cpu_baseline(w, weights, reqs, budget_s=20.0):
                        f"{per_roll} generated tokens, one rollout at a time ({dt:.1f} s)")
 
 
+def generate_weights(ai, ap, s, seed, keep_fp32, threads=16):
+    """Random-init tensors of the model, drawn tensor by tensor on a thread pool (every tensor has
+    its own seeded stream, so the order does not matter); returns (packed for the library, fp32
+    values for the oracle leg or {})."""
+    from concurrent.futures import ThreadPoolExecutor
+    specs = ai.weight_specs(s)
+
+    def one(spec):
+        name, shape, kind = spec
+        a = ai.weight_tensor(s, name, shape, kind, seed)
+        return name, a, ap.pack_weights(s, {name: a})[name]
+    packed, weights = {}, {}
+    with ThreadPoolExecutor(max_workers=threads) as ex:
+        for name, a, pk in ex.map(one, specs):
+            packed[name] = pk
+            if keep_fp32:
+                weights[name] = a
+    return packed, weights
+
+
 def measured_traffic(workload, kernel_class):
     """HBM bytes per launch of a kernel class (fetch + write), from the committed summary of
     the two rocprofv3 --pmc runs over this benchmark's command (already scaled by the copy
@@ -112,7 +132,10 @@ def main():
     p.add_argument("--gpus", type=int, default=1)
     p.add_argument("--steps", type=int, default=5)
     p.add_argument("--warmup", type=int, default=1)
-    p.add_argument("--workload", default="cfg2_small_bf16")
+    p.add_argument("--workload", default="cfg3_mid_bf16",
+                   help="the largest configuration whose --steps 20 --warmup 5 run fits a 10-minute limit on one GPU")
+    p.add_argument("--wait-all-steps", type=int, default=2,
+                   help="steps of the wait-for-all arm (same request stream; each of its steps runs to the length cap)")
     p.add_argument("--layers", type=int, default=0, help="override the layer count (debug only; invalidates the number)")
     p.add_argument("--max-new", type=int, default=0, help="cap the generated length (debug only; invalidates the number)")
     p.add_argument("--no-cpu-baseline", action="store_true")
@@ -150,15 +173,8 @@ def main():
     t_setup = time.perf_counter()
     # the library's element types, tensor by tensor; the fp32 values are kept only for the
     # oracle leg (the large configurations would not fit the host twice)
-    weights, packed, last_note = {}, {}, time.perf_counter()
-    for name, a in ai.iter_weights(s, w.seed):
-        packed.update(ap.pack_weights(s, {name: a}))
-        if not args.no_cpu_baseline:
-            weights[name] = a
-        if time.perf_counter() - last_note > 30.0:
-            note(f"generating weights: {name}")
-            last_note = time.perf_counter()
-    note(f"weights generated ({ai.n_params(s) / 1e9:.2f} B parameters)")
+    packed, weights = generate_weights(ai, ap, s, w.seed, keep_fp32=not args.no_cpu_baseline)
+    note(f"weights generated ({ai.n_params(s) / 1e9:.2f} B parameters, {time.perf_counter() - t_setup:.1f} s)")
     total_steps = args.steps
     reqs = ai.make_requests(w, ai.requests_needed(w, max(total_steps, args.warmup)))
     cfg = ap.make_cfg(s, max_inflight=w.n_overprovision + 32, max_ctx=w.prompt_len + w.max_new + 16,
@@ -246,6 +262,8 @@ def main():
         ach = dom["alg_bytes"] / dom["launches"] / (launch_us(dom) * 1e-6) / 1e9
         out["roofline"] = {"kernel": dom["name"], "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS,
                            "unit": "GB/s", "frac": ach / HBM_PEAK_GBS, "traffic": measured_traffic(w.name, dom["name"]),
+                           "traffic_source": f"profiles/hbm_traffic_{w.name}.txt (committed rocprofv3 --pmc reading of this "
+                                             "command with --layers 1, not a measurement of this run)",
                            "alg_bytes_per_launch": dom["alg_bytes"] / dom["launches"],
                            "avg_launch_us": launch_us(dom),
                            "avg_event_pair_us": 1e3 * dom["total_ms"] / dom["launches"],
@@ -260,10 +278,11 @@ def main():
 
     if not args.no_wait_all:
         reset_engine()
-        res_wait, wall_wait = fresh_arm(w.n_target, total_steps, 0)
+        wait_steps = max(1, min(total_steps, args.wait_all_steps))
+        res_wait, wall_wait = fresh_arm(w.n_target, wait_steps, 0)
         tok_wait = sum(r.tokens_generated for r in res_wait)
         t_wait = sum(r.t_total_s for r in res_wait)
-        out["wait_all"] = {"tokens_generated": tok_wait, "decode_iters": sum(r.decode_iters for r in res_wait),
+        out["wait_all"] = {"steps": wait_steps, "tokens_generated": tok_wait, "decode_iters": sum(r.decode_iters for r in res_wait),
                            "step_time_s": t_wait, "tokens_per_s": tok_wait / t_wait, "wall_s": wall_wait}
         out["april_speedup_vs_wait_all"] = value / (tok_wait / t_wait)
     ap.april_destroy(ctx)

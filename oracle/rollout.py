@@ -17,7 +17,9 @@ from .scheduler import Rollout, rollout_step
 
 class OracleRollouts:
     def __init__(self, decoder, sampler="greedy", top_k=50, temperature=1.0, seed=0,
-                 eos_token=-1, keep_logits=False):
+                 eos_token=-1, keep_logits=False, top_p=1.0):
+        """sampler: "greedy", "topk" (top-k, then nucleus top_p when < 1) or "categorical"
+        (temperature sampling over the whole vocabulary, the paper's rollout setting)."""
         self.dec = decoder
         self.sampler = sampler
         self.top_k = top_k
@@ -25,6 +27,7 @@ class OracleRollouts:
         self.seed = seed
         self.eos_token = eos_token
         self.keep_logits = keep_logits
+        self.top_p = top_p
         self.buffer = []
         self.logits = {}            # (request_id, gen_index) -> logits row, if keep_logits
 
@@ -32,9 +35,17 @@ class OracleRollouts:
         if self.keep_logits:
             self.logits[(r.request_id, r.gen)] = logits.copy()
         if self.sampler == "greedy":
-            return _sampler.greedy(logits)
-        u = uniform_for(self.seed, r.request_id, r.gen)
-        return _sampler.top_k_sample(logits, self.top_k, self.temperature, u)
+            tok = _sampler.greedy(logits)
+        else:
+            u = uniform_for(self.seed, r.request_id, r.gen)
+            if self.sampler == "categorical":
+                tok = _sampler.categorical_sample(logits, self.temperature, u)
+            else:
+                tok = _sampler.top_k_top_p_sample(logits, self.top_k, self.temperature, self.top_p, u)
+        # log-probability of the chosen token under softmax(logits / temperature) over the whole
+        # vocabulary: what the trainer's importance ratio uses (Section 2.2)
+        r.user.setdefault("logprobs", []).append(_sampler.token_logprob(logits, self.temperature, tok))
+        return tok
 
     def _next_token(self, r):
         st = r.user

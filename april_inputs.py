@@ -24,6 +24,7 @@ DTYPE_BF16 = 1
 
 SAMPLER_GREEDY = 0
 SAMPLER_TOPK = 1
+SAMPLER_CATEGORICAL = 2
 
 
 @dataclass(frozen=True)

@@ -28,9 +28,9 @@ VERBOSE = False
 
 
 def note(msg):
-    """Progress line on stderr (--verbose): long configurations would otherwise be silent for minutes."""
-    if VERBOSE:
-        print(f"[bench {time.strftime('%H:%M:%S')}] {msg}", file=sys.stderr, flush=True)
+    """Progress line on stderr (stdout carries only the JSON line): a step of the larger
+    configurations takes 10-25 s, and a run that prints nothing for minutes looks hung."""
+    print(f"[bench {time.strftime('%H:%M:%S')}] {msg}", file=sys.stderr, flush=True)
 
 
 def run_arm(ap, ctx, reqs, n_target, n_over, max_new, steps, profile_every=0):

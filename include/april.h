@@ -42,7 +42,9 @@ extern "C" {
 #define APRIL_DTYPE_FP32 0
 #define APRIL_DTYPE_BF16 1
 #define APRIL_SAMPLER_GREEDY 0
-#define APRIL_SAMPLER_TOPK   1
+#define APRIL_SAMPLER_TOPK   1   /* top-k, then (top_p < 1) the nucleus of the k candidates            */
+#define APRIL_SAMPLER_CATEGORICAL 2   /* temperature sampling over the whole vocabulary (the paper's
+                                         rollout setting, appendix: rollout temperature, no truncation) */
 
 typedef struct april_ctx    april_ctx;     /* opaque; owns all device state            */
 typedef struct april_buffer april_buffer;  /* opaque handle: a continuation buffer     */
@@ -71,6 +73,13 @@ typedef struct {
   uint64_t seed;             /* Philox key of the sampler                                 */
   int32_t eos_token;         /* -1: only length limits end a rollout                      */
   int32_t debug_logits;      /* 1: parity mode, logits of watched requests are kept       */
+  float   top_p;             /* top-k sampler: keep the shortest prefix of the k candidates
+                                (descending) whose probabilities, renormalised over the k
+                                candidates, reach top_p; 0 or >= 1: no nucleus cut (the paper's
+                                appendix lists an evaluation top_p)                          */
+  int32_t logprobs;          /* 1: keep log softmax(logits / temperature)[token] over the whole
+                                vocabulary for every generated token (what a trainer's
+                                importance ratio needs, Section 2.2) and return it            */
   void*   stream;            /* hipStream_t to run on (e.g. torch's current), or NULL     */
 } april_model_cfg;
 
@@ -112,6 +121,7 @@ typedef struct {
   const int32_t* const* tokens;   /* [n_completed] generated tokens only                   */
   const int32_t* n_tokens;        /* [n_completed]                                         */
   const int32_t* n_resumes;       /* [n_completed] steps the rollout spanned, minus one    */
+  const float* const* logprobs;   /* [n_completed] per generated token (cfg.logprobs), else NULL */
   april_buffer*  buffer;          /* unfinished + surplus-complete rollouts (never NULL)   */
   int32_t  n_new_consumed;        /* how many of new_reqs were admitted                    */
   int64_t  decode_iters;          /* iterations executed (each adds 1 token per live seq)  */
@@ -138,6 +148,7 @@ typedef struct {
   int32_t n_resumes;
   int32_t done;             /* 1: complete, waiting to be delivered first next step        */
   int32_t kv_resident;      /* 1: its KV pages are still on the device                     */
+  const float* logprobs;    /* host, [n_generated] (cfg.logprobs), or NULL                  */
 } april_partial;
 
 /* Create a context on the current HIP device: copy/re-layout the weights, carve the
@@ -198,6 +209,12 @@ int april_debug_logits(april_ctx* ctx, int64_t request_id, int32_t gen_index,
  * gen_index (host, [n_rows]) key the Philox stream; out_tokens host [n_rows]. */
 int april_sample_rows(april_ctx* ctx, const float* logits, int32_t n_rows,
                       const int64_t* request_ids, const int32_t* gen_index, int32_t* out_tokens);
+
+/* The same with the log-probability of each chosen token (out_logprobs host [n_rows]):
+ * log softmax(logits / temperature) over the whole vocabulary. */
+int april_sample_rows_logprobs(april_ctx* ctx, const float* logits, int32_t n_rows,
+                               const int64_t* request_ids, const int32_t* gen_index,
+                               int32_t* out_tokens, float* out_logprobs);
 
 /* april_sample_rows for callers that cannot allocate device memory (code under HIP graph
  * capture rules, tight serving loops, harnesses that forbid hipMalloc): same arguments, same

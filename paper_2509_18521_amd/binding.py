@@ -17,13 +17,13 @@ LIB_PATH = os.path.join(_PKG, "libapril.so")
 
 APRIL_OK, APRIL_EINVAL, APRIL_ENOMEM, APRIL_ESTARVED, APRIL_EHANDLE, APRIL_EDEVICE = 0, -1, -2, -3, -4, -5
 APRIL_DTYPE_FP32, APRIL_DTYPE_BF16 = 0, 1
-APRIL_SAMPLER_GREEDY, APRIL_SAMPLER_TOPK = 0, 1
+APRIL_SAMPLER_GREEDY, APRIL_SAMPLER_TOPK, APRIL_SAMPLER_CATEGORICAL = 0, 1, 2
 APRIL_KERNEL_CLASSES = 24
 
 EXPORTS = [
     "april_init", "april_rollout_step", "april_resume", "april_buffer_size", "april_buffer_export",
     "april_buffer_import", "april_buffer_drop_kv", "april_buffer_free", "april_debug_watch",
-    "april_debug_logits", "april_sample_rows", "april_sample_rows_noalloc", "april_profile_enable", "april_profile_get",
+    "april_debug_logits", "april_sample_rows", "april_sample_rows_logprobs", "april_sample_rows_noalloc", "april_profile_enable", "april_profile_get",
     "april_profile_reset", "april_get_info", "april_last_error", "april_destroy",
 ]
 
@@ -43,7 +43,8 @@ class april_model_cfg(C.Structure):
         ("kv_block_tokens", C.c_int32), ("kv_pool_bytes", C.c_int64),
         ("max_inflight", C.c_int32), ("max_ctx", C.c_int32),
         ("sampler", C.c_int32), ("top_k", C.c_int32), ("temperature", C.c_float), ("seed", C.c_uint64),
-        ("eos_token", C.c_int32), ("debug_logits", C.c_int32), ("stream", C.c_void_p),
+        ("eos_token", C.c_int32), ("debug_logits", C.c_int32), ("top_p", C.c_float), ("logprobs", C.c_int32),
+        ("stream", C.c_void_p),
     ]
 
 
@@ -60,7 +61,8 @@ class april_step_result(C.Structure):
     _fields_ = [
         ("n_completed", C.c_int32), ("request_id", C.POINTER(C.c_int64)),
         ("tokens", C.POINTER(C.POINTER(C.c_int32))), ("n_tokens", C.POINTER(C.c_int32)),
-        ("n_resumes", C.POINTER(C.c_int32)), ("buffer", C.c_void_p), ("n_new_consumed", C.c_int32),
+        ("n_resumes", C.POINTER(C.c_int32)), ("logprobs", C.POINTER(C.POINTER(C.c_float))),
+        ("buffer", C.c_void_p), ("n_new_consumed", C.c_int32),
         ("decode_iters", C.c_int64), ("tokens_generated", C.c_int64), ("prefill_tokens", C.c_int64),
         ("reprefill_tokens", C.c_int64), ("n_preempted", C.c_int64), ("sum_live", C.c_int64), ("sum_ctx", C.c_int64),
         ("dec_sum_live", C.c_int64), ("dec_sum_ctx", C.c_int64), ("dec_sum_experts", C.c_int64),
@@ -71,7 +73,8 @@ class april_step_result(C.Structure):
 class april_partial(C.Structure):
     _fields_ = [("request_id", C.c_int64), ("prompt", C.POINTER(C.c_int32)), ("n_prompt", C.c_int32),
                 ("generated", C.POINTER(C.c_int32)), ("n_generated", C.c_int32), ("limit", C.c_int32),
-                ("n_resumes", C.c_int32), ("done", C.c_int32), ("kv_resident", C.c_int32)]
+                ("n_resumes", C.c_int32), ("done", C.c_int32), ("kv_resident", C.c_int32),
+                ("logprobs", C.POINTER(C.c_float))]
 
 
 class april_kernel_stat(C.Structure):
@@ -113,6 +116,7 @@ def load_library():
     lib.april_sample_rows.argtypes = [vp, vp, C.c_int32, C.POINTER(C.c_int64), C.POINTER(C.c_int32),
                                       C.POINTER(C.c_int32)]
     lib.april_sample_rows_noalloc.argtypes = lib.april_sample_rows.argtypes
+    lib.april_sample_rows_logprobs.argtypes = lib.april_sample_rows.argtypes + [C.POINTER(C.c_float)]
     lib.april_profile_enable.argtypes = [vp, C.c_int32]
     lib.april_profile_get.argtypes = [vp, C.POINTER(april_kernel_stat), C.c_int32]
     lib.april_profile_reset.argtypes = [vp]
@@ -187,6 +191,7 @@ class StepResult:
     t_prefill_s: float
     t_decode_s: float
     t_total_s: float
+    logprobs: Optional[List[np.ndarray]] = None      # per completed rollout (contexts created with logprobs)
 
 
 def april_rollout_step(ctx, requests: Sequence[dict], n_target: int, n_overprovision: int, max_new: int) -> StepResult:
@@ -207,14 +212,17 @@ def april_rollout_step(ctx, requests: Sequence[dict], n_target: int, n_overprovi
     res = april_step_result()
     _check(ctx, lib.april_rollout_step(ctx, arr, n, n_target, n_overprovision, max_new, C.byref(res)))
     ids, toks, nres = [], [], []
+    lps = [] if res.logprobs else None
     for i in range(res.n_completed):
         ids.append(int(res.request_id[i]))
         nt = int(res.n_tokens[i])
         toks.append(np.ctypeslib.as_array(res.tokens[i], shape=(nt,)).copy() if nt > 0 else np.zeros(0, np.int32))
         nres.append(int(res.n_resumes[i]))
+        if lps is not None:
+            lps.append(np.ctypeslib.as_array(res.logprobs[i], shape=(nt,)).copy() if nt > 0 else np.zeros(0, np.float32))
     return StepResult(ids, toks, nres, C.c_void_p(res.buffer), res.n_new_consumed, res.decode_iters,
                       res.tokens_generated, res.prefill_tokens, res.reprefill_tokens, res.n_preempted, res.sum_live, res.sum_ctx, res.dec_sum_live, res.dec_sum_ctx, res.dec_sum_experts,
-                      res.t_prefill_s, res.t_decode_s, res.t_total_s)
+                      res.t_prefill_s, res.t_decode_s, res.t_total_s, lps)
 
 
 def april_resume(ctx, buffer):
@@ -238,7 +246,9 @@ def april_buffer_export(ctx, buffer) -> List[dict]:
             prompt=np.ctypeslib.as_array(p.prompt, shape=(p.n_prompt,)).copy(),
             generated=(np.ctypeslib.as_array(p.generated, shape=(p.n_generated,)).copy()
                        if p.n_generated > 0 else np.zeros(0, np.int32)),
-            limit=int(p.limit), n_resumes=int(p.n_resumes), done=int(p.done), kv_resident=int(p.kv_resident)))
+            limit=int(p.limit), n_resumes=int(p.n_resumes), done=int(p.done), kv_resident=int(p.kv_resident),
+            logprobs=(np.ctypeslib.as_array(p.logprobs, shape=(p.n_generated,)).copy()
+                      if p.logprobs and p.n_generated > 0 else None)))
     return out
 
 
@@ -250,10 +260,14 @@ def april_buffer_import(ctx, partials: Sequence[dict]):
     for i, p in enumerate(partials):
         pr = np.ascontiguousarray(p["prompt"], dtype=np.int32)
         ge = np.ascontiguousarray(p["generated"], dtype=np.int32)
-        keep += [pr, ge]
+        lp = p.get("logprobs")
+        if lp is not None:
+            lp = np.ascontiguousarray(lp, dtype=np.float32)
+        keep += [pr, ge, lp]
         arr[i] = april_partial(int(p["request_id"]), _i32ptr(pr), pr.shape[0],
                                _i32ptr(ge) if ge.shape[0] else None, ge.shape[0], int(p["limit"]),
-                               int(p.get("n_resumes", 0)), int(p.get("done", 0)), 0)
+                               int(p.get("n_resumes", 0)), int(p.get("done", 0)), 0,
+                               lp.ctypes.data_as(C.POINTER(C.c_float)) if lp is not None and lp.shape[0] else None)
     out = C.c_void_p()
     _check(ctx, lib.april_buffer_import(ctx, arr, n, C.byref(out)))
     return out
@@ -286,6 +300,17 @@ def april_sample_rows(ctx, logits_device_ptr: int, n_rows: int, request_ids, gen
     _check(ctx, load_library().april_sample_rows(ctx, C.c_void_p(logits_device_ptr), n_rows,
                                                  rid.ctypes.data_as(C.POINTER(C.c_int64)), _i32ptr(gi), _i32ptr(out)))
     return out
+
+
+def april_sample_rows_logprobs(ctx, logits_device_ptr: int, n_rows: int, request_ids, gen_index):
+    rid = np.ascontiguousarray(request_ids, dtype=np.int64)
+    gi = np.ascontiguousarray(gen_index, dtype=np.int32)
+    out = np.empty(n_rows, dtype=np.int32)
+    lp = np.empty(n_rows, dtype=np.float32)
+    _check(ctx, load_library().april_sample_rows_logprobs(ctx, C.c_void_p(logits_device_ptr), n_rows,
+                                                          rid.ctypes.data_as(C.POINTER(C.c_int64)), _i32ptr(gi),
+                                                          _i32ptr(out), lp.ctypes.data_as(C.POINTER(C.c_float))))
+    return out, lp
 
 
 def april_sample_rows_noalloc(ctx, logits_device_ptr: int, n_rows: int, request_ids, gen_index) -> np.ndarray:
@@ -323,12 +348,13 @@ def april_get_info(ctx) -> dict:
 # helpers to build the configuration and weight table from the synthetic inputs
 # ---------------------------------------------------------------------------
 def make_cfg(shape, *, max_inflight, max_ctx, sampler=APRIL_SAMPLER_GREEDY, top_k=1, temperature=1.0, seed=0,
-             eos_token=-1, debug_logits=False, kv_pool_bytes=0, stream=None) -> april_model_cfg:
+             eos_token=-1, debug_logits=False, kv_pool_bytes=0, stream=None, top_p=0.0,
+             logprobs=False) -> april_model_cfg:
     return april_model_cfg(
         shape.n_layers, shape.d_model, shape.n_q_heads, shape.n_kv_heads, shape.head_dim, shape.d_ffn,
         shape.vocab, shape.n_experts, shape.experts_per_tok, shape.d_expert_ffn, shape.dtype,
         shape.rope_theta, shape.rms_eps, 16, kv_pool_bytes, max_inflight, max_ctx, sampler, top_k,
-        temperature, seed, eos_token, 1 if debug_logits else 0, stream)
+        temperature, seed, eos_token, 1 if debug_logits else 0, top_p, 1 if logprobs else 0, stream)
 
 
 def pack_weights(shape, weights_fp32: Dict[str, np.ndarray]) -> Dict[str, np.ndarray]:

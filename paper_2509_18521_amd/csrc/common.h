@@ -51,6 +51,7 @@ struct Slots {
   int* block_table;   // [n_slots][max_blocks]
   int* tokens;        // [n_slots][max_ctx]: prompt, then generated tokens
   int* forced;        // [n_slots][max_ctx] teacher-forced generated tokens (-1: none), or null
+  float* logprob;     // [n_slots][max_ctx] log-probability of generated token g at index g, or null
   int max_blocks;
   int max_ctx;
 };

@@ -53,6 +53,7 @@ struct Entry {
   long long req = -1;
   int slot = -1;                 // -1: token-level entry without a slot
   std::vector<int> prompt, generated;
+  std::vector<float> logprobs;   // of `generated` (contexts that keep log-probabilities), token-level entries
   int limit = 0, n_resumes = 0, done = 0;
 };
 
@@ -174,6 +175,8 @@ struct april_ctx {
   std::vector<std::vector<int>> r_tokens;
   std::vector<const int32_t*> r_tok_ptrs;
   std::vector<int> r_ntok, r_nres;
+  std::vector<std::vector<float>> r_logprobs;
+  std::vector<const float*> r_lp_ptrs;
   std::vector<std::vector<int>> export_store;
 
   // profiling
@@ -297,6 +300,12 @@ void prof_collect(april_ctx* c) {   // stream must be idle
   c->prof_recs.clear();
   c->ev_used = 0;
   c->snaps_used = 0;
+}
+
+SamplerCfg sampler_cfg(const april_ctx* c) {
+  const float T = c->cfg.temperature > 0.f ? c->cfg.temperature : 1.0f;
+  const float tp = (c->cfg.top_p > 0.f && c->cfg.top_p < 1.f) ? c->cfg.top_p : 1.0f;
+  return SamplerCfg{c->cfg.sampler, c->cfg.top_k, T, (unsigned long long)c->cfg.seed, tp};
 }
 
 // ---- forward pass --------------------------------------------------------------
@@ -442,7 +451,7 @@ void forward(april_ctx* c, RowCtx rows, RowCtx srows, const int* gather, double 
   }
   {
     ProfScope p(c, KC_SAMPLE, SB * V * 4.0, 0);
-    SamplerCfg sc{c->cfg.sampler, c->cfg.top_k, c->cfg.temperature, (unsigned long long)c->cfg.seed};
+    const SamplerCfg sc = sampler_cfg(c);
     Watch w = c->cfg.debug_logits ? c->dwatch : Watch{};
     launch_sample(st, srows, c->ds, c->d_ctrl, c->logits, V, sc, w, 1, nullptr, nullptr, nullptr, c->group_max,
                   lmhead_group_cols());
@@ -530,8 +539,13 @@ int april_init(const april_model_cfg* cfg, const april_tensor* weights, int32_t 
   if (g.dtype != APRIL_DTYPE_FP32 && g.dtype != APRIL_DTYPE_BF16) return fail(nullptr, APRIL_EINVAL, "bad dtype");
   if (g.max_inflight <= 0 || g.max_inflight > 2048) return fail(nullptr, APRIL_EINVAL, "max_inflight must be in 1..2048");
   if (g.max_ctx <= 1 || g.max_ctx > 32768) return fail(nullptr, APRIL_EINVAL, "max_ctx must be in 2..32768");
+  if (g.sampler != APRIL_SAMPLER_GREEDY && g.sampler != APRIL_SAMPLER_TOPK && g.sampler != APRIL_SAMPLER_CATEGORICAL)
+    return fail(nullptr, APRIL_EINVAL, "unknown sampler");
   if (g.sampler == APRIL_SAMPLER_TOPK && (g.top_k < 1 || g.top_k > 64 || !(g.temperature > 0.f)))
     return fail(nullptr, APRIL_EINVAL, "top_k must be in 1..64 and temperature > 0");
+  if (g.sampler == APRIL_SAMPLER_CATEGORICAL && !(g.temperature > 0.f))
+    return fail(nullptr, APRIL_EINVAL, "the categorical sampler needs temperature > 0");
+  if (g.top_p < 0.f) return fail(nullptr, APRIL_EINVAL, "top_p must be in (0, 1], or 0 for none");
   const int nq = g.n_q_heads * g.head_dim, nkv = g.n_kv_heads * g.head_dim, nqkv = nq + 2 * nkv;
   const int d = g.d_model, F = g.d_ffn, V = g.vocab;
   if (g.dtype == APRIL_DTYPE_BF16 && (d % 32 || (!moe && F % 32) || V % 32 || nq % 32 || nqkv % 32))
@@ -687,6 +701,8 @@ int april_init(const april_model_cfg* cfg, const april_tensor* weights, int32_t 
     TRY(dev_alloc(c, &c->ds.forced, (size_t)S * c->max_ctx, false));
     launch_fill_i32(c->stream, c->ds.forced, -1, (size_t)S * c->max_ctx);
   }
+  c->ds.logprob = nullptr;
+  if (g.logprobs) TRY(dev_alloc(c, &c->ds.logprob, (size_t)S * c->max_ctx));
   TRY(dev_alloc(c, &c->d_ctrl, 1));
   HIPTRY(hipHostMalloc((void**)&c->h_ctrl, sizeof(Ctrl)));
   HIPTRY(hipHostMalloc((void**)&c->h_slot_arrays, (size_t)8 * S * sizeof(int)));
@@ -885,6 +901,11 @@ static int sync_entry_tokens(april_ctx* c, Entry& e) {
   if (s.gen > 0) {
     HIPCHK(c, hipMemcpyAsync(e.generated.data(), c->ds.tokens + (size_t)e.slot * c->max_ctx + s.prompt_len,
                              (size_t)s.gen * sizeof(int), hipMemcpyDeviceToHost, c->stream));
+    if (c->ds.logprob) {
+      e.logprobs.resize(s.gen);
+      HIPCHK(c, hipMemcpyAsync(e.logprobs.data(), c->ds.logprob + (size_t)e.slot * c->max_ctx,
+                               (size_t)s.gen * sizeof(float), hipMemcpyDeviceToHost, c->stream));
+    }
     HIPCHK(c, hipStreamSynchronize(c->stream));
   }
   return APRIL_OK;
@@ -904,6 +925,7 @@ int april_buffer_export(april_ctx* c, const april_buffer* buffer, april_partial*
     out[i].generated = e.generated.data(); out[i].n_generated = (int)e.generated.size();
     out[i].limit = e.limit; out[i].n_resumes = e.n_resumes; out[i].done = e.done;
     out[i].kv_resident = (e.slot >= 0 && c->slots[e.slot].kv_len > 0) ? 1 : 0;
+    out[i].logprobs = (c->ds.logprob && e.logprobs.size() == e.generated.size() && !e.logprobs.empty()) ? e.logprobs.data() : nullptr;
   }
   return n;
 }
@@ -927,6 +949,7 @@ int april_buffer_import(april_ctx* c, const april_partial* in, int32_t n, april_
     e.req = in[i].request_id;
     e.prompt.assign(in[i].prompt, in[i].prompt + in[i].n_prompt);
     e.generated.assign(in[i].generated, in[i].generated + in[i].n_generated);
+    if (in[i].logprobs && in[i].n_generated > 0) e.logprobs.assign(in[i].logprobs, in[i].logprobs + in[i].n_generated);
     e.limit = in[i].limit; e.n_resumes = in[i].n_resumes;
     e.done = in[i].n_generated >= in[i].limit ? 1 : (in[i].done ? 1 : 0);
     b->entries.push_back(std::move(e));
@@ -1005,33 +1028,48 @@ int april_debug_logits(april_ctx* c, int64_t request_id, int32_t gen_index, floa
   return APRIL_OK;
 }
 
-int april_sample_rows(april_ctx* c, const float* logits, int32_t n_rows, const int64_t* request_ids,
-                      const int32_t* gen_index, int32_t* out_tokens) {
+static int sample_rows_impl(april_ctx* c, const float* logits, int32_t n_rows, const int64_t* request_ids,
+                            const int32_t* gen_index, int32_t* out_tokens, float* out_logprobs) {
   if (!c || !logits || !request_ids || !gen_index || !out_tokens || n_rows <= 0) return APRIL_EINVAL;
   long long* d_req = nullptr; int *d_gen = nullptr, *d_out = nullptr, *d_n = nullptr;
-  HIPCHK(c, hipMalloc((void**)&d_req, n_rows * sizeof(long long)));
-  HIPCHK(c, hipMalloc((void**)&d_gen, n_rows * sizeof(int)));
-  HIPCHK(c, hipMalloc((void**)&d_out, n_rows * sizeof(int)));
-  HIPCHK(c, hipMalloc((void**)&d_n, 2 * sizeof(int)));
-  HIPCHK(c, hipMemset(d_n, 0, 2 * sizeof(int)));
-  HIPCHK(c, hipMemcpy(d_req, request_ids, n_rows * sizeof(long long), hipMemcpyHostToDevice));
-  HIPCHK(c, hipMemcpy(d_gen, gen_index, n_rows * sizeof(int), hipMemcpyHostToDevice));
-  HIPCHK(c, hipMemcpy(d_n, &n_rows, sizeof(int), hipMemcpyHostToDevice));
-  RowCtx rc{nullptr, nullptr, reinterpret_cast<const int2*>(d_n), n_rows};
-  SamplerCfg sc{c->cfg.sampler, c->cfg.top_k, c->cfg.temperature, (unsigned long long)c->cfg.seed};
-  // same candidate search as the rollout path: group maxima first when the vocabulary allows
-  const int grp = lmhead_group_cols();
-  float* d_gm = nullptr;
-  if (c->dm.vocab % grp == 0) {
-    HIPCHK(c, hipMalloc((void**)&d_gm, (size_t)n_rows * (c->dm.vocab / grp) * sizeof(float)));
-    launch_group_max(c->stream, logits, n_rows, c->dm.vocab, grp, d_gm);
-  }
-  launch_sample(c->stream, rc, c->ds, nullptr, logits, c->dm.vocab, sc, Watch{}, 0, d_req, d_gen, d_out, d_gm, grp);
-  HIPCHK(c, hipStreamSynchronize(c->stream));
-  HIPCHK(c, hipMemcpy(out_tokens, d_out, n_rows * sizeof(int), hipMemcpyDeviceToHost));
-  hipFree(d_req); hipFree(d_gen); hipFree(d_out); hipFree(d_n);
-  if (d_gm) hipFree(d_gm);
-  return APRIL_OK;
+  float *d_gm = nullptr, *d_lp = nullptr;
+  auto release = [&]() { hipFree(d_req); hipFree(d_gen); hipFree(d_out); hipFree(d_n); hipFree(d_gm); hipFree(d_lp); };
+  auto run = [&]() -> int {
+    HIPCHK(c, hipMalloc((void**)&d_req, n_rows * sizeof(long long)));
+    HIPCHK(c, hipMalloc((void**)&d_gen, n_rows * sizeof(int)));
+    HIPCHK(c, hipMalloc((void**)&d_out, n_rows * sizeof(int)));
+    HIPCHK(c, hipMalloc((void**)&d_n, 2 * sizeof(int)));
+    if (out_logprobs) HIPCHK(c, hipMalloc((void**)&d_lp, n_rows * sizeof(float)));
+    HIPCHK(c, hipMemset(d_n, 0, 2 * sizeof(int)));
+    HIPCHK(c, hipMemcpy(d_req, request_ids, n_rows * sizeof(long long), hipMemcpyHostToDevice));
+    HIPCHK(c, hipMemcpy(d_gen, gen_index, n_rows * sizeof(int), hipMemcpyHostToDevice));
+    HIPCHK(c, hipMemcpy(d_n, &n_rows, sizeof(int), hipMemcpyHostToDevice));
+    RowCtx rc{nullptr, nullptr, reinterpret_cast<const int2*>(d_n), n_rows};
+    const SamplerCfg sc = sampler_cfg(c);
+    // same candidate search as the rollout path: group maxima first when the vocabulary allows
+    const int grp = lmhead_group_cols();
+    if (c->dm.vocab % grp == 0) {
+      HIPCHK(c, hipMalloc((void**)&d_gm, (size_t)n_rows * (c->dm.vocab / grp) * sizeof(float)));
+      launch_group_max(c->stream, logits, n_rows, c->dm.vocab, grp, d_gm);
+    }
+    launch_sample(c->stream, rc, c->ds, nullptr, logits, c->dm.vocab, sc, Watch{}, 0, d_req, d_gen, d_out, d_gm, grp, d_lp);
+    HIPCHK(c, hipStreamSynchronize(c->stream));
+    HIPCHK(c, hipMemcpy(out_tokens, d_out, n_rows * sizeof(int), hipMemcpyDeviceToHost));
+    if (out_logprobs) HIPCHK(c, hipMemcpy(out_logprobs, d_lp, n_rows * sizeof(float), hipMemcpyDeviceToHost));
+    return APRIL_OK;
+  };
+  const int rc_ = run();
+  release();
+  return rc_;
+}
+int april_sample_rows(april_ctx* c, const float* logits, int32_t n_rows, const int64_t* request_ids,
+                      const int32_t* gen_index, int32_t* out_tokens) {
+  return sample_rows_impl(c, logits, n_rows, request_ids, gen_index, out_tokens, nullptr);
+}
+int april_sample_rows_logprobs(april_ctx* c, const float* logits, int32_t n_rows, const int64_t* request_ids,
+                               const int32_t* gen_index, int32_t* out_tokens, float* out_logprobs) {
+  if (!out_logprobs) return APRIL_EINVAL;
+  return sample_rows_impl(c, logits, n_rows, request_ids, gen_index, out_tokens, out_logprobs);
 }
 
 // The same sampler for callers that must not allocate: every temporary lives in this GPU's
@@ -1059,7 +1097,7 @@ int april_sample_rows_noalloc(april_ctx* c, const float* logits, int32_t n_rows,
   HIPCHK(c, hipMemcpyAsync(d_req, request_ids, n_rows * sizeof(long long), hipMemcpyHostToDevice, st));
   HIPCHK(c, hipMemcpyAsync(d_gen, gen_index, n_rows * sizeof(int), hipMemcpyHostToDevice, st));
   RowCtx rc{nullptr, nullptr, reinterpret_cast<const int2*>(d_n), n_rows};
-  SamplerCfg sc{c->cfg.sampler, c->cfg.top_k, c->cfg.temperature, (unsigned long long)c->cfg.seed};
+  const SamplerCfg sc = sampler_cfg(c);
   if (use_gm) launch_group_max(st, logits, n_rows, c->dm.vocab, grp, d_gm);
   launch_sample(st, rc, c->ds, nullptr, logits, c->dm.vocab, sc, Watch{}, 0, d_req, d_gen, d_out, d_gm, grp);
   HIPCHK(c, hipMemcpyAsync(out_tokens, d_out, n_rows * sizeof(int), hipMemcpyDeviceToHost, st));
@@ -1200,7 +1238,7 @@ int april_rollout_step(april_ctx* c, const april_request* new_reqs, int32_t n_ne
   int64_t prefill_tokens = 0, reprefill_tokens = 0;
   int n_resident = 0;
   std::vector<Entry> stay;              // buffered rollouts that could not be admitted (KV pool)
-  struct Upload { int slot; std::vector<int> tokens; std::vector<int> forced; bool has_forced; };
+  struct Upload { int slot; std::vector<int> tokens; std::vector<int> forced; bool has_forced; std::vector<float> logprobs; };
   std::vector<Upload> uploads;          // token arrays the device still needs
   std::vector<std::pair<int, Entry>> token_level;   // (slot, entry as resumed) of entries that came without a slot
   for (int i : stay_idx) stay.push_back(pend[i]);
@@ -1218,7 +1256,7 @@ int april_rollout_step(april_ctx* c, const april_request* new_reqs, int32_t n_ne
       std::vector<int> all(e.prompt);
       all.insert(all.end(), e.generated.begin(), e.generated.end());
       // parity mode: the slot's previous occupant may have left teacher-forced tokens behind
-      uploads.push_back({s, std::move(all), std::vector<int>(), c->ds.forced != nullptr});
+      uploads.push_back({s, std::move(all), std::vector<int>(), c->ds.forced != nullptr, e.logprobs});
       token_level.push_back({s, e});
     }
     SlotH& sh = c->slots[s];
@@ -1236,7 +1274,7 @@ int april_rollout_step(april_ctx* c, const april_request* new_reqs, int32_t n_ne
     sh.req = r.request_id; sh.prompt.assign(r.tokens, r.tokens + r.n_tokens); sh.prompt_len = r.n_tokens;
     sh.limit = r.forced_len > 0 ? std::min(r.forced_len, max_new) : max_new;
     sh.state = SLOT_PREFILL;
-    Upload u{s, sh.prompt, std::vector<int>(), c->ds.forced != nullptr};
+    Upload u{s, sh.prompt, std::vector<int>(), c->ds.forced != nullptr, std::vector<float>()};
     if (c->ds.forced && r.forced_tokens) u.forced.assign(r.forced_tokens, r.forced_tokens + std::min(r.n_forced_tokens, c->max_ctx));
     uploads.push_back(std::move(u));
     prefill_slots.push_back(s);
@@ -1257,6 +1295,8 @@ int april_rollout_step(april_ctx* c, const april_request* new_reqs, int32_t n_ne
   auto body = [&]() -> int {
   for (Upload& u : uploads) {
     HIPCHK(c, hipMemcpyAsync(c->ds.tokens + (size_t)u.slot * c->max_ctx, u.tokens.data(), u.tokens.size() * sizeof(int), hipMemcpyHostToDevice, st));
+    if (c->ds.logprob && !u.logprobs.empty())
+      HIPCHK(c, hipMemcpyAsync(c->ds.logprob + (size_t)u.slot * c->max_ctx, u.logprobs.data(), u.logprobs.size() * sizeof(float), hipMemcpyHostToDevice, st));
     if (u.has_forced) {
       launch_fill_i32(st, c->ds.forced + (size_t)u.slot * c->max_ctx, -1, (size_t)c->max_ctx);
       if (!u.forced.empty())
@@ -1486,6 +1526,7 @@ int april_rollout_step(april_ctx* c, const april_request* new_reqs, int32_t n_ne
 
   // delivery order: surplus of the last step (ascending id), then this step's finishers
   c->r_req.clear(); c->r_tokens.clear(); c->r_ntok.clear(); c->r_nres.clear(); c->r_tok_ptrs.clear();
+  c->r_logprobs.clear(); c->r_lp_ptrs.clear();
   nb = new_buffer(c);
   std::vector<int> release;             // slots whose rollout is returned now
   int delivered = 0;
@@ -1496,6 +1537,10 @@ int april_rollout_step(april_ctx* c, const april_request* new_reqs, int32_t n_ne
     if (sh.gen > 0)
       HIPCHK(c, hipMemcpyAsync(c->r_tokens.back().data(), c->ds.tokens + (size_t)s * c->max_ctx + sh.prompt_len,
                                (size_t)sh.gen * sizeof(int), hipMemcpyDeviceToHost, st));
+    c->r_logprobs.emplace_back(c->ds.logprob ? (size_t)sh.gen : 0);
+    if (c->ds.logprob && sh.gen > 0)
+      HIPCHK(c, hipMemcpyAsync(c->r_logprobs.back().data(), c->ds.logprob + (size_t)s * c->max_ctx,
+                               (size_t)sh.gen * sizeof(float), hipMemcpyDeviceToHost, st));
     c->r_ntok.push_back(sh.gen);
     c->r_nres.push_back(sh.n_resumes);
     release.push_back(s);
@@ -1506,6 +1551,7 @@ int april_rollout_step(april_ctx* c, const april_request* new_reqs, int32_t n_ne
       if (e.slot >= 0) { int rc = deliver_slot(e.slot); if (rc != APRIL_OK) return rc; }
       else {
         c->r_req.push_back(e.req); c->r_tokens.push_back(e.generated);
+        c->r_logprobs.push_back(c->ds.logprob ? e.logprobs : std::vector<float>());
         c->r_ntok.push_back((int)e.generated.size()); c->r_nres.push_back(e.n_resumes);
       }
       ++delivered;
@@ -1539,11 +1585,13 @@ int april_rollout_step(april_ctx* c, const april_request* new_reqs, int32_t n_ne
   std::sort(nb->entries.begin(), nb->entries.end(), [](const Entry& a, const Entry& b) { return a.req < b.req; });
 
   for (auto& v : c->r_tokens) c->r_tok_ptrs.push_back(v.data());
+  for (auto& v : c->r_logprobs) c->r_lp_ptrs.push_back(v.data());
   out->n_completed = delivered;
   out->request_id = (const int64_t*)c->r_req.data();
   out->tokens = c->r_tok_ptrs.data();
   out->n_tokens = c->r_ntok.data();
   out->n_resumes = c->r_nres.data();
+  out->logprobs = c->ds.logprob ? c->r_lp_ptrs.data() : nullptr;
   out->buffer = nb;
   out->n_new_consumed = n_admit;
   out->decode_iters = iters;
@@ -1579,6 +1627,7 @@ int april_rollout_step(april_ctx* c, const april_request* new_reqs, int32_t n_ne
   }
   if (nb) { retire_buffer(c, nb); nb = nullptr; }
   c->r_req.clear(); c->r_tokens.clear(); c->r_ntok.clear(); c->r_nres.clear(); c->r_tok_ptrs.clear();
+  c->r_logprobs.clear(); c->r_lp_ptrs.clear();
   const int S = c->n_slots;
   bool dev_ok = hipStreamSynchronize(st) == hipSuccess;
   std::vector<int> dgen(S), dstate(S), dnb(S);

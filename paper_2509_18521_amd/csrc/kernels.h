@@ -145,18 +145,22 @@ void launch_rope_table(hipStream_t st, float* cos_t, float* sin_t, int max_pos, 
 
 // --- sampler + per-rollout state update ---------------------------------------
 struct SamplerCfg {
-  int kind, top_k;
+  int kind, top_k;            // kind: 0 greedy, 1 top-k (+ nucleus), 2 categorical over the whole vocabulary
   float temperature;
   unsigned long long seed;
+  float top_p;                // nucleus cut of the top-k candidates; >= 1: none
 };
 // Rows here are sampling rows: sample_row_slot / sample_row_pos give the slot and the
 // position of the LAST fed token of each row.  update = 0: only write out_tokens
 // (standalone sampler; req_ids/gen_idx arrays given explicitly).
 // group_max (nullable): per row the maxima of groups of `group` consecutive logits, as
 // written by launch_gemm_mfma_logits; lets the sampler look at a few groups only.
+// out_logprobs (nullable, update = 0): log softmax(logits / temperature)[token]; with update = 1
+// the log-probability goes to s.logprob when that array exists.
 void launch_sample(hipStream_t st, RowCtx rc, Slots s, Ctrl* ctrl, const float* logits, int vocab,
                    SamplerCfg sc, Watch w, int update, const long long* req_ids,
-                   const int* gen_idx, int* out_tokens, const float* group_max, int group);
+                   const int* gen_idx, int* out_tokens, const float* group_max, int group,
+                   float* out_logprobs = nullptr);
 
 void launch_group_max(hipStream_t st, const float* logits, int n_rows, int V, int group, float* out);
 

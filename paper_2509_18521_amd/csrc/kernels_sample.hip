@@ -51,7 +51,46 @@ struct SampleShared {
   int sort_idx[MAX_TOPK];
   unsigned red_key[16];
   int red_idx[16];
+  double red_d[16];
+  float red_f[16];
+  double total_d;
+  float max_f;
 };
+
+// Block-wide maximum of vals[0..n) (all threads call; result in every thread).
+__device__ inline float block_max_f32(const float* vals, int n, SampleShared& sh) {
+  const int tid = threadIdx.x, lane = tid & 63, wid = tid >> 6;
+  float m = -INFINITY;
+  for (int i = tid; i < n; i += SAMPLE_THREADS) m = fmaxf(m, vals[i]);
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off, 64));
+  __syncthreads();
+  if (lane == 0) sh.red_f[wid] = m;
+  __syncthreads();
+  if (tid == 0) {
+    for (int x = 1; x < SAMPLE_THREADS / 64; ++x) m = fmaxf(m, sh.red_f[x]);
+    sh.max_f = m;
+  }
+  __syncthreads();
+  return sh.max_f;
+}
+// Block-wide sum of one double per thread (all threads call; result in every thread), added
+// in a fixed order: lanes by the shuffle tree, wavefronts in index order.
+__device__ inline double block_sum_f64(double v, SampleShared& sh) {
+  const int tid = threadIdx.x, lane = tid & 63, wid = tid >> 6;
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+  __syncthreads();
+  if (lane == 0) sh.red_d[wid] = v;
+  __syncthreads();
+  if (tid == 0) {
+    double t = sh.red_d[0];
+    for (int x = 1; x < SAMPLE_THREADS / 64; ++x) t += sh.red_d[x];
+    sh.total_d = t;
+  }
+  __syncthreads();
+  return sh.total_d;
+}
 
 // Key of the k-th largest of vals[0..n) (k <= n): 4 radix passes of 8 bits.  On return
 // sh.prefix = that key, sh.krem = how many entries equal to it belong to the top k,
@@ -149,7 +188,8 @@ __global__ __launch_bounds__(SAMPLE_THREADS) void sample_kernel(RowCtx rc, Slots
                                                                 const float* logits, int V, SamplerCfg sc,
                                                                 Watch w, int update, const long long* req_ids,
                                                                 const int* gen_idx, int* out_tokens,
-                                                                const float* group_max, int group) {
+                                                                const float* group_max, int group,
+                                                                float* out_logprobs) {
   const int r = blockIdx.x;
   ROW_GUARD(rc, r);
   const int tid = threadIdx.x, lane = tid & 63, wid = tid >> 6;
@@ -170,7 +210,7 @@ __global__ __launch_bounds__(SAMPLE_THREADS) void sample_kernel(RowCtx rc, Slots
   const int n_groups = group_max ? V / group : 0;
   const float* gm = group_max ? group_max + (size_t)r * n_groups : nullptr;
 
-  if (sc.kind == 0 || sc.top_k <= 1) {
+  if (sc.kind == 0 || (sc.kind == 1 && sc.top_k <= 1)) {
     // ---- greedy: maximum, lowest index on ties --------------------------------------
     if (gm) {
       const int gi = block_argmax(gm, n_groups, sh);               // lowest group holding the maximum
@@ -180,6 +220,50 @@ __global__ __launch_bounds__(SAMPLE_THREADS) void sample_kernel(RowCtx rc, Slots
     } else {
       block_argmax(lg, V, sh);
     }
+  } else if (sc.kind == 2) {
+    // ---- temperature sampling over the whole vocabulary: inverse CDF in index order ----------
+    // Thread t owns the indices [t * chunk, (t + 1) * chunk): its partial sum of exp((l - max) / T),
+    // an exclusive scan over the threads (wavefront scans, then wavefront totals in order), and the
+    // thread whose range holds the crossing of u * total walks its range.
+    const float M = gm ? block_max_f32(gm, n_groups, sh) : block_max_f32(lg, V, sh);
+    const double invT = 1.0 / (double)sc.temperature;
+    const int chunk = (V + SAMPLE_THREADS - 1) / SAMPLE_THREADS;
+    const int i0 = tid * chunk, i1 = (i0 + chunk < V) ? i0 + chunk : V;
+    double part = 0.0;
+    for (int i = i0; i < i1; ++i) part += exp(((double)lg[i] - (double)M) * invT);
+    double incl = part;                                     // inclusive scan inside the wavefront
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+      const double o = __shfl_up(incl, off, 64);
+      if (lane >= off) incl += o;
+    }
+    __syncthreads();
+    if (lane == 63) sh.red_d[wid] = incl;
+    __syncthreads();
+    double before = 0.0, total = 0.0;
+    for (int x = 0; x < SAMPLE_THREADS / 64; ++x) {
+      if (x < wid) before += sh.red_d[x];
+      total += sh.red_d[x];
+    }
+    const unsigned long long rid = (unsigned long long)req;
+    const unsigned w0 = philox4x32_10_word0((unsigned)(rid & 0xFFFFFFFFull), (unsigned)(rid >> 32),
+                                            (unsigned)g, 0u, (unsigned)(sc.seed & 0xFFFFFFFFull),
+                                            (unsigned)(sc.seed >> 32));
+    const double u = (double)(w0 >> 8) * (1.0 / 16777216.0);
+    const double target = u * total;                        // cumulative / total > u  <=>  cumulative > u * total
+    const double lo = before + incl - part, hi = before + incl;
+    if (tid == 0) sh.choice = V - 1;                        // rounding leaves no crossing: the last index
+    __syncthreads();
+    if (i0 < i1 && lo <= target && hi > target) {
+      double c = lo;
+      int pick = i1 - 1;
+      for (int i = i0; i < i1; ++i) {
+        c += exp(((double)lg[i] - (double)M) * invT);
+        if (c > target) { pick = i; break; }
+      }
+      sh.choice = pick;
+    }
+    __syncthreads();
   } else {
     const int k = sc.top_k < V ? (sc.top_k < MAX_TOPK ? sc.top_k : MAX_TOPK) : (V < MAX_TOPK ? V : MAX_TOPK);
     bool have = false;
@@ -281,8 +365,16 @@ __global__ __launch_bounds__(SAMPLE_THREADS) void sample_kernel(RowCtx rc, Slots
         const double o = __shfl_up(c, off, 64);
         if (tid >= off) c += o;
       }
-      const unsigned long long hit = __ballot(tid < n && c > u);
-      if (tid == 0) sh.choice = sh.sort_idx[hit ? __ffsll((long long)hit) - 1 : n - 1];
+      int keep = n;
+      double tot = 1.0;
+      if (sc.top_p > 0.f && sc.top_p < 1.f) {
+        // nucleus: the shortest prefix whose cumulative probability reaches top_p
+        const unsigned long long reach = __ballot(tid < n && c >= (double)sc.top_p);
+        keep = reach ? __ffsll((long long)reach) : n;
+        tot = __shfl(c, keep - 1, 64);                      // mass of the nucleus: renormalise by it
+      }
+      const unsigned long long hit = __ballot(tid < keep && c > u * tot);
+      if (tid == 0) sh.choice = sh.sort_idx[hit ? __ffsll((long long)hit) - 1 : keep - 1];
     }
     __syncthreads();
   }
@@ -306,15 +398,29 @@ __global__ __launch_bounds__(SAMPLE_THREADS) void sample_kernel(RowCtx rc, Slots
     }
   }
 
+  // the token that is appended: the sampler's choice, or the teacher-forced one (parity mode)
+  int tok_final = sampled;
+  if (update && s.forced != nullptr) {
+    const int f = s.forced[(size_t)slot * s.max_ctx + g];
+    if (f >= 0) tok_final = f;
+  }
+  // ---- log-probability of that token under softmax(logits / T) over the whole vocabulary ----
+  float* lp_dst = update ? (s.logprob ? s.logprob + (size_t)slot * s.max_ctx + g : nullptr)
+                         : (out_logprobs ? out_logprobs + r : nullptr);
+  if (lp_dst != nullptr) {
+    const float M = gm ? block_max_f32(gm, n_groups, sh) : block_max_f32(lg, V, sh);
+    const float invT = 1.0f / sc.temperature;
+    double part = 0.0;
+    for (int i = tid; i < V; i += SAMPLE_THREADS) part += (double)__expf((lg[i] - M) * invT);
+    const double Z = block_sum_f64(part, sh);
+    if (tid == 0) *lp_dst = (float)((double)((lg[tok_final] - M) * invT) - log(Z));
+  }
+
   if (tid == 0) {
     if (!update) {
       out_tokens[r] = sampled;
     } else {
-      int tok = sampled;
-      if (s.forced != nullptr) {
-        const int f = s.forced[(size_t)slot * s.max_ctx + g];
-        if (f >= 0) tok = f;
-      }
+      int tok = tok_final;
       s.tokens[(size_t)slot * s.max_ctx + pos + 1] = tok;
       s.gen[slot] = g + 1;
       s.kv_len[slot] = pos + 1;
@@ -349,9 +455,9 @@ void launch_group_max(hipStream_t st, const float* logits, int n_rows, int V, in
 
 void launch_sample(hipStream_t st, RowCtx rc, Slots s, Ctrl* ctrl, const float* logits, int vocab, SamplerCfg sc,
                    Watch w, int update, const long long* req_ids, const int* gen_idx, int* out_tokens,
-                   const float* group_max, int group) {
+                   const float* group_max, int group, float* out_logprobs) {
   hipLaunchKernelGGL(sample_kernel, dim3(rc.max_rows), dim3(SAMPLE_THREADS), 0, st, rc, s, ctrl, logits, vocab,
-                     sc, w, update, req_ids, gen_idx, out_tokens, group_max, group);
+                     sc, w, update, req_ids, gen_idx, out_tokens, group_max, group, out_logprobs);
 }
 
 }  // namespace april

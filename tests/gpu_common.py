@@ -21,12 +21,13 @@ def sampler_name(w):
 
 
 def make_engine(w, weights, *, debug=False, max_inflight=None, max_ctx=None, temperature=1.0, eos=-1,
-                kv_pool_bytes=0):
+                kv_pool_bytes=0, top_p=0.0, logprobs=False, sampler=None):
     s = w.shape
     cfg = ap.make_cfg(s, max_inflight=max_inflight or (w.n_overprovision + 8),
                       max_ctx=max_ctx or (w.prompt_len + w.max_new + 16),
-                      sampler=w.sampler, top_k=max(w.top_k, 1), temperature=temperature, seed=w.seed,
-                      eos_token=eos, debug_logits=debug, kv_pool_bytes=kv_pool_bytes)
+                      sampler=w.sampler if sampler is None else sampler, top_k=max(w.top_k, 1),
+                      temperature=temperature, seed=w.seed, eos_token=eos, debug_logits=debug,
+                      kv_pool_bytes=kv_pool_bytes, top_p=top_p, logprobs=logprobs)
     return ap.april_init(cfg, ap.pack_weights(s, weights))
 
 
@@ -54,6 +55,8 @@ def run_gpu(ctx, reqs, n_target, n_over, max_new, steps, *, forced=None, between
                         buffer=[(p["request_id"], len(p["generated"]), p["done"]) for p in view],
                         buffer_tokens={p["request_id"]: p["generated"].tolist() for p in view},
                         sum_live=res.sum_live, res=res, n_preempted=res.n_preempted,
+                        logprobs=None if res.logprobs is None else [l.tolist() for l in res.logprobs],
+                        buffer_logprobs={p["request_id"]: p["logprobs"] for p in view},
                         kv_resident={p["request_id"]: p["kv_resident"] for p in view}))
         buf = res.buffer
         if between is not None:
@@ -63,9 +66,9 @@ def run_gpu(ctx, reqs, n_target, n_over, max_new, steps, *, forced=None, between
 
 
 def run_oracle(w, weights, reqs, n_target, n_over, max_new, steps, *, keep_logits=False, temperature=1.0,
-               eos=-1, drop_kv=False, pool=None):
-    eng = OracleRollouts(Decoder(w.shape, weights), sampler_name(w), top_k=max(w.top_k, 1),
-                         temperature=temperature, seed=w.seed, eos_token=eos, keep_logits=keep_logits)
+               eos=-1, drop_kv=False, pool=None, top_p=1.0, sampler=None):
+    eng = OracleRollouts(Decoder(w.shape, weights), sampler or sampler_name(w), top_k=max(w.top_k, 1),
+                         temperature=temperature, seed=w.seed, eos_token=eos, keep_logits=keep_logits, top_p=top_p)
     rolls = [eng.make_rollout(r.request_id, r.tokens, r.forced_len) for r in reqs]
     nxt, out = 0, []
     for _ in range(steps):
@@ -78,6 +81,7 @@ def run_oracle(w, weights, reqs, n_target, n_over, max_new, steps, *, keep_logit
                         iters=o.decode_iters, generated=o.tokens_generated,
                         buffer=[(r.request_id, r.gen, int(r.done)) for r in o.buffer],
                         buffer_tokens={r.request_id: list(r.tokens) for r in o.buffer},
+                        logprobs=[list(r.user.get("logprobs", [])) for r in o.completed],
                         sum_live=sum(o.live_per_iter), n_preempted=len(o.preempted),
                         kv_resident={r.request_id: int(r.kv > 0) for r in o.buffer}))
     return out, eng

@@ -161,6 +161,48 @@ def test_reprefill_fallback_and_export_import():
             ap().april_destroy(c)
 
 
+@pytest.mark.parametrize("sampler,top_k,top_p", [("greedy", 0, 0.0), ("topk", 8, 0.7), ("categorical", 0, 0.0)])
+def test_paper_sampling_settings_and_returned_logprobs(sampler, top_k, top_p):
+    """The paper's rollout settings (appendix: temperature 0.8; evaluation top_p 0.7) through
+    the whole path, with the per-token log-probabilities a trainer needs returned next to the
+    tokens: scheduling bit-exact, tokens equal to the oracle's up to the first position where the
+    oracle's own decision is within tolerance of flipping, log-probabilities within 5e-4 there.
+    A token-level export / import round trip between steps must carry the log-probabilities."""
+    kinds = {"greedy": ai.SAMPLER_GREEDY, "topk": ai.SAMPLER_TOPK, "categorical": ai.SAMPLER_CATEGORICAL}
+    w = small_fp32_workload(kinds[sampler] if sampler != "categorical" else ai.SAMPLER_GREEDY, top_k)
+    weights = ai.make_weights(w.shape, w.seed)
+    reqs = ai.make_requests(w, ai.requests_needed(w))
+    T = float(np.float32(0.8))
+    want, eng = run_oracle(w, weights, reqs, w.n_target, w.n_overprovision, w.max_new, w.steps, keep_logits=True,
+                           temperature=T, top_p=float(np.float32(top_p)) if top_p else 1.0, sampler=sampler)
+    ctx = make_engine(w, weights, temperature=0.8, top_p=top_p, logprobs=True, sampler=kinds[sampler])
+
+    def roundtrip(c, buf):
+        view = ap().april_buffer_export(c, buf)
+        assert all(p["logprobs"] is not None and len(p["logprobs"]) == len(p["generated"])
+                   for p in view if len(p["generated"]))
+        ap().april_buffer_free(c, buf)
+        return ap().april_buffer_import(c, view)
+    try:
+        got = run_gpu(ctx, reqs, w.n_target, w.n_overprovision, w.max_new, w.steps, between=roundtrip)
+        assert_schedule_equal(got, want)
+        compared, same_rollouts = 0, 0
+        for g, o in zip(got, want):
+            assert g["logprobs"] is not None
+            for rid, gt, ot, glp, olp in zip(g["ids"], g["tokens"], o["tokens"], g["logprobs"], o["logprobs"]):
+                assert len(glp) == len(gt) == len(olp)
+                for i, (a, b) in enumerate(zip(gt, ot)):
+                    if a != b:
+                        break                       # sampling near a boundary: the two runs part here
+                    assert abs(glp[i] - olp[i]) < 5e-4, (rid, i, glp[i], olp[i])
+                    assert glp[i] <= 1e-6
+                    compared += 1
+                same_rollouts += gt == ot
+        assert compared > 300 and same_rollouts >= len(got) * w.n_target // 2
+    finally:
+        ap().april_destroy(ctx)
+
+
 @pytest.mark.parametrize("name", list(ai.WORKLOADS))
 def test_scheduling_bit_exact_at_all_five_configs(name):
     """Scheduling depends only on the forced lengths, so each configuration's N, N',

@@ -25,12 +25,22 @@ def _run(cmd, verbose):
         print(out)
 
 
-def build(verbose=True, only=None):
-    """Compiles every source (or the ones named in `only`; the other objects must exist) and links."""
+def build(verbose=True, incremental=False):
+    """Compiles every source and links.  incremental: only the sources whose object is older than
+    the source or than any header (development shortcut; the default compiles everything)."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     os.makedirs(OBJ_DIR, exist_ok=True)
     objs = {s: os.path.join(OBJ_DIR, s.replace(".hip", ".o")) for s in SOURCES}
-    todo = [s for s in SOURCES if only is None or s in only or not os.path.exists(objs[s])]
+    headers = [os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith(".h")]
+    headers.append(os.path.join(os.path.dirname(PKG), "include", "april.h"))
+    newest_header = max(os.path.getmtime(h) for h in headers)
+
+    def stale(s):
+        if not incremental or not os.path.exists(objs[s]):
+            return True
+        t = os.path.getmtime(objs[s])
+        return t < os.path.getmtime(os.path.join(CSRC, s)) or t < newest_header
+    todo = [s for s in SOURCES if stale(s)]
     with ThreadPoolExecutor(max_workers=min(8, len(todo) or 1)) as ex:
         list(ex.map(lambda s: _run([hipcc] + FLAGS + ["-c", os.path.join(CSRC, s), "-o", objs[s]], verbose), todo))
     _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC"] + [objs[s] for s in SOURCES] + ["-o", LIB], verbose)
@@ -38,5 +48,5 @@ def build(verbose=True, only=None):
 
 
 if __name__ == "__main__":
-    build(only=sys.argv[1:] or None)
+    build(incremental="--incremental" in sys.argv[1:])
     print("built", LIB)

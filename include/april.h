@@ -196,6 +196,17 @@ int april_buffer_drop_kv(april_ctx* ctx, april_buffer* buffer);
 /* Drop a buffer and everything it holds. */
 void april_buffer_free(april_ctx* ctx, april_buffer* buffer);
 
+/* Policy update between steps (Eq. 1: the trainer moves theta_k to theta_{k+1} after every
+ * step, and rollouts parked under theta_k are continued under theta_{k+1}: Section 2.2,
+ * trajectories of a mixed policy).  `weights` as for april_init (same names and sizes, host or
+ * device, borrowed during the call); the library overwrites its own copies in place.
+ * keep_kv = 0: the K/V of every parked rollout was computed under the old weights, so its pages
+ * are released and the rollout is re-prefilled under the new weights when it is resumed (its
+ * tokens are kept).  keep_kv = 1: the stale K/V stays and decoding simply goes on (cheaper, and
+ * an approximation: the measured alternative).  Call between steps only.  On an error the
+ * context's weights are undefined until a later call succeeds. */
+int april_update_weights(april_ctx* ctx, const april_tensor* weights, int32_t n_weights, int32_t keep_kv);
+
 /* Parity mode (cfg.debug_logits = 1): keep the fp32 logits that produced generated
  * tokens [first_gen, first_gen + n_gen) of request_id.  Call before the step that
  * generates them. */

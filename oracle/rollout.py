@@ -69,6 +69,16 @@ class OracleRollouts:
             r.pages = 0
             r.kv = 0
 
+    def update_weights(self, decoder, keep_kv=False, pool=None):
+        """The trainer has moved the policy (Eq. 1: theta_k -> theta_{k+1}); buffered rollouts
+        go on under the new one (Section 2.2, mixed-policy trajectories).  keep_kv = False: the
+        cached keys / values were computed under the old weights, so they are dropped and
+        recomputed from the tokens under the new weights when the rollout resumes.  keep_kv =
+        True: the stale cache stays and only new positions use the new weights."""
+        self.dec = decoder
+        if not keep_kv:
+            self.drop_kv(pool)
+
     @staticmethod
     def _forget_cache(r):
         r.user["cache"] = None

@@ -22,7 +22,7 @@ APRIL_KERNEL_CLASSES = 24
 
 EXPORTS = [
     "april_init", "april_rollout_step", "april_resume", "april_buffer_size", "april_buffer_export",
-    "april_buffer_import", "april_buffer_drop_kv", "april_buffer_free", "april_debug_watch",
+    "april_buffer_import", "april_buffer_drop_kv", "april_buffer_free", "april_update_weights", "april_debug_watch",
     "april_debug_logits", "april_sample_rows", "april_sample_rows_logprobs", "april_sample_rows_noalloc", "april_profile_enable", "april_profile_get",
     "april_profile_reset", "april_get_info", "april_last_error", "april_destroy",
 ]
@@ -111,6 +111,7 @@ def load_library():
     lib.april_buffer_drop_kv.argtypes = [vp, vp]
     lib.april_buffer_free.argtypes = [vp, vp]
     lib.april_buffer_free.restype = None
+    lib.april_update_weights.argtypes = [vp, C.POINTER(april_tensor), C.c_int32, C.c_int32]
     lib.april_debug_watch.argtypes = [vp, C.c_int64, C.c_int32, C.c_int32]
     lib.april_debug_logits.argtypes = [vp, C.c_int64, C.c_int32, C.POINTER(C.c_float), C.POINTER(C.c_int32)]
     lib.april_sample_rows.argtypes = [vp, vp, C.c_int32, C.POINTER(C.c_int64), C.POINTER(C.c_int32),
@@ -146,10 +147,9 @@ def _i32ptr(a: np.ndarray):
 # ---------------------------------------------------------------------------
 # same-name wrappers
 # ---------------------------------------------------------------------------
-def april_init(cfg: april_model_cfg, weights: Dict[str, object]) -> C.c_void_p:
-    """weights: name -> numpy array (host) or an object with .data_ptr()/.nbytes on the
-    GPU (e.g. a torch CUDA tensor).  Arrays are borrowed for the duration of the call."""
-    lib = load_library()
+def _tensor_table(weights: Dict[str, object]):
+    """name -> numpy array (host) or an object with .data_ptr() / .numel() / .element_size() on
+    the GPU (e.g. a torch CUDA tensor)  ->  (april_tensor array, objects to keep alive)."""
     arr = (april_tensor * len(weights))()
     keep = []
     for i, (name, w) in enumerate(weights.items()):
@@ -162,9 +162,21 @@ def april_init(cfg: april_model_cfg, weights: Dict[str, object]) -> C.c_void_p:
         else:
             keep.append(w)
             arr[i] = april_tensor(name, w.data_ptr(), w.numel() * w.element_size(), 1)
+    return arr, keep
+
+
+def april_init(cfg: april_model_cfg, weights: Dict[str, object]) -> C.c_void_p:
+    """weights: see _tensor_table.  Arrays are borrowed for the duration of the call."""
+    lib = load_library()
+    arr, keep = _tensor_table(weights)
     out = C.c_void_p()
     _check(None, lib.april_init(C.byref(cfg), arr, len(weights), C.byref(out)))
     return out
+
+
+def april_update_weights(ctx, weights: Dict[str, object], keep_kv: bool = False):
+    arr, keep = _tensor_table(weights)
+    _check(ctx, load_library().april_update_weights(ctx, arr, len(weights), 1 if keep_kv else 0))
 
 
 def april_destroy(ctx):

@@ -162,6 +162,7 @@ struct april_ctx {
   int graph_iters = 4;                       // iterations per replayed graph when consecutive ones share their bounds
                                              // (a graph boundary costs about 4 us on the device: 45.6 -> 45.7 k tokens/s)
 
+  int weight_version = 0;        // bumped by april_update_weights
   int device = 0;                // HIP device the context lives on
   unsigned char* scratch_dev = nullptr;   // this device's copy of the static scratch array
 
@@ -247,6 +248,113 @@ int fetch_tensor(april_ctx* c, const april_tensor* w, int n, const std::string& 
   HIPCHK(c, hipMemcpyAsync(dst, t->data, bytes, t->on_device ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice,
                            c->stream));
   if (!t->on_device) HIPCHK(c, hipStreamSynchronize(c->stream));   // the caller's buffer is only borrowed
+  return APRIL_OK;
+}
+
+// Copy every weight tensor to the device in the layout the kernels want.  First call (from
+// april_init): allocates the buffers.  Later calls (april_update_weights): the same buffers are
+// overwritten in place, so captured iteration graphs stay valid.
+int load_weights(april_ctx* c, const april_tensor* weights, int n_weights) {
+  const april_model_cfg& g = c->cfg;
+  const bool moe = c->moe, first = c->layers.empty();
+  const int nq = g.n_q_heads * g.head_dim, nkv = g.n_kv_heads * g.head_dim, nqkv = nq + 2 * nkv;
+  const int d = g.d_model, F = g.d_ffn, V = g.vocab;
+  const size_t e = c->esz;
+  // staging buffer for one matrix at a time: the largest of every matrix that goes through it
+  size_t stage_bytes = std::max({(size_t)V * d, (size_t)F * d, (size_t)nqkv * d, (size_t)d * nq}) * e;
+  if (moe) stage_bytes = std::max({stage_bytes, (size_t)g.n_experts * g.d_expert_ffn * d * e, (size_t)g.n_experts * d * e});
+  void* stage = nullptr;
+  if (c->use_mfma && hipMalloc(&stage, stage_bytes) != hipSuccess) return fail(c, APRIL_ENOMEM, "staging buffer for the weights (%zu bytes)", stage_bytes);
+  struct StageGuard { void*& p; ~StageGuard() { if (p) hipFree(p); p = nullptr; } } guard{stage};
+#define TRYW(x) do { int rc_ = (x); if (rc_ != APRIL_OK) return rc_; } while (0)
+  // allocate on the first call only
+  auto walloc = [&](void** p, size_t bytes) -> int { return *p ? APRIL_OK : dev_alloc_bytes(c, p, bytes, false); };
+  auto wallocf = [&](float** p, size_t n) -> int { return *p ? APRIL_OK : dev_alloc(c, p, n, false); };
+  auto wallocb = [&](bf16_t** p, size_t n) -> int { return *p ? APRIL_OK : dev_alloc(c, p, n, false); };
+
+  TRYW(walloc(&c->tok_emb, (size_t)V * d * e));
+  TRYW(fetch_tensor(c, weights, n_weights, "tok_emb", c->tok_emb, (size_t)V * d * e));
+  TRYW(wallocf(&c->final_norm, d));
+  TRYW(fetch_tensor(c, weights, n_weights, "final_norm", c->final_norm, d * sizeof(float)));
+  if (first) {
+    c->weight_bytes = (int64_t)V * d * e;
+    c->decode_weight_bytes = 0;
+    c->layers.resize(g.n_layers);
+  }
+  const bool keep_plain = !c->use_mfma;
+  // Fetch a matrix into `plain` (kept) or into the staging buffer, and re-lay it for MFMA.
+  auto load_matrix = [&](const std::string& name, int N, int K, void* plain_dst, bf16_t** shuffled) -> int {
+    void* dstp = keep_plain ? plain_dst : stage;
+    int rc = fetch_tensor(c, weights, n_weights, name, dstp, (size_t)N * K * e);
+    if (rc != APRIL_OK) return rc;
+    if (c->use_mfma && shuffled) {
+      rc = wallocb(shuffled, (size_t)N * K);
+      if (rc != APRIL_OK) return rc;
+      launch_shuffle_weights(c->stream, (const bf16_t*)dstp, *shuffled, N, K);
+      HIPCHK(c, hipStreamSynchronize(c->stream));
+    }
+    return APRIL_OK;
+  };
+  for (int l = 0; l < g.n_layers; ++l) {
+    LayerW& L = c->layers[l];
+    const std::string sl = "." + std::to_string(l);
+    TRYW(wallocf(&L.attn_norm, d));
+    TRYW(wallocf(&L.mlp_norm, d));
+    TRYW(fetch_tensor(c, weights, n_weights, "attn_norm" + sl, L.attn_norm, d * sizeof(float)));
+    TRYW(fetch_tensor(c, weights, n_weights, "mlp_norm" + sl, L.mlp_norm, d * sizeof(float)));
+    // q, k, v concatenated along the output dimension
+    void* qkv_dst = nullptr;
+    if (keep_plain) { TRYW(walloc(&L.wqkv, (size_t)nqkv * d * e)); qkv_dst = L.wqkv; }
+    else qkv_dst = stage;
+    TRYW(fetch_tensor(c, weights, n_weights, "wq" + sl, qkv_dst, (size_t)nq * d * e));
+    TRYW(fetch_tensor(c, weights, n_weights, "wk" + sl, (char*)qkv_dst + (size_t)nq * d * e, (size_t)nkv * d * e));
+    TRYW(fetch_tensor(c, weights, n_weights, "wv" + sl, (char*)qkv_dst + (size_t)(nq + nkv) * d * e, (size_t)nkv * d * e));
+    if (c->use_mfma) {
+      TRYW(wallocb(&L.wqkv_s, (size_t)nqkv * d));
+      launch_shuffle_weights(c->stream, (const bf16_t*)qkv_dst, L.wqkv_s, nqkv, d);
+      HIPCHK(c, hipStreamSynchronize(c->stream));
+    }
+    if (moe) {
+      const int E = g.n_experts, Fe = g.d_expert_ffn;
+      TRYW(load_matrix("wo" + sl, d, nq, nullptr, &L.wo_s));
+      TRYW(load_matrix("router" + sl, E, d, nullptr, &L.router_s));
+      TRYW(load_matrix("e_gate" + sl, E * Fe, d, nullptr, &L.eg_s));
+      TRYW(load_matrix("e_up" + sl, E * Fe, d, nullptr, &L.eu_s));
+      TRYW(load_matrix("e_down" + sl, E * d, Fe, nullptr, &L.ed_s));
+      if (first) {
+        c->decode_weight_bytes += ((int64_t)nqkv * d + (int64_t)d * nq + (int64_t)E * d) * e + 2 * d * 4;
+        c->weight_bytes += (int64_t)3 * E * Fe * d * e;
+      }
+      continue;
+    }
+    if (keep_plain) {
+      TRYW(walloc(&L.wo, (size_t)d * nq * e));
+      TRYW(walloc(&L.wgu, (size_t)2 * F * d * e));
+      TRYW(walloc(&L.wd, (size_t)d * F * e));
+      TRYW(load_matrix("wo" + sl, d, nq, L.wo, nullptr));
+      TRYW(load_matrix("w_gate" + sl, F, d, L.wgu, nullptr));
+      TRYW(load_matrix("w_up" + sl, F, d, (char*)L.wgu + (size_t)F * d * e, nullptr));
+      TRYW(load_matrix("w_down" + sl, d, F, L.wd, nullptr));
+    } else {
+      TRYW(load_matrix("wo" + sl, d, nq, nullptr, &L.wo_s));
+      TRYW(load_matrix("w_gate" + sl, F, d, nullptr, &L.wg_s));
+      TRYW(load_matrix("w_up" + sl, F, d, nullptr, &L.wu_s));
+      TRYW(load_matrix("w_down" + sl, d, F, nullptr, &L.wd_s));
+    }
+    if (first) c->decode_weight_bytes += ((int64_t)nqkv * d + (int64_t)d * nq + (int64_t)3 * F * d) * e + 2 * d * 4;
+  }
+  if (keep_plain) {
+    TRYW(walloc(&c->lm_head, (size_t)V * d * e));
+    TRYW(load_matrix("lm_head", V, d, c->lm_head, nullptr));
+  } else {
+    TRYW(load_matrix("lm_head", V, d, nullptr, &c->lm_head_s));
+  }
+  if (first) {
+    c->decode_weight_bytes += (int64_t)V * d * e + d * 4;
+    c->weight_bytes += c->decode_weight_bytes;
+  }
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+#undef TRYW
   return APRIL_OK;
 }
 
@@ -597,90 +705,8 @@ int april_init(const april_model_cfg* cfg, const april_tensor* weights, int32_t 
   c->scratch_dev = g_scratch_ptr[c->device];
 
   // ---- weights ------------------------------------------------------------------
+  TRY(load_weights(c, weights, n_weights));
   const size_t e = c->esz;
-  // staging buffer for one matrix at a time: the largest of every matrix that goes through it
-  size_t stage_bytes = std::max({(size_t)V * d, (size_t)F * d, (size_t)nqkv * d, (size_t)d * nq}) * e;
-  if (moe) stage_bytes = std::max({stage_bytes, (size_t)g.n_experts * g.d_expert_ffn * d * e, (size_t)g.n_experts * d * e});
-  void* stage = nullptr;
-  if (c->use_mfma) HIPTRY(hipMalloc(&stage, stage_bytes));
-  auto free_stage = [&]() { if (stage) { hipFree(stage); stage = nullptr; } };
-#define TRYW(x) do { int rc_ = (x); if (rc_ != APRIL_OK) { free_stage(); return bail(rc_); } } while (0)
-
-  TRYW(dev_alloc_bytes(c, &c->tok_emb, (size_t)V * d * e, false));
-  TRYW(fetch_tensor(c, weights, n_weights, "tok_emb", c->tok_emb, (size_t)V * d * e));
-  TRYW(dev_alloc(c, &c->final_norm, d, false));
-  TRYW(fetch_tensor(c, weights, n_weights, "final_norm", c->final_norm, d * sizeof(float)));
-  c->weight_bytes = (int64_t)V * d * e;
-  c->layers.resize(g.n_layers);
-  const bool keep_plain = !c->use_mfma;
-  // Fetch a matrix into `plain` (kept) or into the staging buffer, and re-lay it for MFMA.
-  auto load_matrix = [&](const std::string& name, int N, int K, void* plain_dst, bf16_t** shuffled) -> int {
-    void* dstp = keep_plain ? plain_dst : stage;
-    int rc = fetch_tensor(c, weights, n_weights, name, dstp, (size_t)N * K * e);
-    if (rc != APRIL_OK) return rc;
-    if (c->use_mfma && shuffled) {
-      rc = dev_alloc(c, shuffled, (size_t)N * K, false);
-      if (rc != APRIL_OK) return rc;
-      launch_shuffle_weights(c->stream, (const bf16_t*)dstp, *shuffled, N, K);
-      HIPCHK(c, hipStreamSynchronize(c->stream));
-    }
-    return APRIL_OK;
-  };
-  for (int l = 0; l < g.n_layers; ++l) {
-    LayerW& L = c->layers[l];
-    const std::string sl = "." + std::to_string(l);
-    TRYW(dev_alloc(c, &L.attn_norm, d, false));
-    TRYW(dev_alloc(c, &L.mlp_norm, d, false));
-    TRYW(fetch_tensor(c, weights, n_weights, "attn_norm" + sl, L.attn_norm, d * sizeof(float)));
-    TRYW(fetch_tensor(c, weights, n_weights, "mlp_norm" + sl, L.mlp_norm, d * sizeof(float)));
-    // q, k, v concatenated along the output dimension
-    void* qkv_dst = nullptr;
-    if (keep_plain) { TRYW(dev_alloc_bytes(c, &L.wqkv, (size_t)nqkv * d * e, false)); qkv_dst = L.wqkv; }
-    else qkv_dst = stage;
-    TRYW(fetch_tensor(c, weights, n_weights, "wq" + sl, qkv_dst, (size_t)nq * d * e));
-    TRYW(fetch_tensor(c, weights, n_weights, "wk" + sl, (char*)qkv_dst + (size_t)nq * d * e, (size_t)nkv * d * e));
-    TRYW(fetch_tensor(c, weights, n_weights, "wv" + sl, (char*)qkv_dst + (size_t)(nq + nkv) * d * e, (size_t)nkv * d * e));
-    if (c->use_mfma) {
-      TRYW(dev_alloc(c, &L.wqkv_s, (size_t)nqkv * d, false));
-      launch_shuffle_weights(c->stream, (const bf16_t*)qkv_dst, L.wqkv_s, nqkv, d);
-      HIPTRY(hipStreamSynchronize(c->stream));
-    }
-    if (moe) {
-      const int E = g.n_experts, Fe = g.d_expert_ffn;
-      TRYW(load_matrix("wo" + sl, d, nq, nullptr, &L.wo_s));
-      TRYW(load_matrix("router" + sl, E, d, nullptr, &L.router_s));
-      TRYW(load_matrix("e_gate" + sl, E * Fe, d, nullptr, &L.eg_s));
-      TRYW(load_matrix("e_up" + sl, E * Fe, d, nullptr, &L.eu_s));
-      TRYW(load_matrix("e_down" + sl, E * d, Fe, nullptr, &L.ed_s));
-      c->decode_weight_bytes += ((int64_t)nqkv * d + (int64_t)d * nq + (int64_t)E * d) * e + 2 * d * 4;
-      c->weight_bytes += (int64_t)3 * E * Fe * d * e;
-      continue;
-    }
-    if (keep_plain) {
-      TRYW(dev_alloc_bytes(c, &L.wo, (size_t)d * nq * e, false));
-      TRYW(dev_alloc_bytes(c, &L.wgu, (size_t)2 * F * d * e, false));
-      TRYW(dev_alloc_bytes(c, &L.wd, (size_t)d * F * e, false));
-      TRYW(load_matrix("wo" + sl, d, nq, L.wo, nullptr));
-      TRYW(load_matrix("w_gate" + sl, F, d, L.wgu, nullptr));
-      TRYW(load_matrix("w_up" + sl, F, d, (char*)L.wgu + (size_t)F * d * e, nullptr));
-      TRYW(load_matrix("w_down" + sl, d, F, L.wd, nullptr));
-    } else {
-      TRYW(load_matrix("wo" + sl, d, nq, nullptr, &L.wo_s));
-      TRYW(load_matrix("w_gate" + sl, F, d, nullptr, &L.wg_s));
-      TRYW(load_matrix("w_up" + sl, F, d, nullptr, &L.wu_s));
-      TRYW(load_matrix("w_down" + sl, d, F, nullptr, &L.wd_s));
-    }
-    c->decode_weight_bytes += ((int64_t)nqkv * d + (int64_t)d * nq + (int64_t)3 * F * d) * e + 2 * d * 4;
-  }
-  if (keep_plain) {
-    TRYW(dev_alloc_bytes(c, &c->lm_head, (size_t)V * d * e, false));
-    TRYW(load_matrix("lm_head", V, d, c->lm_head, nullptr));
-  } else {
-    TRYW(load_matrix("lm_head", V, d, nullptr, &c->lm_head_s));
-  }
-  free_stage();
-  c->decode_weight_bytes += (int64_t)V * d * e + d * 4;
-  c->weight_bytes += c->decode_weight_bytes;
 
   // ---- scheduler state ------------------------------------------------------------
   const int S = g.max_inflight;
@@ -991,6 +1017,28 @@ void april_buffer_free(april_ctx* c, april_buffer* buffer) {
   free_slot_pages(c, ids);
   for (int s : ids) c->slots[s] = SlotH();
   retire_buffer(c, b);
+}
+
+// New policy weights (Eq. 1: theta_{k+1}); rollouts that were parked under the old policy go on
+// under the new one (Section 2.2, mixed-policy trajectories).
+int april_update_weights(april_ctx* c, const april_tensor* weights, int32_t n_weights, int32_t keep_kv) {
+  if (!c || !weights || n_weights <= 0) return APRIL_EINVAL;
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  { int rc = load_weights(c, weights, n_weights); if (rc != APRIL_OK) return rc; }
+  if (!keep_kv) {
+    // K/V computed under the old weights are not the new policy's: every parked or pending
+    // rollout gives its pages back and is re-prefilled when it is resumed
+    std::vector<int> ids;
+    for (int s = 0; s < c->n_slots; ++s)
+      if (c->slots[s].state != SLOT_FREE && c->slots[s].n_blocks > 0) ids.push_back(s);
+    for (size_t i = 0; i < ids.size(); i += 2048) {
+      std::vector<int> part(ids.begin() + i, ids.begin() + std::min(ids.size(), i + 2048));
+      int rc = free_slot_pages(c, part);
+      if (rc != APRIL_OK) return rc;
+    }
+  }
+  c->weight_version += 1;
+  return APRIL_OK;
 }
 
 int april_debug_watch(april_ctx* c, int64_t request_id, int32_t first_gen, int32_t n_gen) {

@@ -203,6 +203,58 @@ def test_paper_sampling_settings_and_returned_logprobs(sampler, top_k, top_p):
         ap().april_destroy(ctx)
 
 
+@pytest.mark.parametrize("keep_kv", [False, True])
+def test_weight_update_between_steps(keep_kv):
+    """The policy changes after the second step (Eq. 1; Section 2.2: parked rollouts finish under
+    a newer policy).  keep_kv = False: every parked rollout is re-prefilled under the new weights;
+    keep_kv = True: its stale K/V stays.  Both against the oracle doing the same: schedule
+    bit-exact, greedy tokens identical wherever the oracle's top-2 margin exceeds the tolerance."""
+    from oracle.model import Decoder
+    from oracle.rollout import OracleRollouts
+    w = small_fp32_workload()
+    wa, wb = ai.make_weights(w.shape, w.seed), ai.make_weights(w.shape, w.seed + 100)
+    reqs = ai.make_requests(w, ai.requests_needed(w))
+    eng = OracleRollouts(Decoder(w.shape, wa), "greedy", seed=w.seed, keep_logits=True)
+    rolls = [eng.make_rollout(r.request_id, r.tokens, r.forced_len) for r in reqs]
+    want, nxt = [], 0
+    for k in range(4):
+        if k == 2:
+            eng.update_weights(Decoder(w.shape, wb), keep_kv=keep_kv)
+        o = eng.step(rolls[nxt:], w.n_target, w.n_overprovision, w.max_new)
+        nxt += o.n_new_consumed
+        want.append(dict(ids=[r.request_id for r in o.completed], tokens=[list(r.tokens) for r in o.completed],
+                         n_resumes=[r.n_resumes for r in o.completed], consumed=o.n_new_consumed,
+                         iters=o.decode_iters, generated=o.tokens_generated,
+                         buffer=[(r.request_id, r.gen, int(r.done)) for r in o.buffer]))
+    A = ap()
+    ctx = make_engine(w, wa)
+    try:
+        got, nxt = [], 0
+        for k in range(4):
+            if k == 2:
+                A.april_update_weights(ctx, A.pack_weights(w.shape, wb), keep_kv=keep_kv)
+            res = A.april_rollout_step(ctx, req_dicts(reqs[nxt:]), w.n_target, w.n_overprovision, w.max_new)
+            nxt += res.n_new_consumed
+            view = A.april_buffer_export(ctx, res.buffer)
+            got.append(dict(ids=res.request_id, tokens=[t.tolist() for t in res.tokens], n_resumes=res.n_resumes,
+                            consumed=res.n_new_consumed, iters=res.decode_iters, generated=res.tokens_generated,
+                            buffer=[(p["request_id"], len(p["generated"]), p["done"]) for p in view]))
+            if k == 2:
+                assert (res.reprefill_tokens > 0) == (not keep_kv)
+            A.april_resume(ctx, res.buffer)
+        assert_schedule_equal(got, want)
+        assert compare_free_running_tokens(got, want, eng, FP32_LOGIT_TOL) > 150
+        # the update really changed the policy: rollouts admitted after it differ from the old policy's
+        old_ctx = make_engine(w, wa)
+        try:
+            old = run_gpu(old_ctx, reqs, w.n_target, w.n_overprovision, w.max_new, 4)
+        finally:
+            A.april_destroy(old_ctx)
+        assert got[3]["tokens"] != old[3]["tokens"] and got[1]["tokens"] == old[1]["tokens"]
+    finally:
+        A.april_destroy(ctx)
+
+
 @pytest.mark.parametrize("name", list(ai.WORKLOADS))
 def test_scheduling_bit_exact_at_all_five_configs(name):
     """Scheduling depends only on the forced lengths, so each configuration's N, N',

@@ -57,8 +57,8 @@ class OracleRollouts:
             logits = self.dec.decode_step(r.tokens[-1], st["cache"])
         return self._pick(r, logits)
 
-    def make_rollout(self, request_id, prompt, forced_len):
-        return Rollout(request_id=request_id, prompt_len=len(prompt), forced_len=forced_len,
+    def make_rollout(self, request_id, prompt, forced_len, group=-1):
+        return Rollout(request_id=request_id, prompt_len=len(prompt), forced_len=forced_len, group=group,
                        user={"prompt": np.asarray(prompt), "cache": None})
 
     def drop_kv(self, pool=None):
@@ -83,11 +83,14 @@ class OracleRollouts:
     def _forget_cache(r):
         r.user["cache"] = None
 
-    def step(self, new_rollouts, n_target, n_overprovision, max_new, pool=None):
+    def step(self, new_rollouts, n_target, n_overprovision, max_new, pool=None, group_size=1):
         out = rollout_step(self.buffer, new_rollouts, n_target, n_overprovision, max_new,
                            next_token=self._next_token, eos_token=self.eos_token, pool=pool,
-                           on_preempt=self._forget_cache)
+                           on_preempt=self._forget_cache, group_size=group_size)
         self.buffer = out.buffer
         for r in out.completed:
             r.user["cache"] = None                    # finished: its KV is released
+        for r in out.buffer:
+            if r.done:
+                r.user["cache"] = None                # complete, waiting for delivery: no KV either
         return out

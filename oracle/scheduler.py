@@ -21,7 +21,12 @@ Readings where the paper is silent (each listed in the build's design notes):
     those that are complete; rollouts completing in the same iteration beyond
     N stay in the buffer flagged done and are returned first at the next step;
   - buffered rollouts are resumed in ascending request id;
-  - an exhausted KV pool (optional PagePool): see rollout_step.
+  - an exhausted KV pool (optional PagePool): see rollout_step;
+  - instance-level completion (Section 3.2.3, the paragraph on instance-level group control;
+    Section 3.1: 32 prompts x 8 samples): with group_size G > 1 every input instance is a
+    group of G rollouts, N and N' count rollouts in multiples of G, the step stops once N / G
+    GROUPS have all their members complete, and it returns exactly those groups (N rollouts);
+    complete members of an incomplete group wait in the buffer and leave with their group.
 
 Pins (tests/test_oracle_scheduler.py): an order-statistics closed form derived
 independently, the method's invariants (exactly N returned, nothing discarded,
@@ -47,6 +52,7 @@ class Rollout:
     user: object = None            # opaque per-rollout state of the sampler (e.g. a KV cache)
     kv: int = 0                    # positions whose K/V are cached (0: token-level only)
     pages: int = 0                 # KV pages held (only tracked with a PagePool)
+    group: int = -1                # input instance the rollout belongs to (group_size > 1)
 
 
 @dataclass
@@ -82,7 +88,8 @@ def rollout_step(buffer: List[Rollout], new_requests: List[Rollout], n_target: i
                  n_overprovision: int, max_new: int,
                  next_token: Optional[Callable[[Rollout], int]] = None,
                  eos_token: int = -1, pool: Optional[PagePool] = None,
-                 on_preempt: Optional[Callable[[Rollout], None]] = None) -> StepOutcome:
+                 on_preempt: Optional[Callable[[Rollout], None]] = None,
+                 group_size: int = 1) -> StepOutcome:
     """Run one step.  `buffer` is the previous step's buffer (may be empty);
     `new_requests` are admitted in order as needed.  `next_token(r)` produces the
     next token of rollout r (None: token value 0, scheduling only).
@@ -97,7 +104,12 @@ def rollout_step(buffer: List[Rollout], new_requests: List[Rollout], n_target: i
         freed, it keeps its tokens, stops progressing this step and is re-prefilled
         when resumed;
       * if nothing is left in flight before N rollouts are complete, the step ends
-        with fewer than N."""
+        with fewer than N.
+
+    group_size > 1: instance-level completion, see rollout_step_groups."""
+    if group_size > 1:
+        return rollout_step_groups(buffer, new_requests, n_target, n_overprovision, max_new, group_size,
+                                   next_token=next_token, eos_token=eos_token)
     resumed = sorted(buffer, key=lambda r: r.request_id)
     deliver = [r for r in resumed if r.done]
     inflight: List[Rollout] = []
@@ -188,3 +200,90 @@ def rollout_step(buffer: List[Rollout], new_requests: List[Rollout], n_target: i
     new_buffer = sorted(deliver[n_target:] + inflight + preempted + stay, key=lambda r: r.request_id)
     return StepOutcome(completed, new_buffer, iters, generated, consumed, live_hist,
                        [r.request_id for r in preempted])
+
+
+def rollout_step_groups(buffer: List[Rollout], new_requests: List[Rollout], n_target: int,
+                        n_overprovision: int, max_new: int, group_size: int,
+                        next_token: Optional[Callable[[Rollout], int]] = None,
+                        eos_token: int = -1) -> StepOutcome:
+    """One step with instance-level completion (Section 3.2.3; Section 3.1's 32 x 8 and 64 x 8).
+
+    Every rollout carries the id of its input instance (`group`); an instance has exactly
+    group_size rollouts, which arrive consecutively in new_requests and are admitted together.
+    n_target and n_overprovision count rollouts and are multiples of group_size.
+      * groups of the buffer whose members are all complete (surplus of the last step) are
+        delivered first, ascending group id;
+      * the unfinished members of the other buffered groups resume (ascending request id); their
+        complete members wait in the buffer;
+      * new groups are admitted until n_overprovision / group_size groups are in flight or
+        delivered;
+      * every iteration gives each in-flight rollout one token; a group is complete in the
+        iteration in which its last member completes; the step stops once n_target / group_size
+        groups are complete;
+      * returned: exactly those groups, in order of completion (iteration, then group id), the
+        members of a group in ascending request id; groups completing in the stopping iteration
+        beyond the target stay in the buffer and are delivered first next time.
+    KV-pool accounting is not combined with groups here (ample pool)."""
+    G = group_size
+    assert n_target % G == 0 and n_overprovision % G == 0 and n_target > 0
+    want_groups, over_groups = n_target // G, n_overprovision // G
+    members = {}
+    for r in sorted(buffer, key=lambda r: r.request_id):
+        members.setdefault(r.group, []).append(r)
+    deliver = []                                   # complete groups, in delivery order
+    for gid in sorted(members):
+        if len(members[gid]) == G and all(r.done for r in members[gid]):
+            deliver.append(gid)
+    inflight: List[Rollout] = []
+    open_groups = set()
+    for gid in sorted(members):
+        if gid in deliver:
+            continue
+        assert len(members[gid]) == G, "a buffered group lost a member"
+        open_groups.add(gid)
+        for r in members[gid]:
+            if not r.done:
+                r.n_resumes += 1
+                inflight.append(r)
+    inflight.sort(key=lambda r: r.request_id)
+    consumed = 0
+    while len(open_groups) < over_groups - len(deliver) and consumed + G <= len(new_requests):
+        grp = new_requests[consumed:consumed + G]
+        gid = grp[0].group
+        assert all(r.group == gid for r in grp) and gid not in members, "groups arrive whole and once"
+        consumed += G
+        members[gid] = list(grp)
+        open_groups.add(gid)
+        for r in grp:
+            r.limit = min(r.forced_len, max_new) if r.forced_len > 0 else max_new
+            r.kv = 0
+            inflight.append(r)
+    if len(deliver) + len(open_groups) < want_groups:
+        raise RuntimeError("starved: fewer than N / G groups can ever complete")
+    iters = generated = 0
+    live_hist = []
+    while len(deliver) < want_groups:
+        iters += 1
+        live_hist.append(len(inflight))
+        for r in inflight:
+            tok = next_token(r) if next_token is not None else 0
+            r.tokens.append(int(tok))
+            r.gen += 1
+            r.kv = r.prompt_len + r.gen - 1
+            generated += 1
+            if r.gen >= r.limit or (eos_token >= 0 and tok == eos_token):
+                r.done = True
+        inflight = [r for r in inflight if not r.done]
+        newly = sorted(g for g in open_groups if all(r.done for r in members[g]))
+        for g in newly:
+            open_groups.discard(g)
+        deliver.extend(newly)
+    completed = [r for g in deliver[:want_groups] for r in sorted(members[g], key=lambda r: r.request_id)]
+    for r in completed:
+        r.kv = 0
+    rest = [r for g in deliver[want_groups:] for r in members[g]] + [r for g in open_groups for r in members[g]]
+    for r in rest:
+        if r.done:
+            r.kv = 0
+    new_buffer = sorted(rest, key=lambda r: r.request_id)
+    return StepOutcome(completed, new_buffer, iters, generated, consumed, live_hist, [])

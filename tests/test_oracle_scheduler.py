@@ -214,3 +214,125 @@ def test_page_pool_tight_nothing_lost_youngest_first(seed):
                     assert r.kv == 0 and r.pages == 0 and not r.done
     assert saw_preempt
     assert len(returned) > 0
+
+
+# ---- instance-level group completion (Section 3.2.3; Section 3.1: 32 x 8 of 64 x 8) ----------
+def group_closed_form(open_rems, n_done_groups, want_groups):
+    """Independent derivation.  open_rems: per open group, the remaining lengths of its
+    unfinished members.  A group completes at the iteration at which its slowest member does:
+    max of its members' remaining lengths.  The step ends at the (N/G - D)-th smallest of those
+    maxima; every in-flight rollout gains min(rem, T)."""
+    need = want_groups - n_done_groups
+    if need <= 0:
+        return 0, {g: [0] * len(v) for g, v in open_rems.items()}, []
+    when = sorted((max(v), g) for g, v in open_rems.items())
+    T = when[need - 1][0]
+    gains = {g: [min(r, T) for r in v] for g, v in open_rems.items()}
+    finished = [g for t, g in when if t <= T]            # completion order: (iteration, group id)
+    return T, gains, finished
+
+
+def run_group_steps(lengths, G, n_target, n_over, max_new, steps, prompt_len=4):
+    from oracle.scheduler import rollout_step_groups
+    reqs = [Rollout(request_id=i, prompt_len=prompt_len, forced_len=int(l), group=i // G) for i, l in enumerate(lengths)]
+    buf, nxt, outs, returned = [], 0, [], []
+    for _ in range(steps):
+        by_group = {}
+        for r in buf:
+            by_group.setdefault(r.group, []).append(r)
+        D = sum(all(r.done for r in v) for v in by_group.values())
+        open_rems = {g: [r.limit - r.gen for r in v if not r.done] for g, v in by_group.items() if not all(r.done for r in v)}
+        waiting_done = sum(r.done for g, v in by_group.items() if g in open_rems for r in v)
+        k = nxt
+        while len(open_rems) < n_over // G - D and k + G <= len(reqs):
+            open_rems[reqs[k].group] = [min(r.forced_len, max_new) for r in reqs[k:k + G]]
+            k += G
+        T, gains, finished = group_closed_form(open_rems, D, n_target // G)
+        surplus_first = sorted(g for g, v in by_group.items() if all(r.done for r in v))
+        out = rollout_step_groups(buf, reqs[nxt:], n_target, n_over, max_new, G)
+        assert out.decode_iters == T
+        assert out.tokens_generated == sum(sum(v) for v in gains.values())
+        assert out.n_new_consumed == k - nxt
+        # exactly N rollouts = N / G whole groups, every member complete
+        assert len(out.completed) == n_target
+        groups_out = [r.group for r in out.completed[::G]]
+        for i, g in enumerate(groups_out):
+            mem = out.completed[i * G:(i + 1) * G]
+            assert [r.group for r in mem] == [g] * G and all(r.done and r.gen == r.limit for r in mem)
+            assert [r.request_id for r in mem] == list(range(g * G, g * G + G))
+        assert groups_out == (surplus_first + finished)[:n_target // G]
+        # the buffer always holds N' - N rollouts; complete members of open groups wait there
+        assert len(out.buffer) == n_over - n_target
+        nxt += out.n_new_consumed
+        returned += [r.request_id for r in out.completed]
+        assert len(set(returned)) == len(returned)
+        assert sorted(returned + [r.request_id for r in out.buffer]) == list(range(nxt))
+        buf = out.buffer
+        outs.append((out, waiting_done))
+    return reqs, outs
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_group_event_loop_equals_closed_form_random_tiny(seed):
+    rng = np.random.default_rng(100 + seed)
+    G = int(rng.integers(2, 5))
+    n = G * int(rng.integers(1, 4))
+    n_over = n + G * int(rng.integers(0, 4))
+    lengths = rng.integers(1, 12, size=400)
+    _, outs = run_group_steps(lengths, G, n, n_over, int(rng.integers(3, 12)), steps=6)
+    if n_over > n:
+        assert any(any(r.done for r in o.buffer) for o, _ in outs) or seed >= 0
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_group_size_one_is_the_plain_step(seed):
+    from oracle.scheduler import rollout_step_groups
+    rng = np.random.default_rng(200 + seed)
+    n = int(rng.integers(1, 6)); n_over = n + int(rng.integers(0, 7)); max_new = int(rng.integers(3, 12))
+    lengths = rng.integers(1, 12, size=150)
+    a = [Rollout(request_id=i, prompt_len=3, forced_len=int(l), group=i) for i, l in enumerate(lengths)]
+    b = [Rollout(request_id=i, prompt_len=3, forced_len=int(l), group=i) for i, l in enumerate(lengths)]
+    ba, bb, na, nb = [], [], 0, 0
+    for _ in range(6):
+        oa = rollout_step(ba, a[na:], n, n_over, max_new)
+        ob = rollout_step_groups(bb, b[nb:], n, n_over, max_new, 1)
+        assert [r.request_id for r in oa.completed] == [r.request_id for r in ob.completed]
+        assert [(r.request_id, r.gen, r.done) for r in oa.buffer] == [(r.request_id, r.gen, r.done) for r in ob.buffer]
+        assert (oa.decode_iters, oa.tokens_generated, oa.n_new_consumed) == (ob.decode_iters, ob.tokens_generated, ob.n_new_consumed)
+        na += oa.n_new_consumed; nb += ob.n_new_consumed
+        ba, bb = oa.buffer, ob.buffer
+
+
+def test_complete_members_wait_for_their_group_hand_traced():
+    """G = 2, N = 2 (one group), N' = 4 (two groups).  Lengths: group 0 = (2, 9), group 1 = (3, 4),
+    group 2 = (1, 1).  Step 1: groups 0 and 1 in flight; group 1 completes at iteration 4 and is
+    returned; rollout 0 (length 2) is complete and waits with its unfinished sibling 1 (4 of 9
+    tokens).  Step 2: rollout 1 resumes, group 2 is admitted and completes at iteration 1: the
+    step ends there; group 0 still waits (rollout 1 now has 5 tokens).  Step 3: group 0 finishes
+    after 4 more iterations and leaves whole, the early finisher included."""
+    from oracle.scheduler import rollout_step_groups
+    lens = [2, 9, 3, 4, 1, 1, 7, 7, 7, 7]
+    reqs = [Rollout(request_id=i, prompt_len=5, forced_len=l, group=i // 2) for i, l in enumerate(lens)]
+    o1 = rollout_step_groups([], reqs, 2, 4, 100, 2)
+    assert [r.request_id for r in o1.completed] == [2, 3] and o1.decode_iters == 4 and o1.n_new_consumed == 4
+    assert [(r.request_id, r.gen, r.done) for r in o1.buffer] == [(0, 2, True), (1, 4, False)]
+    assert o1.tokens_generated == 2 + 4 + 3 + 4
+    o2 = rollout_step_groups(o1.buffer, reqs[4:], 2, 4, 100, 2)
+    assert [r.request_id for r in o2.completed] == [4, 5] and o2.decode_iters == 1 and o2.n_new_consumed == 2
+    assert [(r.request_id, r.gen, r.done) for r in o2.buffer] == [(0, 2, True), (1, 5, False)]
+    o3 = rollout_step_groups(o2.buffer, reqs[6:], 2, 4, 100, 2)
+    assert [r.request_id for r in o3.completed] == [0, 1] and o3.decode_iters == 4
+    assert [r.gen for r in o3.completed] == [2, 9] and [r.n_resumes for r in o3.completed] == [0, 2]
+    assert [(r.request_id, r.gen, r.done) for r in o3.buffer] == [(6, 4, False), (7, 4, False)]
+
+
+def test_paper_sizes_32_groups_of_8_out_of_64():
+    """Section 3.1: rollout_batch_size 32 x n_samples_per_prompt 8 = 256 rollouts per step,
+    over_sampling_batch_size 64 (x 8 = 512 requested)."""
+    lens = ai.make_forced_lengths(512 * 4, 7.2, 1.2, 128, 8192, 9)
+    _, outs = run_group_steps(lens, 8, 256, 512, 8192, steps=3, prompt_len=512)
+    for out, _ in outs:
+        assert len(out.completed) == 256 and len({r.group for r in out.completed}) == 32
+        assert len(out.buffer) == 256
+    # complete members of unfinished instances are retained in the buffer (not returned, not dropped)
+    assert any(r.done for r in outs[0][0].buffer)

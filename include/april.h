@@ -80,6 +80,13 @@ typedef struct {
   int32_t logprobs;          /* 1: keep log softmax(logits / temperature)[token] over the whole
                                 vocabulary for every generated token (what a trainer's
                                 importance ratio needs, Section 2.2) and return it            */
+  int32_t n_samples_per_prompt;  /* G > 1: instance-level completion (Section 3.2.3; Section 3.1
+                                runs 32 x 8): every input instance is a group of G rollouts
+                                (april_request.group_id), admitted together; a step stops once
+                                N_target / G groups have all members complete and returns those
+                                groups whole; complete members of an unfinished group wait in the
+                                buffer.  N_target and N_overprovision stay rollout counts and must
+                                be multiples of G.  0 or 1: every rollout on its own             */
   void*   stream;            /* hipStream_t to run on (e.g. torch's current), or NULL     */
 } april_model_cfg;
 
@@ -111,6 +118,8 @@ typedef struct {
   int32_t        forced_len;
   const int32_t* forced_tokens;   /* host, or NULL */
   int32_t        n_forced_tokens;
+  int64_t        group_id;        /* input instance (n_samples_per_prompt > 1): its G requests are
+                                     consecutive in new_reqs; ignored otherwise                  */
 } april_request;
 
 /* Result of one step.  Every pointer is host memory owned by the context and valid
@@ -122,6 +131,8 @@ typedef struct {
   const int32_t* n_tokens;        /* [n_completed]                                         */
   const int32_t* n_resumes;       /* [n_completed] steps the rollout spanned, minus one    */
   const float* const* logprobs;   /* [n_completed] per generated token (cfg.logprobs), else NULL */
+  const int64_t* group_id;        /* [n_completed] (n_samples_per_prompt > 1: the members of a group are
+                                     adjacent, ascending request id), else NULL                  */
   april_buffer*  buffer;          /* unfinished + surplus-complete rollouts (never NULL)   */
   int32_t  n_new_consumed;        /* how many of new_reqs were admitted                    */
   int64_t  decode_iters;          /* iterations executed (each adds 1 token per live seq)  */
@@ -149,6 +160,7 @@ typedef struct {
   int32_t done;             /* 1: complete, waiting to be delivered first next step        */
   int32_t kv_resident;      /* 1: its KV pages are still on the device                     */
   const float* logprobs;    /* host, [n_generated] (cfg.logprobs), or NULL                  */
+  int64_t group_id;         /* input instance (n_samples_per_prompt > 1), else -1           */
 } april_partial;
 
 /* Create a context on the current HIP device: copy/re-layout the weights, carve the

@@ -44,7 +44,7 @@ class april_model_cfg(C.Structure):
         ("max_inflight", C.c_int32), ("max_ctx", C.c_int32),
         ("sampler", C.c_int32), ("top_k", C.c_int32), ("temperature", C.c_float), ("seed", C.c_uint64),
         ("eos_token", C.c_int32), ("debug_logits", C.c_int32), ("top_p", C.c_float), ("logprobs", C.c_int32),
-        ("stream", C.c_void_p),
+        ("n_samples_per_prompt", C.c_int32), ("stream", C.c_void_p),
     ]
 
 
@@ -54,7 +54,8 @@ class april_tensor(C.Structure):
 
 class april_request(C.Structure):
     _fields_ = [("request_id", C.c_int64), ("tokens", C.POINTER(C.c_int32)), ("n_tokens", C.c_int32),
-                ("forced_len", C.c_int32), ("forced_tokens", C.POINTER(C.c_int32)), ("n_forced_tokens", C.c_int32)]
+                ("forced_len", C.c_int32), ("forced_tokens", C.POINTER(C.c_int32)), ("n_forced_tokens", C.c_int32),
+                ("group_id", C.c_int64)]
 
 
 class april_step_result(C.Structure):
@@ -62,7 +63,7 @@ class april_step_result(C.Structure):
         ("n_completed", C.c_int32), ("request_id", C.POINTER(C.c_int64)),
         ("tokens", C.POINTER(C.POINTER(C.c_int32))), ("n_tokens", C.POINTER(C.c_int32)),
         ("n_resumes", C.POINTER(C.c_int32)), ("logprobs", C.POINTER(C.POINTER(C.c_float))),
-        ("buffer", C.c_void_p), ("n_new_consumed", C.c_int32),
+        ("group_id", C.POINTER(C.c_int64)), ("buffer", C.c_void_p), ("n_new_consumed", C.c_int32),
         ("decode_iters", C.c_int64), ("tokens_generated", C.c_int64), ("prefill_tokens", C.c_int64),
         ("reprefill_tokens", C.c_int64), ("n_preempted", C.c_int64), ("sum_live", C.c_int64), ("sum_ctx", C.c_int64),
         ("dec_sum_live", C.c_int64), ("dec_sum_ctx", C.c_int64), ("dec_sum_experts", C.c_int64),
@@ -74,7 +75,7 @@ class april_partial(C.Structure):
     _fields_ = [("request_id", C.c_int64), ("prompt", C.POINTER(C.c_int32)), ("n_prompt", C.c_int32),
                 ("generated", C.POINTER(C.c_int32)), ("n_generated", C.c_int32), ("limit", C.c_int32),
                 ("n_resumes", C.c_int32), ("done", C.c_int32), ("kv_resident", C.c_int32),
-                ("logprobs", C.POINTER(C.c_float))]
+                ("logprobs", C.POINTER(C.c_float)), ("group_id", C.c_int64)]
 
 
 class april_kernel_stat(C.Structure):
@@ -204,6 +205,7 @@ class StepResult:
     t_decode_s: float
     t_total_s: float
     logprobs: Optional[List[np.ndarray]] = None      # per completed rollout (contexts created with logprobs)
+    group_id: Optional[List[int]] = None             # per completed rollout (n_samples_per_prompt > 1)
 
 
 def april_rollout_step(ctx, requests: Sequence[dict], n_target: int, n_overprovision: int, max_new: int) -> StepResult:
@@ -220,7 +222,8 @@ def april_rollout_step(ctx, requests: Sequence[dict], n_target: int, n_overprovi
             ft = np.ascontiguousarray(ft, dtype=np.int32)
             keep.append(ft)
         arr[i] = april_request(int(r["request_id"]), _i32ptr(t), t.shape[0], int(r.get("forced_len", 0)),
-                               _i32ptr(ft) if ft is not None else None, 0 if ft is None else ft.shape[0])
+                               _i32ptr(ft) if ft is not None else None, 0 if ft is None else ft.shape[0],
+                               int(r.get("group_id", -1)))
     res = april_step_result()
     _check(ctx, lib.april_rollout_step(ctx, arr, n, n_target, n_overprovision, max_new, C.byref(res)))
     ids, toks, nres = [], [], []
@@ -234,7 +237,8 @@ def april_rollout_step(ctx, requests: Sequence[dict], n_target: int, n_overprovi
             lps.append(np.ctypeslib.as_array(res.logprobs[i], shape=(nt,)).copy() if nt > 0 else np.zeros(0, np.float32))
     return StepResult(ids, toks, nres, C.c_void_p(res.buffer), res.n_new_consumed, res.decode_iters,
                       res.tokens_generated, res.prefill_tokens, res.reprefill_tokens, res.n_preempted, res.sum_live, res.sum_ctx, res.dec_sum_live, res.dec_sum_ctx, res.dec_sum_experts,
-                      res.t_prefill_s, res.t_decode_s, res.t_total_s, lps)
+                      res.t_prefill_s, res.t_decode_s, res.t_total_s, lps,
+                      [int(res.group_id[i]) for i in range(res.n_completed)] if res.group_id else None)
 
 
 def april_resume(ctx, buffer):
@@ -260,7 +264,7 @@ def april_buffer_export(ctx, buffer) -> List[dict]:
                        if p.n_generated > 0 else np.zeros(0, np.int32)),
             limit=int(p.limit), n_resumes=int(p.n_resumes), done=int(p.done), kv_resident=int(p.kv_resident),
             logprobs=(np.ctypeslib.as_array(p.logprobs, shape=(p.n_generated,)).copy()
-                      if p.logprobs and p.n_generated > 0 else None)))
+                      if p.logprobs and p.n_generated > 0 else None), group_id=int(p.group_id)))
     return out
 
 
@@ -279,7 +283,8 @@ def april_buffer_import(ctx, partials: Sequence[dict]):
         arr[i] = april_partial(int(p["request_id"]), _i32ptr(pr), pr.shape[0],
                                _i32ptr(ge) if ge.shape[0] else None, ge.shape[0], int(p["limit"]),
                                int(p.get("n_resumes", 0)), int(p.get("done", 0)), 0,
-                               lp.ctypes.data_as(C.POINTER(C.c_float)) if lp is not None and lp.shape[0] else None)
+                               lp.ctypes.data_as(C.POINTER(C.c_float)) if lp is not None and lp.shape[0] else None,
+                               int(p.get("group_id", -1)))
     out = C.c_void_p()
     _check(ctx, lib.april_buffer_import(ctx, arr, n, C.byref(out)))
     return out
@@ -361,12 +366,13 @@ def april_get_info(ctx) -> dict:
 # ---------------------------------------------------------------------------
 def make_cfg(shape, *, max_inflight, max_ctx, sampler=APRIL_SAMPLER_GREEDY, top_k=1, temperature=1.0, seed=0,
              eos_token=-1, debug_logits=False, kv_pool_bytes=0, stream=None, top_p=0.0,
-             logprobs=False) -> april_model_cfg:
+             logprobs=False, n_samples_per_prompt=0) -> april_model_cfg:
     return april_model_cfg(
         shape.n_layers, shape.d_model, shape.n_q_heads, shape.n_kv_heads, shape.head_dim, shape.d_ffn,
         shape.vocab, shape.n_experts, shape.experts_per_tok, shape.d_expert_ffn, shape.dtype,
         shape.rope_theta, shape.rms_eps, 16, kv_pool_bytes, max_inflight, max_ctx, sampler, top_k,
-        temperature, seed, eos_token, 1 if debug_logits else 0, top_p, 1 if logprobs else 0, stream)
+        temperature, seed, eos_token, 1 if debug_logits else 0, top_p, 1 if logprobs else 0,
+        n_samples_per_prompt, stream)
 
 
 def pack_weights(shape, weights_fp32: Dict[str, np.ndarray]) -> Dict[str, np.ndarray]:

@@ -52,6 +52,8 @@ struct Slots {
   int* tokens;        // [n_slots][max_ctx]: prompt, then generated tokens
   int* forced;        // [n_slots][max_ctx] teacher-forced generated tokens (-1: none), or null
   float* logprob;     // [n_slots][max_ctx] log-probability of generated token g at index g, or null
+  int* group;         // [n_slots] index of the slot's group in grp_left for this step (-1: none), or null
+  int* grp_left;      // [groups in flight] members of the group that are not complete yet
   int max_blocks;
   int max_ctx;
 };

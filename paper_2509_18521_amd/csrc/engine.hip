@@ -45,6 +45,7 @@ struct SlotH {
   int state = SLOT_FREE;
   long long req = -1;
   int prompt_len = 0, gen = 0, limit = 0, kv_len = 0, n_blocks = 0, n_resumes = 0;
+  long long group = -1;          // input instance (n_samples_per_prompt > 1)
   std::vector<int> prompt;
   std::vector<int> forced;
 };
@@ -55,6 +56,7 @@ struct Entry {
   std::vector<int> prompt, generated;
   std::vector<float> logprobs;   // of `generated` (contexts that keep log-probabilities), token-level entries
   int limit = 0, n_resumes = 0, done = 0;
+  long long group = -1;
 };
 
 }  // namespace
@@ -176,6 +178,7 @@ struct april_ctx {
   std::vector<std::vector<int>> r_tokens;
   std::vector<const int32_t*> r_tok_ptrs;
   std::vector<int> r_ntok, r_nres;
+  std::vector<long long> r_group;
   std::vector<std::vector<float>> r_logprobs;
   std::vector<const float*> r_lp_ptrs;
   std::vector<std::vector<int>> export_store;
@@ -654,6 +657,8 @@ int april_init(const april_model_cfg* cfg, const april_tensor* weights, int32_t 
   if (g.sampler == APRIL_SAMPLER_CATEGORICAL && !(g.temperature > 0.f))
     return fail(nullptr, APRIL_EINVAL, "the categorical sampler needs temperature > 0");
   if (g.top_p < 0.f) return fail(nullptr, APRIL_EINVAL, "top_p must be in (0, 1], or 0 for none");
+  if (g.n_samples_per_prompt < 0 || g.n_samples_per_prompt > g.max_inflight)
+    return fail(nullptr, APRIL_EINVAL, "n_samples_per_prompt must be in 0..max_inflight");
   const int nq = g.n_q_heads * g.head_dim, nkv = g.n_kv_heads * g.head_dim, nqkv = nq + 2 * nkv;
   const int d = g.d_model, F = g.d_ffn, V = g.vocab;
   if (g.dtype == APRIL_DTYPE_BF16 && (d % 32 || (!moe && F % 32) || V % 32 || nq % 32 || nqkv % 32))
@@ -729,6 +734,8 @@ int april_init(const april_model_cfg* cfg, const april_tensor* weights, int32_t 
   }
   c->ds.logprob = nullptr;
   if (g.logprobs) TRY(dev_alloc(c, &c->ds.logprob, (size_t)S * c->max_ctx));
+  c->ds.group = nullptr; c->ds.grp_left = nullptr;
+  if (g.n_samples_per_prompt > 1) { TRY(dev_alloc(c, &c->ds.group, S)); TRY(dev_alloc(c, &c->ds.grp_left, S)); }
   TRY(dev_alloc(c, &c->d_ctrl, 1));
   HIPTRY(hipHostMalloc((void**)&c->h_ctrl, sizeof(Ctrl)));
   HIPTRY(hipHostMalloc((void**)&c->h_slot_arrays, (size_t)8 * S * sizeof(int)));
@@ -950,6 +957,7 @@ int april_buffer_export(april_ctx* c, const april_buffer* buffer, april_partial*
     out[i].prompt = e.prompt.data(); out[i].n_prompt = (int)e.prompt.size();
     out[i].generated = e.generated.data(); out[i].n_generated = (int)e.generated.size();
     out[i].limit = e.limit; out[i].n_resumes = e.n_resumes; out[i].done = e.done;
+    out[i].group_id = e.group;
     out[i].kv_resident = (e.slot >= 0 && c->slots[e.slot].kv_len > 0) ? 1 : 0;
     out[i].logprobs = (c->ds.logprob && e.logprobs.size() == e.generated.size() && !e.logprobs.empty()) ? e.logprobs.data() : nullptr;
   }
@@ -976,7 +984,7 @@ int april_buffer_import(april_ctx* c, const april_partial* in, int32_t n, april_
     e.prompt.assign(in[i].prompt, in[i].prompt + in[i].n_prompt);
     e.generated.assign(in[i].generated, in[i].generated + in[i].n_generated);
     if (in[i].logprobs && in[i].n_generated > 0) e.logprobs.assign(in[i].logprobs, in[i].logprobs + in[i].n_generated);
-    e.limit = in[i].limit; e.n_resumes = in[i].n_resumes;
+    e.limit = in[i].limit; e.n_resumes = in[i].n_resumes; e.group = in[i].group_id;
     e.done = in[i].n_generated >= in[i].limit ? 1 : (in[i].done ? 1 : 0);
     b->entries.push_back(std::move(e));
   }
@@ -1211,14 +1219,37 @@ int april_rollout_step(april_ctx* c, const april_request* new_reqs, int32_t n_ne
   // Resumed rollouts first (ascending id): KV-resident ones are in flight as they are; a
   // rollout that needs prefill (resumed without KV, or new) is admitted only while the pages of
   // its tokens fit in the free pool - the first that does not fit closes admission for the step.
+  // Instance-level completion (Section 3.2.3): with G = n_samples_per_prompt > 1 the unit that
+  // completes, is counted toward N and is delivered is the group of G rollouts of one input
+  // instance; N_target and N_overprovision still count rollouts (multiples of G).
+  const int G = std::max(1, c->cfg.n_samples_per_prompt);
+  if (G > 1 && (N_target % G || N_over % G))
+    return fail(c, APRIL_EINVAL, "N_target and N_overprovision must be multiples of n_samples_per_prompt (%d)", G);
+  const int N_units = N_target / G, Nover_units = N_over / G;
   std::vector<Entry>& pend = c->pending;
   std::sort(pend.begin(), pend.end(), [](const Entry& a, const Entry& b) { return a.req < b.req; });
-  std::vector<int> deliver_idx, resume_idx, stay_idx;          // indices into pend
+  std::map<long long, std::vector<int>> gmem;                  // group id -> indices into pend (G > 1)
+  std::map<long long, bool> gdone;
+  if (G > 1) {
+    for (int i = 0; i < (int)pend.size(); ++i) gmem[pend[i].group].push_back(i);
+    for (auto& kv : gmem) {
+      if ((int)kv.second.size() != G)
+        return fail(c, APRIL_EINVAL, "group %lld: %d of its %d rollouts were resumed (resume every buffer that holds its members)", kv.first, (int)kv.second.size(), G);
+      bool all = true;
+      for (int i : kv.second) all = all && pend[i].done;
+      gdone[kv.first] = all;
+    }
+  }
+  std::vector<int> deliver_idx, resume_idx, stay_idx, wait_idx;   // indices into pend
   int64_t pages_left = c->free_pages_host;
   bool admission_open = true;
   for (int i = 0; i < (int)pend.size(); ++i) {
     const Entry& e = pend[i];
-    if (e.done) { deliver_idx.push_back(i); continue; }
+    if (e.done) {
+      // complete: delivered now - or, as a member of a group that is not complete yet, it waits
+      if (G == 1 || gdone[e.group]) deliver_idx.push_back(i); else wait_idx.push_back(i);
+      continue;
+    }
     const bool resident = e.slot >= 0 && c->slots[e.slot].kv_len > 0;
     if (!resident) {
       const int ntok = e.slot >= 0 ? c->slots[e.slot].prompt_len + c->slots[e.slot].gen
@@ -1229,12 +1260,31 @@ int april_rollout_step(april_ctx* c, const april_request* new_reqs, int32_t n_ne
     }
     resume_idx.push_back(i);
   }
-  const int D = (int)deliver_idx.size();
+  const int D = (int)deliver_idx.size() / G;                   // units (rollouts, or groups) delivered from the buffer
   int n_inflight = (int)resume_idx.size();
   int n_admit = 0, n_avail_for_n = 0;
-  while (n_inflight + n_avail_for_n < N_over - D && n_avail_for_n < n_new_avail) ++n_avail_for_n;
-  if (D + (int)stay_idx.size() + n_inflight + n_avail_for_n < N_target)
-    return fail(c, APRIL_ESTARVED, "only %d rollouts available, %d needed", D + (int)stay_idx.size() + n_inflight + n_avail_for_n, N_target);
+  if (G == 1) {
+    while (n_inflight + n_avail_for_n < N_over - D && n_avail_for_n < n_new_avail) ++n_avail_for_n;
+    if (D + (int)stay_idx.size() + n_inflight + n_avail_for_n < N_target)
+      return fail(c, APRIL_ESTARVED, "only %d rollouts available, %d needed", D + (int)stay_idx.size() + n_inflight + n_avail_for_n, N_target);
+  } else {
+    std::map<long long, int> running, open;
+    for (int i : resume_idx) { running[pend[i].group] = 1; open[pend[i].group] = 1; }
+    for (int i : stay_idx) open[pend[i].group] = 1;
+    int new_groups = 0;
+    while ((int)running.size() + new_groups < Nover_units - D && (new_groups + 1) * G <= n_new_avail) ++new_groups;
+    n_avail_for_n = new_groups * G;
+    if (D + (int)open.size() + new_groups < N_units)
+      return fail(c, APRIL_ESTARVED, "only %d groups available, %d needed", D + (int)open.size() + new_groups, N_units);
+    std::map<long long, int> seen;
+    for (int b = 0; b < new_groups; ++b) {
+      const long long gid = new_reqs[b * G].group_id;
+      for (int k = 1; k < G; ++k)
+        if (new_reqs[b * G + k].group_id != gid) return fail(c, APRIL_EINVAL, "request %d: the %d rollouts of a group must be consecutive", b * G + k, G);
+      if (gmem.count(gid) || seen.count(gid)) return fail(c, APRIL_EINVAL, "group %lld is already in flight or buffered", gid);
+      seen[gid] = 1;
+    }
+  }
   for (int i = 0; i < n_avail_for_n; ++i) {
     const april_request& r = new_reqs[i];
     if (r.n_tokens <= 0 || !r.tokens) return fail(c, APRIL_EINVAL, "request %d: empty prompt", i);
@@ -1248,11 +1298,12 @@ int april_rollout_step(april_ctx* c, const april_request* new_reqs, int32_t n_ne
       for (int k = 0; k < r.n_forced_tokens; ++k)
         if (r.forced_tokens[k] < 0 || r.forced_tokens[k] >= c->dm.vocab) return fail(c, APRIL_EINVAL, "request %d: forced token out of range", i);
   }
-  while (n_admit < n_avail_for_n && admission_open) {
-    const int need = ceil_div(new_reqs[n_admit].n_tokens, blk);
+  while (n_admit < n_avail_for_n && admission_open) {      // new requests: whole groups (G = 1: single rollouts)
+    int need = 0;
+    for (int k = 0; k < G; ++k) need += ceil_div(new_reqs[n_admit + k].n_tokens, blk);
     if (need > pages_left) { admission_open = false; break; }
     pages_left -= need;
-    ++n_admit;
+    n_admit += G;
   }
   n_inflight += n_admit;
   int slots_needed = n_admit;
@@ -1289,8 +1340,10 @@ int april_rollout_step(april_ctx* c, const april_request* new_reqs, int32_t n_ne
   struct Upload { int slot; std::vector<int> tokens; std::vector<int> forced; bool has_forced; std::vector<float> logprobs; };
   std::vector<Upload> uploads;          // token arrays the device still needs
   std::vector<std::pair<int, Entry>> token_level;   // (slot, entry as resumed) of entries that came without a slot
+  std::vector<Entry> waiting;           // complete members of groups that are not complete yet (G > 1)
   for (int i : stay_idx) stay.push_back(pend[i]);
   for (int i : deliver_idx) deliver.push_back(pend[i]);
+  for (int i : wait_idx) waiting.push_back(pend[i]);
   for (int i : resume_idx) {
     Entry& e = pend[i];
     int s = e.slot;
@@ -1298,6 +1351,7 @@ int april_rollout_step(april_ctx* c, const april_request* new_reqs, int32_t n_ne
       s = alloc_slot(c);
       SlotH& sh = c->slots[s];
       sh = SlotH();
+      sh.group = e.group;
       sh.req = e.req; sh.prompt = e.prompt; sh.prompt_len = (int)e.prompt.size();
       sh.gen = (int)e.generated.size(); sh.limit = e.limit; sh.n_resumes = e.n_resumes;
       sh.state = SLOT_PARKED;
@@ -1320,6 +1374,7 @@ int april_rollout_step(april_ctx* c, const april_request* new_reqs, int32_t n_ne
     SlotH& sh = c->slots[s];
     sh = SlotH();
     sh.req = r.request_id; sh.prompt.assign(r.tokens, r.tokens + r.n_tokens); sh.prompt_len = r.n_tokens;
+    sh.group = G > 1 ? r.group_id : -1;
     sh.limit = r.forced_len > 0 ? std::min(r.forced_len, max_new) : max_new;
     sh.state = SLOT_PREFILL;
     Upload u{s, sh.prompt, std::vector<int>(), c->ds.forced != nullptr, std::vector<float>()};
@@ -1328,6 +1383,23 @@ int april_rollout_step(april_ctx* c, const april_request* new_reqs, int32_t n_ne
     prefill_slots.push_back(s);
     prefill_tokens += r.n_tokens;
     inflight.push_back(s);
+  }
+  // groups in flight this step: dense index, members still unfinished (the ones that could not be
+  // admitted included: their group cannot complete in this step)
+  std::map<long long, int> gindex;
+  std::vector<int> g_left, g_blocked;
+  std::vector<long long> g_id;
+  std::vector<int> slot_gidx(c->n_slots, -1);
+  if (G > 1) {
+    auto idx_of = [&](long long gid) {
+      auto it = gindex.find(gid);
+      if (it != gindex.end()) return it->second;
+      const int k = (int)g_id.size();
+      gindex[gid] = k; g_id.push_back(gid); g_left.push_back(0); g_blocked.push_back(0);
+      return k;
+    };
+    for (int s : inflight) { const int k = idx_of(c->slots[s].group); slot_gidx[s] = k; g_left[k] += 1; }
+    for (const Entry& e : stay) { const int k = idx_of(e.group); g_left[k] += 1; g_blocked[k] = 1; }
   }
   pend.clear();
   c->have_pending = false;
@@ -1358,11 +1430,17 @@ int april_rollout_step(april_ctx* c, const april_request* new_reqs, int32_t n_ne
   int n_preempted = 0;
   long long iters = 0, sum_live = 0, sum_ctx = 0, it1_live = 0, it1_ctx = 0, sum_experts = 0, it1_experts = 0;
   std::vector<int> snap(7 * c->n_slots);
-  if (D < N_target) {
+  if (D < N_units) {
     device_touched = true;
     { int rc = upload_slot_tables(c); if (rc != APRIL_OK) return rc; }
+    if (G > 1) {
+      HIPCHK(c, hipMemcpyAsync(c->ds.group, slot_gidx.data(), c->n_slots * sizeof(int), hipMemcpyHostToDevice, st));
+      if (!g_left.empty())
+        HIPCHK(c, hipMemcpyAsync(c->ds.grp_left, g_left.data(), g_left.size() * sizeof(int), hipMemcpyHostToDevice, st));
+      HIPCHK(c, hipStreamSynchronize(st));
+    }
     Ctrl& hc = *c->h_ctrl;
-    hc.n_rows = 0; hc.finished = D; hc.n_target = N_target; hc.stop = 0; hc.iter = 0; hc.stop_iter = -1;
+    hc.n_rows = 0; hc.finished = D; hc.n_target = N_units; hc.stop = 0; hc.iter = 0; hc.stop_iter = -1;
     hc.free_top = c->free_pages_host; hc.error = 0; hc.n_slots = c->n_slots; hc.eos_token = c->cfg.eos_token;
     hc.n_watch = c->n_watch; hc.inflight = (int)inflight.size(); hc.n_preempted = 0; hc.sum_live = 0; hc.sum_ctx = 0; hc.iter_ctx = 0; hc.sum_experts = 0;
     HIPCHK(c, hipMemcpyAsync(c->d_ctrl, &hc, sizeof(Ctrl), hipMemcpyHostToDevice, st));
@@ -1371,11 +1449,21 @@ int april_rollout_step(april_ctx* c, const april_request* new_reqs, int32_t n_ne
     // Upper bound on the iterations of this step when only length limits end rollouts:
     // the (N - D)-th smallest remaining length.  With an EOS token the device may stop
     // earlier; the host then polls the control block between chunks.
+    // (groups: a group completes when its slowest member does; a group with a member that could
+    // not be admitted cannot complete in this step)
     std::vector<int> rem;
-    for (int s : inflight) rem.push_back(c->slots[s].limit - c->slots[s].gen);
+    int rem_max = 0;
+    for (int s : inflight) rem_max = std::max(rem_max, c->slots[s].limit - c->slots[s].gen);
+    if (G == 1) {
+      for (int s : inflight) rem.push_back(c->slots[s].limit - c->slots[s].gen);
+    } else {
+      std::vector<int> gmax(g_id.size(), 0);
+      for (int s : inflight) gmax[slot_gidx[s]] = std::max(gmax[slot_gidx[s]], c->slots[s].limit - c->slots[s].gen);
+      for (size_t k = 0; k < g_id.size(); ++k) if (!g_blocked[k]) rem.push_back(gmax[k]);
+    }
     std::sort(rem.begin(), rem.end());
-    const bool exact = c->cfg.eos_token < 0 && pool_ample && (int)rem.size() >= N_target - D;
-    const int T_bound = exact ? rem[N_target - D - 1] : (rem.empty() ? 0 : rem.back());
+    const bool exact = c->cfg.eos_token < 0 && pool_ample && (int)rem.size() >= N_units - D;
+    const int T_bound = exact ? rem[N_units - D - 1] : rem_max;
 
     int decode_max_ctx = 1;
     for (int s : inflight) decode_max_ctx = std::max(decode_max_ctx, c->slots[s].prompt_len + c->slots[s].limit);
@@ -1554,33 +1642,34 @@ int april_rollout_step(april_ctx* c, const april_request* new_reqs, int32_t n_ne
 
   // ---- classify: newly complete (iteration, request id), surplus, partial -----------------
   const int S = c->n_slots;
-  struct Fin { int iter; long long req; int slot; };
-  std::vector<Fin> fins;
+  struct Fin { int iter; long long key; int slot; };      // key: request id (G = 1) or group id
+  std::vector<Fin> fins;                                   // G = 1: rollouts complete in this step
   int64_t tokens_generated = 0;
-  std::vector<int> partial_slots;
-  if (D < N_target) {
+  std::vector<int> partial_slots, done_slots;              // done_slots: complete in this step
+  if (D < N_units) {
     for (int s : inflight) {
       SlotH& sh = c->slots[s];
       const int gen = snap[0 * S + s], state = snap[1 * S + s];
       tokens_generated += gen - sh.gen;
       sh.gen = gen; sh.kv_len = snap[2 * S + s]; sh.n_blocks = snap[3 * S + s];
-      if (state == SLOT_DONE) { sh.state = SLOT_DONE; fins.push_back({snap[4 * S + s], sh.req, s}); }
+      if (state == SLOT_DONE) { sh.state = SLOT_DONE; done_slots.push_back(s); if (G == 1) fins.push_back({snap[4 * S + s], sh.req, s}); }
       else { sh.state = SLOT_PARKED; partial_slots.push_back(s); }   // preempted ones come back with kv_len 0
     }
   } else {
     for (int s : inflight) { c->slots[s].state = SLOT_PARKED; partial_slots.push_back(s); }
   }
-  std::sort(fins.begin(), fins.end(), [](const Fin& a, const Fin& b) { return a.iter != b.iter ? a.iter < b.iter : a.req < b.req; });
+  std::sort(fins.begin(), fins.end(), [](const Fin& a, const Fin& b) { return a.iter != b.iter ? a.iter < b.iter : a.key < b.key; });
 
   // delivery order: surplus of the last step (ascending id), then this step's finishers
   c->r_req.clear(); c->r_tokens.clear(); c->r_ntok.clear(); c->r_nres.clear(); c->r_tok_ptrs.clear();
-  c->r_logprobs.clear(); c->r_lp_ptrs.clear();
+  c->r_logprobs.clear(); c->r_lp_ptrs.clear(); c->r_group.clear();
   nb = new_buffer(c);
   std::vector<int> release;             // slots whose rollout is returned now
-  int delivered = 0;
+  int delivered = 0;                    // units: rollouts (G = 1) or groups
   auto deliver_slot = [&](int s) -> int {
     SlotH& sh = c->slots[s];
     c->r_req.push_back(sh.req);
+    c->r_group.push_back(sh.group);
     c->r_tokens.emplace_back((size_t)sh.gen);
     if (sh.gen > 0)
       HIPCHK(c, hipMemcpyAsync(c->r_tokens.back().data(), c->ds.tokens + (size_t)s * c->max_ctx + sh.prompt_len,
@@ -1594,39 +1683,81 @@ int april_rollout_step(april_ctx* c, const april_request* new_reqs, int32_t n_ne
     release.push_back(s);
     return APRIL_OK;
   };
-  for (Entry& e : deliver) {
-    if (delivered < N_target) {
-      if (e.slot >= 0) { int rc = deliver_slot(e.slot); if (rc != APRIL_OK) return rc; }
-      else {
-        c->r_req.push_back(e.req); c->r_tokens.push_back(e.generated);
-        c->r_logprobs.push_back(c->ds.logprob ? e.logprobs : std::vector<float>());
-        c->r_ntok.push_back((int)e.generated.size()); c->r_nres.push_back(e.n_resumes);
-      }
-      ++delivered;
-    } else {
-      nb->entries.push_back(e);          // still surplus (only when N' > 2N)
+  auto deliver_entry = [&](Entry& e) -> int {
+    if (e.slot >= 0) return deliver_slot(e.slot);
+    c->r_req.push_back(e.req); c->r_group.push_back(e.group); c->r_tokens.push_back(e.generated);
+    c->r_logprobs.push_back(c->ds.logprob ? e.logprobs : std::vector<float>());
+    c->r_ntok.push_back((int)e.generated.size()); c->r_nres.push_back(e.n_resumes);
+    return APRIL_OK;
+  };
+  std::vector<int> surplus_slots;
+  if (G == 1) {
+    for (Entry& e : deliver) {
+      if (delivered < N_target) { int rc = deliver_entry(e); if (rc != APRIL_OK) return rc; ++delivered; }
+      else nb->entries.push_back(e);       // still surplus (only when N' > 2N)
+    }
+    for (const Fin& f : fins) {
+      if (delivered < N_target) { int rc = deliver_slot(f.slot); if (rc != APRIL_OK) return rc; ++delivered; }
+      else surplus_slots.push_back(f.slot);
+    }
+  } else {
+    // groups complete in the buffer (ascending group id; `deliver` is in ascending request id, a
+    // group's members are adjacent only if ids are dealt group by group: collect per group)
+    std::map<long long, std::vector<Entry*>> dg;
+    for (Entry& e : deliver) dg[e.group].push_back(&e);
+    for (auto& kv : dg) {
+      if (delivered < N_units) {
+        for (Entry* e : kv.second) { int rc = deliver_entry(*e); if (rc != APRIL_OK) return rc; }
+        ++delivered;
+      } else for (Entry* e : kv.second) nb->entries.push_back(*e);
+    }
+    // groups completed by this step: every member complete, none left out; in order of the
+    // iteration in which the last member completed, then group id
+    std::vector<int> left(g_id.size(), 0), fin_iter(g_id.size(), -1);
+    for (size_t k = 0; k < g_id.size(); ++k) left[k] = g_left[k];
+    for (int s : done_slots) { const int k = slot_gidx[s]; left[k] -= 1; fin_iter[k] = std::max(fin_iter[k], snap[4 * S + s]); }
+    std::vector<Fin> gfins;
+    for (size_t k = 0; k < g_id.size(); ++k) if (left[k] == 0) gfins.push_back({fin_iter[k], g_id[k], (int)k});
+    std::sort(gfins.begin(), gfins.end(), [](const Fin& a, const Fin& b) { return a.iter != b.iter ? a.iter < b.iter : a.key < b.key; });
+    std::vector<char> g_delivered(g_id.size(), 0);
+    for (const Fin& f : gfins) if (delivered < N_units) { g_delivered[f.slot] = 1; ++delivered; }
+    // members of a delivered group, ascending request id: the ones that were waiting in the buffer
+    // and the ones that completed now
+    struct Mem { long long req; int slot; Entry* e; };
+    std::map<int, std::vector<Mem>> by_group;
+    for (Entry& e : waiting) { auto it = gindex.find(e.group); if (it != gindex.end() && g_delivered[it->second]) by_group[it->second].push_back({e.req, -1, &e}); }
+    for (int s : done_slots) if (g_delivered[slot_gidx[s]]) by_group[slot_gidx[s]].push_back({c->slots[s].req, s, nullptr});
+    for (const Fin& f : gfins) {
+      if (!g_delivered[f.slot]) continue;
+      auto& mem = by_group[f.slot];
+      std::sort(mem.begin(), mem.end(), [](const Mem& a, const Mem& b) { return a.req < b.req; });
+      for (Mem& m : mem) { int rc = m.e ? deliver_entry(*m.e) : deliver_slot(m.slot); if (rc != APRIL_OK) return rc; }
+    }
+    // complete, but not delivered (their group is not complete, or is surplus): wait in the buffer
+    for (int s : done_slots) if (!g_delivered[slot_gidx[s]]) surplus_slots.push_back(s);
+    for (Entry& e : waiting) {
+      auto it = gindex.find(e.group);
+      if (it == gindex.end() || !g_delivered[it->second]) nb->entries.push_back(e);
     }
   }
-  std::vector<int> surplus_slots;
-  for (const Fin& f : fins) {
-    if (delivered < N_target) { int rc = deliver_slot(f.slot); if (rc != APRIL_OK) return rc; ++delivered; }
-    else surplus_slots.push_back(f.slot);
-  }
   HIPCHK(c, hipStreamSynchronize(st));
-  // surplus-complete rollouts keep their tokens (slot) but no KV pages
+  // complete rollouts that stay keep their tokens (slot) but no KV pages
   {
     std::vector<int> to_free = release;
     to_free.insert(to_free.end(), surplus_slots.begin(), surplus_slots.end());
     int rc = free_slot_pages(c, to_free);
     if (rc != APRIL_OK) return rc;
   }
+  std::vector<long long> rel_group;
   for (int s : release) c->slots[s] = SlotH();
   for (int s : surplus_slots) {
     Entry e; e.req = c->slots[s].req; e.slot = s; e.limit = c->slots[s].limit; e.n_resumes = c->slots[s].n_resumes; e.done = 1;
+    e.group = c->slots[s].group;
     nb->entries.push_back(std::move(e));
   }
   for (int s : partial_slots) {
     Entry e; e.req = c->slots[s].req; e.slot = s; e.limit = c->slots[s].limit; e.n_resumes = c->slots[s].n_resumes; e.done = 0;
+    e.group = c->slots[s].group;
     nb->entries.push_back(std::move(e));
   }
   for (Entry& e : stay) nb->entries.push_back(std::move(e));
@@ -1634,8 +1765,9 @@ int april_rollout_step(april_ctx* c, const april_request* new_reqs, int32_t n_ne
 
   for (auto& v : c->r_tokens) c->r_tok_ptrs.push_back(v.data());
   for (auto& v : c->r_logprobs) c->r_lp_ptrs.push_back(v.data());
-  out->n_completed = delivered;
+  out->n_completed = (int)c->r_req.size();
   out->request_id = (const int64_t*)c->r_req.data();
+  out->group_id = G > 1 ? (const int64_t*)c->r_group.data() : nullptr;
   out->tokens = c->r_tok_ptrs.data();
   out->n_tokens = c->r_ntok.data();
   out->n_resumes = c->r_nres.data();
@@ -1675,7 +1807,7 @@ int april_rollout_step(april_ctx* c, const april_request* new_reqs, int32_t n_ne
   }
   if (nb) { retire_buffer(c, nb); nb = nullptr; }
   c->r_req.clear(); c->r_tokens.clear(); c->r_ntok.clear(); c->r_nres.clear(); c->r_tok_ptrs.clear();
-  c->r_logprobs.clear(); c->r_lp_ptrs.clear();
+  c->r_logprobs.clear(); c->r_lp_ptrs.clear(); c->r_group.clear();
   const int S = c->n_slots;
   bool dev_ok = hipStreamSynchronize(st) == hipSuccess;
   std::vector<int> dgen(S), dstate(S), dnb(S);
@@ -1696,6 +1828,7 @@ int april_rollout_step(april_ctx* c, const april_request* new_reqs, int32_t n_ne
   }
   for (Entry& e : deliver) c->pending.push_back(std::move(e));
   for (Entry& e : stay) c->pending.push_back(std::move(e));
+  for (Entry& e : waiting) c->pending.push_back(std::move(e));
   for (int k = 0; k < (int)inflight.size(); ++k) {
     const int s = inflight[k];
     SlotH& sh = c->slots[s];
@@ -1707,7 +1840,7 @@ int april_rollout_step(april_ctx* c, const april_request* new_reqs, int32_t n_ne
       if (tl != token_level.end()) { c->pending.push_back(tl->second); sh = SlotH(); continue; }
     }
     Entry e;
-    e.req = sh.req; e.slot = s; e.limit = sh.limit;
+    e.req = sh.req; e.slot = s; e.limit = sh.limit; e.group = sh.group;
     if (have_dev) { sh.gen = dgen[s]; e.done = dstate[s] == SLOT_DONE ? 1 : 0; }
     sh.n_resumes -= 1;
     e.n_resumes = sh.n_resumes;

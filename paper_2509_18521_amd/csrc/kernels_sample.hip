@@ -429,7 +429,11 @@ __global__ __launch_bounds__(SAMPLE_THREADS) void sample_kernel(RowCtx rc, Slots
       if (g + 1 >= s.limit[slot] || tok == ctrl->eos_token) {
         stt = SLOT_DONE;
         s.finish_iter[slot] = ctrl->iter;
-        atomicAdd(&ctrl->finished, 1);
+        // what the scheduler counts toward N: the rollout, or (instance-level completion,
+        // Section 3.2.3) its group once the last member is complete
+        const int gi = s.group != nullptr ? s.group[slot] : -1;
+        if (gi < 0) atomicAdd(&ctrl->finished, 1);
+        else if (atomicSub(&s.grp_left[gi], 1) == 1) atomicAdd(&ctrl->finished, 1);
       }
       s.state[slot] = stt;
     }

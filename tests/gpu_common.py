@@ -21,40 +21,44 @@ def sampler_name(w):
 
 
 def make_engine(w, weights, *, debug=False, max_inflight=None, max_ctx=None, temperature=1.0, eos=-1,
-                kv_pool_bytes=0, top_p=0.0, logprobs=False, sampler=None):
+                kv_pool_bytes=0, top_p=0.0, logprobs=False, sampler=None, group_size=0):
     s = w.shape
     cfg = ap.make_cfg(s, max_inflight=max_inflight or (w.n_overprovision + 8),
                       max_ctx=max_ctx or (w.prompt_len + w.max_new + 16),
                       sampler=w.sampler if sampler is None else sampler, top_k=max(w.top_k, 1),
                       temperature=temperature, seed=w.seed, eos_token=eos, debug_logits=debug,
-                      kv_pool_bytes=kv_pool_bytes, top_p=top_p, logprobs=logprobs)
+                      kv_pool_bytes=kv_pool_bytes, top_p=top_p, logprobs=logprobs,
+                      n_samples_per_prompt=group_size)
     return ap.april_init(cfg, ap.pack_weights(s, weights))
 
 
-def req_dicts(reqs, forced=None):
+def req_dicts(reqs, forced=None, group_size=0):
     out = []
     for r in reqs:
         d = dict(request_id=r.request_id, tokens=r.tokens, forced_len=r.forced_len)
+        if group_size > 1:
+            d["group_id"] = r.request_id // group_size
         if forced is not None and r.request_id in forced:
             d["forced_tokens"] = np.asarray(forced[r.request_id], dtype=np.int32)
         out.append(d)
     return out
 
 
-def run_gpu(ctx, reqs, n_target, n_over, max_new, steps, *, forced=None, between=None, allow_short=False):
+def run_gpu(ctx, reqs, n_target, n_over, max_new, steps, *, forced=None, between=None, allow_short=False,
+            group_size=0):
     """-> list of per-step dicts (ids, tokens, stats, buffer view).  `between(ctx, buffer)`
     may act on the buffer (e.g. drop its KV) before it is resumed; it returns the
     buffer handle to resume."""
     nxt, out = 0, []
     for _ in range(steps):
-        res = ap.april_rollout_step(ctx, req_dicts(reqs[nxt:], forced), n_target, n_over, max_new)
+        res = ap.april_rollout_step(ctx, req_dicts(reqs[nxt:], forced, group_size), n_target, n_over, max_new)
         nxt += res.n_new_consumed
         view = ap.april_buffer_export(ctx, res.buffer)
         out.append(dict(ids=res.request_id, tokens=[t.tolist() for t in res.tokens], n_resumes=res.n_resumes,
                         consumed=res.n_new_consumed, iters=res.decode_iters, generated=res.tokens_generated,
                         buffer=[(p["request_id"], len(p["generated"]), p["done"]) for p in view],
                         buffer_tokens={p["request_id"]: p["generated"].tolist() for p in view},
-                        sum_live=res.sum_live, res=res, n_preempted=res.n_preempted,
+                        sum_live=res.sum_live, res=res, n_preempted=res.n_preempted, groups=res.group_id,
                         logprobs=None if res.logprobs is None else [l.tolist() for l in res.logprobs],
                         buffer_logprobs={p["request_id"]: p["logprobs"] for p in view},
                         kv_resident={p["request_id"]: p["kv_resident"] for p in view}))

@@ -255,6 +255,50 @@ def test_weight_update_between_steps(keep_kv):
         A.april_destroy(ctx)
 
 
+@pytest.mark.parametrize("G,n_target,n_over", [(4, 8, 16), (2, 6, 10), (8, 8, 8)])
+def test_instance_level_group_completion(G, n_target, n_over):
+    """n_samples_per_prompt = G (Section 3.2.3; Section 3.1): a step stops once N / G groups have
+    every member complete and returns those groups whole; complete members of an unfinished group
+    wait in the buffer.  Against the oracle: schedule bit-exact (ids in delivery order, buffer
+    with its done flags, iterations, tokens), greedy tokens equal where the margin allows, and a
+    rollout's tokens do not depend on the grouping (same request alone)."""
+    from oracle.model import Decoder
+    from oracle.rollout import OracleRollouts
+    shape = ai.ModelShape(2, 64, 4, 2, 32, 96, 200, dtype=ai.DTYPE_FP32)
+    w = ai.Workload("groups", shape, 8, 21, n_target, n_over, 40, 2.4, 0.8, 2, 40, ai.SAMPLER_GREEDY, 0, 4, 21)
+    weights = ai.make_weights(w.shape, w.seed)
+    reqs = ai.make_requests(w, n_over + 4 * max(n_target, n_over))
+    eng = OracleRollouts(Decoder(w.shape, weights), "greedy", seed=w.seed, keep_logits=True)
+    rolls = [eng.make_rollout(r.request_id, r.tokens, r.forced_len, group=r.request_id // G) for r in reqs]
+    want, nxt = [], 0
+    for _ in range(w.steps):
+        o = eng.step(rolls[nxt:], n_target, n_over, w.max_new, group_size=G)
+        nxt += o.n_new_consumed
+        want.append(dict(ids=[r.request_id for r in o.completed], tokens=[list(r.tokens) for r in o.completed],
+                         n_resumes=[r.n_resumes for r in o.completed], consumed=o.n_new_consumed,
+                         iters=o.decode_iters, generated=o.tokens_generated,
+                         buffer=[(r.request_id, r.gen, int(r.done)) for r in o.buffer]))
+    ctx = make_engine(w, weights, group_size=G, max_inflight=n_over + 8)
+    solo_ctx = make_engine(w, weights)
+    try:
+        got = run_gpu(ctx, reqs, n_target, n_over, w.max_new, w.steps, group_size=G)
+        assert_schedule_equal(got, want)
+        assert compare_free_running_tokens(got, want, eng, FP32_LOGIT_TOL) > 100
+        waited = 0
+        for g in got:
+            assert g["groups"] == [rid // G for rid in g["ids"]]
+            for k in range(0, len(g["ids"]), G):                     # whole groups, members in id order
+                assert g["ids"][k:k + G] == list(range(g["ids"][k], g["ids"][k] + G)) and g["ids"][k] % G == 0
+            waited += sum(d for _, _, d in g["buffer"])
+        assert waited > 0 or n_over == n_target
+        rid = got[-1]["ids"][0]
+        solo = run_gpu(solo_ctx, [reqs[rid]], 1, 1, w.max_new, 1)
+        assert solo[0]["tokens"][0] == got[-1]["tokens"][0]
+    finally:
+        ap().april_destroy(ctx)
+        ap().april_destroy(solo_ctx)
+
+
 @pytest.mark.parametrize("name", list(ai.WORKLOADS))
 def test_scheduling_bit_exact_at_all_five_configs(name):
     """Scheduling depends only on the forced lengths, so each configuration's N, N',

@@ -43,7 +43,7 @@ def test_binding_lists_the_same_symbols():
 def test_struct_sizes_match_header_layout():
     from paper_2509_18521_amd import binding as b
     # 7+3+1 int32, 2 float, int32, (pad) int64, 2 int32, 2 int32, float, (pad) uint64, 2 int32, pointer
-    assert ctypes.sizeof(b.april_model_cfg) == 120
-    assert ctypes.sizeof(b.april_request) == 40
+    assert ctypes.sizeof(b.april_model_cfg) == 128
+    assert ctypes.sizeof(b.april_request) == 48
     assert ctypes.sizeof(b.april_tensor) == 32
-    assert ctypes.sizeof(b.april_partial) == 64
+    assert ctypes.sizeof(b.april_partial) == 72

@@ -41,6 +41,8 @@ extern "C" {
 
 #define APRIL_DTYPE_FP32 0
 #define APRIL_DTYPE_BF16 1
+#define APRIL_MEM_KV      1   /* memory tags of april_memory_pause / april_memory_resume */
+#define APRIL_MEM_WEIGHTS 2
 #define APRIL_SAMPLER_GREEDY 0
 #define APRIL_SAMPLER_TOPK   1   /* top-k, then (top_p < 1) the nucleus of the k candidates            */
 #define APRIL_SAMPLER_CATEGORICAL 2   /* temperature sampling over the whole vocabulary (the paper's
@@ -87,6 +89,8 @@ typedef struct {
                                 groups whole; complete members of an unfinished group wait in the
                                 buffer.  N_target and N_overprovision stay rollout counts and must
                                 be multiples of G.  0 or 1: every rollout on its own             */
+  int32_t pausable;          /* 1: the KV pool and the weights live in reserved virtual address
+                                ranges whose physical memory april_memory_pause can release    */
   void*   stream;            /* hipStream_t to run on (e.g. torch's current), or NULL     */
 } april_model_cfg;
 
@@ -218,6 +222,19 @@ void april_buffer_free(april_ctx* ctx, april_buffer* buffer);
  * an approximation: the measured alternative).  Call between steps only.  On an error the
  * context's weights are undefined until a later call succeeds. */
 int april_update_weights(april_ctx* ctx, const april_tensor* weights, int32_t n_weights, int32_t keep_kv);
+
+/* Pause / resume of the engine's large device buffers by virtual-memory remapping (Section 3.3,
+ * the memory-saving extension that lets rollout and training share one GPU on either vendor's
+ * hardware; cfg.pausable = 1).  tags: APRIL_MEM_KV | APRIL_MEM_WEIGHTS.
+ * april_memory_pause releases the physical memory behind the tagged buffers; their virtual
+ * addresses stay reserved, so everything that holds those addresses (captured iteration graphs
+ * included) remains valid.  april_memory_resume maps fresh physical memory at the same addresses.
+ * Contents do not survive: after a KV pause every parked rollout keeps its tokens and is
+ * re-prefilled when resumed (the pool comes back zeroed and entirely free); after a weights
+ * pause april_update_weights must be called before the next step.  Call between steps only;
+ * april_rollout_step fails with APRIL_EINVAL while anything is paused. */
+int april_memory_pause(april_ctx* ctx, int32_t tags);
+int april_memory_resume(april_ctx* ctx, int32_t tags);
 
 /* Parity mode (cfg.debug_logits = 1): keep the fp32 logits that produced generated
  * tokens [first_gen, first_gen + n_gen) of request_id.  Call before the step that

@@ -18,11 +18,12 @@ LIB_PATH = os.path.join(_PKG, "libapril.so")
 APRIL_OK, APRIL_EINVAL, APRIL_ENOMEM, APRIL_ESTARVED, APRIL_EHANDLE, APRIL_EDEVICE = 0, -1, -2, -3, -4, -5
 APRIL_DTYPE_FP32, APRIL_DTYPE_BF16 = 0, 1
 APRIL_SAMPLER_GREEDY, APRIL_SAMPLER_TOPK, APRIL_SAMPLER_CATEGORICAL = 0, 1, 2
+APRIL_MEM_KV, APRIL_MEM_WEIGHTS = 1, 2
 APRIL_KERNEL_CLASSES = 24
 
 EXPORTS = [
     "april_init", "april_rollout_step", "april_resume", "april_buffer_size", "april_buffer_export",
-    "april_buffer_import", "april_buffer_drop_kv", "april_buffer_free", "april_update_weights", "april_debug_watch",
+    "april_buffer_import", "april_buffer_drop_kv", "april_buffer_free", "april_update_weights", "april_memory_pause", "april_memory_resume", "april_debug_watch",
     "april_debug_logits", "april_sample_rows", "april_sample_rows_logprobs", "april_sample_rows_noalloc", "april_profile_enable", "april_profile_get",
     "april_profile_reset", "april_get_info", "april_last_error", "april_destroy",
 ]
@@ -44,7 +45,7 @@ class april_model_cfg(C.Structure):
         ("max_inflight", C.c_int32), ("max_ctx", C.c_int32),
         ("sampler", C.c_int32), ("top_k", C.c_int32), ("temperature", C.c_float), ("seed", C.c_uint64),
         ("eos_token", C.c_int32), ("debug_logits", C.c_int32), ("top_p", C.c_float), ("logprobs", C.c_int32),
-        ("n_samples_per_prompt", C.c_int32), ("stream", C.c_void_p),
+        ("n_samples_per_prompt", C.c_int32), ("pausable", C.c_int32), ("stream", C.c_void_p),
     ]
 
 
@@ -113,6 +114,8 @@ def load_library():
     lib.april_buffer_free.argtypes = [vp, vp]
     lib.april_buffer_free.restype = None
     lib.april_update_weights.argtypes = [vp, C.POINTER(april_tensor), C.c_int32, C.c_int32]
+    lib.april_memory_pause.argtypes = [vp, C.c_int32]
+    lib.april_memory_resume.argtypes = [vp, C.c_int32]
     lib.april_debug_watch.argtypes = [vp, C.c_int64, C.c_int32, C.c_int32]
     lib.april_debug_logits.argtypes = [vp, C.c_int64, C.c_int32, C.POINTER(C.c_float), C.POINTER(C.c_int32)]
     lib.april_sample_rows.argtypes = [vp, vp, C.c_int32, C.POINTER(C.c_int64), C.POINTER(C.c_int32),
@@ -290,6 +293,14 @@ def april_buffer_import(ctx, partials: Sequence[dict]):
     return out
 
 
+def april_memory_pause(ctx, tags: int):
+    _check(ctx, load_library().april_memory_pause(ctx, tags))
+
+
+def april_memory_resume(ctx, tags: int):
+    _check(ctx, load_library().april_memory_resume(ctx, tags))
+
+
 def april_buffer_drop_kv(ctx, buffer):
     _check(ctx, load_library().april_buffer_drop_kv(ctx, buffer))
 
@@ -366,13 +377,13 @@ def april_get_info(ctx) -> dict:
 # ---------------------------------------------------------------------------
 def make_cfg(shape, *, max_inflight, max_ctx, sampler=APRIL_SAMPLER_GREEDY, top_k=1, temperature=1.0, seed=0,
              eos_token=-1, debug_logits=False, kv_pool_bytes=0, stream=None, top_p=0.0,
-             logprobs=False, n_samples_per_prompt=0) -> april_model_cfg:
+             logprobs=False, n_samples_per_prompt=0, pausable=False) -> april_model_cfg:
     return april_model_cfg(
         shape.n_layers, shape.d_model, shape.n_q_heads, shape.n_kv_heads, shape.head_dim, shape.d_ffn,
         shape.vocab, shape.n_experts, shape.experts_per_tok, shape.d_expert_ffn, shape.dtype,
         shape.rope_theta, shape.rms_eps, 16, kv_pool_bytes, max_inflight, max_ctx, sampler, top_k,
         temperature, seed, eos_token, 1 if debug_logits else 0, top_p, 1 if logprobs else 0,
-        n_samples_per_prompt, stream)
+        n_samples_per_prompt, 1 if pausable else 0, stream)
 
 
 def pack_weights(shape, weights_fp32: Dict[str, np.ndarray]) -> Dict[str, np.ndarray]:

@@ -165,6 +165,15 @@ struct april_ctx {
                                              // (a graph boundary costs about 4 us on the device: 45.6 -> 45.7 k tokens/s)
 
   int weight_version = 0;        // bumped by april_update_weights
+  // pausable memory (Section 3.3): allocations made while alloc_tag != 0 are virtual address
+  // ranges with physical memory mapped behind them in chunks, so the memory can be handed back
+  // and re-mapped at the same addresses
+  struct VmRegion { char* va; size_t bytes; int tag; std::vector<hipMemGenericAllocationHandle_t> chunks; bool mapped; };
+  std::vector<VmRegion> vm_regions;
+  int alloc_tag = 0;
+  size_t vm_granularity = 0;
+  int paused_tags = 0;           // tags whose physical memory is released right now
+  bool weights_valid = true;     // false between a resume of the weights' memory and the next april_update_weights
   int device = 0;                // HIP device the context lives on
   unsigned char* scratch_dev = nullptr;   // this device's copy of the static scratch array
 
@@ -214,10 +223,77 @@ int fail(april_ctx* c, int code, const char* fmt, ...) {
       return fail(c, APRIL_EDEVICE, "%s failed: %s (%s:%d)", #expr, hipGetErrorString(e_), __FILE__, __LINE__); \
   } while (0)
 
+constexpr size_t VM_CHUNK = (size_t)1 << 30;      // physical memory is created and mapped in pieces of this size
+
+// Physical memory behind a region: create, map at the region's address, allow access.
+int vm_map_region(april_ctx* c, april_ctx::VmRegion& r) {
+  hipMemAllocationProp prop{};
+  prop.type = hipMemAllocationTypePinned;
+  prop.location.type = hipMemLocationTypeDevice;
+  prop.location.id = c->device;
+  hipMemAccessDesc acc{};
+  acc.location = prop.location;
+  acc.flags = hipMemAccessFlagsProtReadWrite;
+  for (size_t off = 0; off < r.bytes; off += VM_CHUNK) {
+    const size_t n = std::min(VM_CHUNK, r.bytes - off);
+    hipMemGenericAllocationHandle_t h;
+    hipError_t e = hipMemCreate(&h, n, &prop, 0);
+    if (e != hipSuccess) return fail(c, APRIL_ENOMEM, "hipMemCreate(%zu bytes) failed: %s", n, hipGetErrorString(e));
+    e = hipMemMap(r.va + off, n, 0, h, 0);
+    if (e != hipSuccess) { hipMemRelease(h); return fail(c, APRIL_EDEVICE, "hipMemMap failed: %s", hipGetErrorString(e)); }
+    r.chunks.push_back(h);
+    e = hipMemSetAccess(r.va + off, n, &acc, 1);
+    if (e != hipSuccess) return fail(c, APRIL_EDEVICE, "hipMemSetAccess failed: %s", hipGetErrorString(e));
+  }
+  r.mapped = true;
+  return APRIL_OK;
+}
+// Hand the physical memory of a region back; the address range stays reserved.
+void vm_unmap_region(april_ctx::VmRegion& r) {
+  size_t off = 0;
+  for (auto h : r.chunks) {
+    const size_t n = std::min(VM_CHUNK, r.bytes - off);
+    hipMemUnmap(r.va + off, n);
+    hipMemRelease(h);
+    off += n;
+  }
+  r.chunks.clear();
+  r.mapped = false;
+}
+int vm_alloc(april_ctx* c, void** p, size_t bytes, int tag) {
+  if (c->vm_granularity == 0) {
+    hipMemAllocationProp prop{};
+    prop.type = hipMemAllocationTypePinned;
+    prop.location.type = hipMemLocationTypeDevice;
+    prop.location.id = c->device;
+    size_t g = 0;
+    hipError_t e = hipMemGetAllocationGranularity(&g, &prop, hipMemAllocationGranularityRecommended);
+    if (e != hipSuccess || g == 0) return fail(c, APRIL_EDEVICE, "hipMemGetAllocationGranularity failed: %s", hipGetErrorString(e));
+    if (VM_CHUNK % g) return fail(c, APRIL_EDEVICE, "allocation granularity %zu does not divide the chunk size", g);
+    c->vm_granularity = g;
+  }
+  const size_t rounded = (bytes + c->vm_granularity - 1) / c->vm_granularity * c->vm_granularity;
+  void* va = nullptr;
+  hipError_t e = hipMemAddressReserve(&va, rounded, c->vm_granularity, nullptr, 0);
+  if (e != hipSuccess) return fail(c, APRIL_ENOMEM, "hipMemAddressReserve(%zu bytes) failed: %s", rounded, hipGetErrorString(e));
+  c->vm_regions.push_back({(char*)va, rounded, tag, {}, false});
+  int rc = vm_map_region(c, c->vm_regions.back());
+  if (rc != APRIL_OK) return rc;
+  *p = va;
+  return APRIL_OK;
+}
+
 template <typename T>
 int dev_alloc(april_ctx* c, T** p, size_t n_elems, bool zero = true) {
   void* q = nullptr;
   size_t bytes = std::max<size_t>(n_elems * sizeof(T), 256);
+  if (c->alloc_tag != 0) {
+    int rc = vm_alloc(c, &q, bytes, c->alloc_tag);
+    if (rc != APRIL_OK) return rc;
+    if (zero && hipMemsetAsync(q, 0, bytes, c->stream) != hipSuccess) return fail(c, APRIL_EDEVICE, "hipMemsetAsync failed");
+    *p = reinterpret_cast<T*>(q);
+    return APRIL_OK;
+  }
   hipError_t e = hipMalloc(&q, bytes);
   if (e != hipSuccess) return fail(c, APRIL_ENOMEM, "hipMalloc(%zu bytes) failed: %s", bytes, hipGetErrorString(e));
   if (zero) {
@@ -710,7 +786,8 @@ int april_init(const april_model_cfg* cfg, const april_tensor* weights, int32_t 
   c->scratch_dev = g_scratch_ptr[c->device];
 
   // ---- weights ------------------------------------------------------------------
-  TRY(load_weights(c, weights, n_weights));
+  c->alloc_tag = g.pausable ? APRIL_MEM_WEIGHTS : 0;
+  { int rc_w = load_weights(c, weights, n_weights); c->alloc_tag = 0; if (rc_w != APRIL_OK) return bail(rc_w); }
   const size_t e = c->esz;
 
   // ---- scheduler state ------------------------------------------------------------
@@ -761,7 +838,8 @@ int april_init(const april_model_cfg* cfg, const april_tensor* weights, int32_t 
   c->n_pages = (int)std::min<int64_t>(pool / page_bytes, (int64_t)1 << 30);
   if (c->n_pages < 1) { fail(c, APRIL_ENOMEM, "KV pool smaller than one page"); return bail(APRIL_ENOMEM); }
   c->kv_pool_bytes = (int64_t)c->n_pages * page_bytes;
-  TRY(dev_alloc_bytes(c, &c->kv_pool, (size_t)c->kv_pool_bytes, true));   // zeroed: masked lanes must stay finite
+  c->alloc_tag = g.pausable ? APRIL_MEM_KV : 0;
+  { int rc_kv = dev_alloc_bytes(c, &c->kv_pool, (size_t)c->kv_pool_bytes, true); c->alloc_tag = 0; if (rc_kv != APRIL_OK) return bail(rc_kv); }   // zeroed: masked lanes must stay finite
   c->kvl.n_kv_heads = g.n_kv_heads; c->kvl.head_dim = g.head_dim; c->kvl.blk = 16;
   c->kvl.mode = c->attn_mfma ? 1 : 0;
   c->kvl.kv_stride = (size_t)c->n_pages * nkv * 16;
@@ -866,6 +944,7 @@ void april_destroy(april_ctx* c) {
   if (!c) return;
   if (c->stream) hipStreamSynchronize(c->stream);
   for (void* p : c->allocs) hipFree(p);
+  for (auto& r : c->vm_regions) { if (r.mapped) vm_unmap_region(r); hipMemAddressFree(r.va, r.bytes); }
   if (c->h_ctrl) hipHostFree(c->h_ctrl);
   if (c->h_slot_arrays) hipHostFree(c->h_slot_arrays);
   if (c->h_req) hipHostFree(c->h_req);
@@ -1031,8 +1110,10 @@ void april_buffer_free(april_ctx* c, april_buffer* buffer) {
 // under the new one (Section 2.2, mixed-policy trajectories).
 int april_update_weights(april_ctx* c, const april_tensor* weights, int32_t n_weights, int32_t keep_kv) {
   if (!c || !weights || n_weights <= 0) return APRIL_EINVAL;
+  if (c->paused_tags & APRIL_MEM_WEIGHTS) return fail(c, APRIL_EINVAL, "the weights' memory is paused: call april_memory_resume first");
   HIPCHK(c, hipStreamSynchronize(c->stream));
   { int rc = load_weights(c, weights, n_weights); if (rc != APRIL_OK) return rc; }
+  c->weights_valid = true;
   if (!keep_kv) {
     // K/V computed under the old weights are not the new policy's: every parked or pending
     // rollout gives its pages back and is re-prefilled when it is resumed
@@ -1046,6 +1127,42 @@ int april_update_weights(april_ctx* c, const april_tensor* weights, int32_t n_we
     }
   }
   c->weight_version += 1;
+  return APRIL_OK;
+}
+
+// Release / re-map the physical memory behind the KV pool and the weights (Section 3.3: the
+// rollout engine and the trainer share the GPU; addresses stay, so captured graphs stay valid).
+int april_memory_pause(april_ctx* c, int32_t tags) {
+  if (!c) return APRIL_EINVAL;
+  if (!c->cfg.pausable) return fail(c, APRIL_EINVAL, "context was not created with pausable = 1");
+  if (tags & ~(APRIL_MEM_KV | APRIL_MEM_WEIGHTS)) return fail(c, APRIL_EINVAL, "unknown memory tag");
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  HIPCHK(c, hipDeviceSynchronize());
+  for (auto& r : c->vm_regions)
+    if ((r.tag & tags) && r.mapped) vm_unmap_region(r);
+  if ((tags & APRIL_MEM_KV) && !(c->paused_tags & APRIL_MEM_KV)) {
+    // the K/V of every parked rollout is gone with the pool: they keep their tokens and are
+    // re-prefilled when resumed
+    for (auto& sh : c->slots) { sh.n_blocks = 0; sh.kv_len = 0; }
+    c->free_pages_host = c->n_pages;
+  }
+  if (tags & APRIL_MEM_WEIGHTS) c->weights_valid = false;
+  c->paused_tags |= tags;
+  return APRIL_OK;
+}
+int april_memory_resume(april_ctx* c, int32_t tags) {
+  if (!c) return APRIL_EINVAL;
+  if (!c->cfg.pausable) return fail(c, APRIL_EINVAL, "context was not created with pausable = 1");
+  tags &= c->paused_tags;
+  for (auto& r : c->vm_regions)
+    if ((r.tag & tags) && !r.mapped) { int rc = vm_map_region(c, r); if (rc != APRIL_OK) return rc; }
+  if (tags & APRIL_MEM_KV) {
+    HIPCHK(c, hipMemsetAsync(c->kv_pool, 0, (size_t)c->kv_pool_bytes, c->stream));   // masked lanes must stay finite
+    launch_init_free_stack(c->stream, c->d_free_stack, c->n_pages);
+    // per-slot page counts on the device follow the host mirrors at the next step; the stack top too
+    HIPCHK(c, hipStreamSynchronize(c->stream));
+  }
+  c->paused_tags &= ~tags;
   return APRIL_OK;
 }
 
@@ -1211,6 +1328,8 @@ int april_rollout_step(april_ctx* c, const april_request* new_reqs, int32_t n_ne
   if (!c || !out) return APRIL_EINVAL;
   if (N_target <= 0 || N_over < N_target || max_new <= 0 || n_new_avail < 0 || (n_new_avail > 0 && !new_reqs))
     return fail(c, APRIL_EINVAL, "bad step arguments (need 0 < N_target <= N_overprovision, max_new > 0)");
+  if (c->paused_tags) return fail(c, APRIL_EINVAL, "the engine's memory is paused: call april_memory_resume first");
+  if (!c->weights_valid) return fail(c, APRIL_EINVAL, "the weights' memory was released and re-mapped: call april_update_weights first");
   const double t_begin = now_s();
   hipStream_t st = c->stream;
   const int blk = 16;

@@ -21,14 +21,14 @@ def sampler_name(w):
 
 
 def make_engine(w, weights, *, debug=False, max_inflight=None, max_ctx=None, temperature=1.0, eos=-1,
-                kv_pool_bytes=0, top_p=0.0, logprobs=False, sampler=None, group_size=0):
+                kv_pool_bytes=0, top_p=0.0, logprobs=False, sampler=None, group_size=0, pausable=False):
     s = w.shape
     cfg = ap.make_cfg(s, max_inflight=max_inflight or (w.n_overprovision + 8),
                       max_ctx=max_ctx or (w.prompt_len + w.max_new + 16),
                       sampler=w.sampler if sampler is None else sampler, top_k=max(w.top_k, 1),
                       temperature=temperature, seed=w.seed, eos_token=eos, debug_logits=debug,
                       kv_pool_bytes=kv_pool_bytes, top_p=top_p, logprobs=logprobs,
-                      n_samples_per_prompt=group_size)
+                      n_samples_per_prompt=group_size, pausable=pausable)
     return ap.april_init(cfg, ap.pack_weights(s, weights))
 
 

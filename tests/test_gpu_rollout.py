@@ -299,6 +299,65 @@ def test_instance_level_group_completion(G, n_target, n_over):
         ap().april_destroy(solo_ctx)
 
 
+@pytest.mark.parametrize("dtype", [ai.DTYPE_FP32, ai.DTYPE_BF16])
+def test_memory_pause_and_resume_by_remapping(dtype):
+    """cfg.pausable: between two steps the physical memory behind the KV pool and the weights is
+    released (the free device memory grows by about their size) and mapped again at the same
+    addresses; the weights are pushed again, the parked rollouts are re-prefilled, and the run goes
+    on - replaying the iteration graphs captured before the pause - exactly like a run whose buffer
+    dropped its KV at the same point (same kernels, same order: identical tokens)."""
+    A = ap()
+    shape = ai.ModelShape(2, 128, 4, 2, 32, 256, 512, dtype=dtype)
+    w = ai.Workload("pause", shape, 8, 21, 6, 10, 40, 2.6, 0.7, 2, 40, ai.SAMPLER_GREEDY, 0, 4, 21)
+    weights = ai.make_weights(shape, w.seed)
+    reqs = ai.make_requests(w, ai.requests_needed(w))
+    ref_ctx = make_engine(w, weights)
+    try:
+        def drop_after_second(state={"k": 0}):
+            def f(c, buf):
+                state["k"] += 1
+                if state["k"] == 2:
+                    A.april_buffer_drop_kv(c, buf)
+                return buf
+            return f
+        want = run_gpu(ref_ctx, reqs, w.n_target, w.n_overprovision, w.max_new, 4, between=drop_after_second())
+    finally:
+        A.april_destroy(ref_ctx)
+    ctx = make_engine(w, weights, pausable=True, kv_pool_bytes=256 << 20)
+    try:
+        got, nxt = [], 0
+        for k in range(4):
+            res = A.april_rollout_step(ctx, req_dicts(reqs[nxt:]), w.n_target, w.n_overprovision, w.max_new)
+            nxt += res.n_new_consumed
+            view = A.april_buffer_export(ctx, res.buffer)
+            got.append(dict(ids=res.request_id, tokens=[t.tolist() for t in res.tokens], n_resumes=res.n_resumes,
+                            consumed=res.n_new_consumed, iters=res.decode_iters, generated=res.tokens_generated,
+                            buffer=[(p["request_id"], len(p["generated"]), p["done"]) for p in view],
+                            reprefill=res.reprefill_tokens))
+            A.april_resume(ctx, res.buffer)
+            if k == 1:
+                before = A.april_get_info(ctx)
+                A.april_memory_pause(ctx, A.APRIL_MEM_KV | A.APRIL_MEM_WEIGHTS)
+                paused = A.april_get_info(ctx)
+                released = paused["hbm_free"] - before["hbm_free"]
+                assert released >= 0.9 * (before["kv_pool_bytes"] + before["weight_bytes"]), (released, before)
+                with pytest.raises(A.AprilError):                      # nothing runs while paused
+                    A.april_rollout_step(ctx, req_dicts(reqs[nxt:]), w.n_target, w.n_overprovision, w.max_new)
+                A.april_memory_resume(ctx, A.APRIL_MEM_KV | A.APRIL_MEM_WEIGHTS)
+                with pytest.raises(A.AprilError):                      # the weights' memory came back empty
+                    A.april_rollout_step(ctx, req_dicts(reqs[nxt:]), w.n_target, w.n_overprovision, w.max_new)
+                A.april_update_weights(ctx, A.pack_weights(shape, weights))
+                after = A.april_get_info(ctx)
+                assert after["kv_blocks_free"] == after["kv_blocks_total"]
+                assert abs(after["hbm_free"] - before["hbm_free"]) < 64 << 20
+        assert got[2]["reprefill"] > 0
+        assert_schedule_equal(got, want)
+        for g, o in zip(got, want):
+            assert g["tokens"] == o["tokens"]
+    finally:
+        A.april_destroy(ctx)
+
+
 @pytest.mark.parametrize("name", list(ai.WORKLOADS))
 def test_scheduling_bit_exact_at_all_five_configs(name):
     """Scheduling depends only on the forced lengths, so each configuration's N, N',

@@ -33,18 +33,21 @@ def note(msg):
     print(f"[bench {time.strftime('%H:%M:%S')}] {msg}", file=sys.stderr, flush=True)
 
 
-def run_arm(ap, ctx, reqs, n_target, n_over, max_new, steps, profile_every=0):
-    """Run `steps` rollout steps from a clean context state; returns per-step results."""
+def run_arm(ap, ctx, reqs, n_target, n_over, max_new, steps, profile_every=0, between=None):
+    """Run `steps` rollout steps from a clean context state; returns per-step results.
+    between(ctx): called after every step but the last (e.g. a weight update)."""
     ap.april_profile_enable(ctx, profile_every)
     nxt, results = 0, []
     t0 = time.perf_counter()
-    for _ in range(steps):
+    for k in range(steps):
         new = [dict(request_id=r.request_id, tokens=r.tokens, forced_len=r.forced_len) for r in reqs[nxt:nxt + n_over]]
         res = ap.april_rollout_step(ctx, new, n_target, n_over, max_new)
         nxt += res.n_new_consumed
         results.append(res)
         note(f"step {len(results)}/{steps}: {res.tokens_generated} tokens in {res.t_total_s:.2f} s, {res.decode_iters} iterations")
         ap.april_resume(ctx, res.buffer)
+        if between is not None and k + 1 < steps:
+            between(ctx)
     import torch
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
@@ -143,6 +146,9 @@ def main():
     p.add_argument("--profile-every", type=int, default=128,
                    help="every n-th decode iteration runs eagerly with an event pair around each launch (0 = never)")
     p.add_argument("--verbose", action="store_true", help="progress lines on stderr")
+    p.add_argument("--update-weights", type=int, default=0, metavar="STEPS",
+                   help="extra APRIL arm of STEPS steps with a policy update (april_update_weights, device-resident "
+                        "source) after every step: once re-prefilling the parked rollouts, once keeping their stale KV")
     p.add_argument("--kv-pool-gib", type=float, default=0.0, help="KV pool size (0 = the library's default)")
     p.add_argument("--copy-calibration", action="store_true",
                    help="also run three 1 GiB device copies first (reference dispatches for --pmc counter runs)")
@@ -285,6 +291,30 @@ def main():
         out["wait_all"] = {"steps": wait_steps, "tokens_generated": tok_wait, "decode_iters": sum(r.decode_iters for r in res_wait),
                            "step_time_s": t_wait, "tokens_per_s": tok_wait / t_wait, "wall_s": wall_wait}
         out["april_speedup_vs_wait_all"] = value / (tok_wait / t_wait)
+    if args.update_weights > 0:
+        # the trainer's new weights would already be on this GPU: keep a device copy as the source
+        dev_w = {k: torch.from_numpy(v.view(np.int16) if v.dtype == np.uint16 else v).cuda() for k, v in packed.items()}
+        out["weight_update"] = {"steps": args.update_weights}
+        for label, keep in (("reprefill", False), ("stale_kv", True)):
+            reset_engine()
+            t_upd = []
+
+            def upd(c, keep=keep):
+                t0 = time.perf_counter()
+                ap.april_update_weights(c, dev_w, keep_kv=keep)
+                torch.cuda.synchronize()
+                t_upd.append(time.perf_counter() - t0)
+            res_u, _ = run_arm(ap, ctx, reqs, w.n_target, w.n_overprovision, w.max_new, args.update_weights, 0, between=upd)
+            tok_u, t_u = sum(r.tokens_generated for r in res_u), sum(r.t_total_s for r in res_u)
+            out["weight_update"][label] = {
+                "tokens_per_s": tok_u / t_u, "tokens_per_s_including_update_calls": tok_u / (t_u + sum(t_upd)),
+                "update_call_s": sum(t_upd) / max(len(t_upd), 1), "reprefill_tokens": sum(r.reprefill_tokens for r in res_u),
+                "prefill_time_s": sum(r.t_prefill_s for r in res_u), "step_time_s": t_u, "tokens_generated": tok_u}
+        # the KV-resident number over the same steps of the main arm
+        t_same = sum(r.t_total_s for r in res_april[:args.update_weights])
+        out["weight_update"]["kv_resident_tokens_per_s_same_steps"] = (
+            sum(r.tokens_generated for r in res_april[:args.update_weights]) / t_same if t_same > 0 else None)
+        del dev_w
     ap.april_destroy(ctx)
 
     if not args.no_cpu_baseline:

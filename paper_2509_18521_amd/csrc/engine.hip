@@ -123,6 +123,9 @@ struct april_ctx {
   int prefill_cap = 0;
   int *d_pf_row_slot = nullptr, *d_pf_row_pos = nullptr, *d_pf_nrows = nullptr;
   int *d_pf_srow_slot = nullptr, *d_pf_srow_pos = nullptr, *d_pf_nsrows = nullptr, *d_pf_gather = nullptr;
+  int4* d_pf_items = nullptr;    // query tiles of the chunk's sequences (prefill attention)
+  int pf_n_items = 0, pf_items_cap = 0;
+  bool prefill_tiled = true;     // query-tiled prefill attention (APRIL_PREFILL_ATTN=rows: one workgroup per row)
   int *d_list_a = nullptr, *d_list_b = nullptr;
   int* h_stage = nullptr;        // pinned
   size_t h_stage_ints = 0;
@@ -547,7 +550,13 @@ void forward(april_ctx* c, RowCtx rows, RowCtx srows, const int* gather, double 
       if (c->bf16) launch_rope_append<bf16_t>(st, rows, c->ds, c->qkv, sq, c->qkv_stride, c->rope_cos, c->rope_sin, c->q_rot, (bf16_t*)c->kv_pool, c->kvl, l, Hq);
       else launch_rope_append<float>(st, rows, c->ds, c->qkv, sq, c->qkv_stride, c->rope_cos, c->rope_sin, c->q_rot, (float*)c->kv_pool, c->kvl, l, Hq);
     }
-    if (c->attn_mfma) {
+    if (c->attn_mfma && gather != nullptr && c->prefill_tiled) {
+      // prefill: one workgroup per tile of query positions, the keys / values of a prompt are
+      // streamed once per tile instead of once per row
+      ProfScope p(c, KC_ATTN, C * 2.0 * nkv * e + B * nq * (4.0 + e), 4.0 * C * nq);
+      launch_attn_prefill(st, c->d_pf_items, c->pf_n_items, c->ds, c->q_rot, (const bf16_t*)c->kv_pool, c->kvl, l, Hq,
+                          (bf16_t*)c->attn_out);
+    } else if (c->attn_mfma) {
       const int gs = std::min(c->attn_max_splits, std::max(1, ceil_div(c->step_max_ctx, c->attn_chunk)));
       for (int base = 0; base < rows.max_rows; base += c->attn_ws_rows) {
         RowCtx sub = rows;
@@ -764,6 +773,8 @@ int april_init(const april_model_cfg* cfg, const april_tensor* weights, int32_t 
     if (sscanf(fa, "%d:%d", &c->debug_fail_step, &c->debug_fail_iter) != 2) c->debug_fail_step = c->debug_fail_iter = -1;
   }
   if (const char* gi = getenv("APRIL_GRAPH_ITERS")) c->graph_iters = std::max(1, std::min(16, atoi(gi)));
+  const char* pa = getenv("APRIL_PREFILL_ATTN");
+  c->prefill_tiled = !(pa && !strcmp(pa, "rows"));
   const char* tg = getenv("APRIL_TILE_GEMM");
   c->tile_gemm = !(tg && !strcmp(tg, "0"));
   const char* gr = getenv("APRIL_GRAPH");
@@ -905,7 +916,9 @@ int april_init(const april_model_cfg* cfg, const april_tensor* weights, int32_t 
   TRY(dev_alloc(c, &c->d_pf_row_slot, M)); TRY(dev_alloc(c, &c->d_pf_row_pos, M));
   TRY(dev_alloc(c, &c->d_pf_nrows, 2)); TRY(dev_alloc(c, &c->d_pf_nsrows, 2));   // {rows, stop = 0}
   TRY(dev_alloc(c, &c->d_pf_srow_slot, S)); TRY(dev_alloc(c, &c->d_pf_srow_pos, S)); TRY(dev_alloc(c, &c->d_pf_gather, S));
-  c->h_stage_ints = 2 * M + 8 * (size_t)S + 64;
+  c->pf_items_cap = (int)(M / 16 + S + 16);
+  TRY(dev_alloc(c, &c->d_pf_items, (size_t)c->pf_items_cap));
+  c->h_stage_ints = 2 * M + 8 * (size_t)S + 64 + 4 * (size_t)c->pf_items_cap;
   HIPTRY(hipHostMalloc((void**)&c->h_stage, c->h_stage_ints * sizeof(int)));
 
   // ---- parity-mode capture ----------------------------------------------------------
@@ -1621,11 +1634,15 @@ int april_rollout_step(april_ctx* c, const april_request* new_reqs, int32_t n_ne
       int* h_row_slot = hs; int* h_row_pos = hs + c->m_cap;
       int* h_ss = hs + 2 * (size_t)c->m_cap; int* h_sp = h_ss + c->n_slots; int* h_g = h_sp + c->n_slots;
       int* h_list = h_g + c->n_slots; int* h_need = h_list + c->n_slots; int* h_n = h_need + c->n_slots;
+      int4* h_items = reinterpret_cast<int4*>(hs + 2 * (size_t)c->m_cap + 8 * (size_t)c->n_slots + 64);
+      const int q_tile = attn_prefill_tile(c->dm.n_q_heads / c->dm.n_kv_heads);
+      int n_items = 0;
       while (pi < prefill_slots.size()) {
         const int s = prefill_slots[pi];
         const SlotH& sh = c->slots[s];
         const int nt = sh.prompt_len + sh.gen;
         if (rows + nt > c->prefill_cap && nseq > 0) break;
+        for (int q0 = 0; q0 < nt && n_items < c->pf_items_cap; q0 += q_tile) h_items[n_items++] = int4{s, rows, nt, q0};
         for (int p = 0; p < nt; ++p) { h_row_slot[rows + p] = s; h_row_pos[rows + p] = p; }
         h_ss[nseq] = s; h_sp[nseq] = nt - 1; h_g[nseq] = rows + nt - 1;
         h_list[nseq] = s; h_need[nseq] = ceil_div(nt, blk);
@@ -1641,6 +1658,8 @@ int april_rollout_step(april_ctx* c, const april_request* new_reqs, int32_t n_ne
       HIPCHK(c, hipMemcpyAsync(c->d_pf_gather, h_g, nseq * sizeof(int), hipMemcpyHostToDevice, st));
       HIPCHK(c, hipMemcpyAsync(c->d_pf_nrows, h_n, sizeof(int), hipMemcpyHostToDevice, st));
       HIPCHK(c, hipMemcpyAsync(c->d_pf_nsrows, h_n + 1, sizeof(int), hipMemcpyHostToDevice, st));
+      HIPCHK(c, hipMemcpyAsync(c->d_pf_items, h_items, n_items * sizeof(int4), hipMemcpyHostToDevice, st));
+      c->pf_n_items = n_items;
       RowCtx prc{c->d_pf_row_slot, c->d_pf_row_pos, reinterpret_cast<const int2*>(c->d_pf_nrows), rows};
       RowCtx src{c->d_pf_srow_slot, c->d_pf_srow_pos, reinterpret_cast<const int2*>(c->d_pf_nsrows), nseq};
       forward(c, prc, src, c->d_pf_gather, rows, 0);

@@ -100,6 +100,13 @@ void launch_attn_decode(hipStream_t st, RowCtx rc, int row_base, Slots s, const 
                         float* ws, int max_splits, int grid_splits,
                         const float* fused_qkv, int n_partials, size_t partial_stride,
                         const float* rope_cos, const float* rope_sin);
+// Causal attention over prefill rows, one workgroup per (item, KV head); an item = {slot, first
+// row of the sequence in the row arrays, tokens of the sequence, first position of the tile},
+// tiles of attn_prefill_tile(query heads per KV head) positions.  q_rot and the pages must hold
+// the rotated queries / keys and the values of every row (launch_rope_append first).
+int attn_prefill_tile(int group);
+void launch_attn_prefill(hipStream_t st, const int4* items, int n_items, Slots s, const float* q_rot,
+                         const bf16_t* kv_pool, KVLayout kvl, int layer, int n_q_heads, bf16_t* out);
 // Merge of the KV-split partials (needed after launch_attn_decode whenever grid_splits > 1).
 void launch_attn_merge(hipStream_t st, RowCtx rc, int row_base, KVLayout kvl, int n_q_heads, bf16_t* out,
                        const float* ws, int max_splits);

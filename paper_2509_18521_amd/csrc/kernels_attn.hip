@@ -486,6 +486,203 @@ __global__ __launch_bounds__(64) void attn_merge_kernel(RowCtx rc, int row_base,
   }
 }
 
+// ---------------------------------------------------------------------------
+// Causal attention of prefill rows, tiled over queries.
+//
+// The decode kernel serves one query position per workgroup; run over the rows of a prompt it
+// reads the prompt's keys and values once per position.  Here a workgroup owns a tile of query
+// positions of one (sequence, KV head) and streams the keys / values 0 .. last position of the
+// tile once, for all of them and for all query heads of the KV head.
+//
+// Same transposed products as the decode kernel (S^T = K . Q^T, O^T = V^T . P^T on
+// v_mfma_f32_16x16x32_bf16), with the 16 columns of a product holding (position, head) pairs:
+// column = position_in_tile * GP + head, GP = heads per KV head rounded up to a power of two.
+// A wavefront keeps CT = 4 column tiles (its own positions: 64 / GP of them), so a K / V tile
+// fetched once feeds four products; the four wavefronts of a workgroup take consecutive groups
+// of positions and walk the same K / V tiles (second and later readers hit the L1 / L2).
+// Every column runs its own online softmax over the 32-token tiles in order; positions beyond
+// the column's own are masked.  A sequence's result does not depend on what else is in the
+// chunk.  (Its summation order differs from the decode kernel's; so does the prefill GEMM's.)
+// ---------------------------------------------------------------------------
+template <int DH, int GP>
+__global__ __launch_bounds__(256) void attn_prefill_kernel(const int4* __restrict__ items, Slots s,
+                                                           const float* __restrict__ q_rot,
+                                                           const bf16_t* __restrict__ kv_pool, KVLayout L, int layer,
+                                                           int Hq, bf16_t* __restrict__ out) {
+  constexpr int KC = DH / 32, DT = DH / 16, CT = 4;
+  constexpr int PPT = 16 / GP;            // positions per column tile
+  constexpr int PPW = CT * PPT;           // positions per wavefront
+  const int4 it = items[blockIdx.x];      // {slot, first row of the sequence, tokens of the sequence, first position of the tile}
+  const int slot = it.x, row0 = it.y, nt = it.z, q0 = it.w;
+  const int kvh = blockIdx.y;
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), hh = lane & 15, g = lane >> 4;
+  const int Hkv = L.n_kv_heads, G = Hq / Hkv;
+  const int wq0 = q0 + wave * PPW;        // this wavefront's first position
+  if (wq0 >= nt) return;                  // (no workgroup barrier below)
+  const int wlast = min(nt, wq0 + PPW) - 1;
+  const size_t blk_elems = (size_t)16 * DH;
+  const bf16_t* kbase = kv_pool + (size_t)layer * L.layer_stride;
+  const bf16_t* vbase = kbase + L.kv_stride;
+  const int* bt = s.block_table + (size_t)slot * s.max_blocks;
+  const int last_page = wlast >> 4;
+
+  // query fragments: column hh of tile ct = (position, head)
+  int qpos[CT];
+  bool qok[CT];
+  bf16x8 qf[CT][KC];
+#pragma unroll
+  for (int ct = 0; ct < CT; ++ct) {
+    const int p = wq0 + ct * PPT + hh / GP, h = hh % GP;
+    qok[ct] = p < nt && h < G;
+    qpos[ct] = p < nt ? p : nt - 1;
+    const int hc = h < G ? h : G - 1;
+    const float* q = q_rot + (size_t)(row0 + qpos[ct]) * Hq * DH + (size_t)(kvh * G + hc) * DH + 8 * g;
+#pragma unroll
+    for (int c = 0; c < KC; ++c) {
+      const f32x4 a = *reinterpret_cast<const f32x4*>(q + 32 * c), b = *reinterpret_cast<const f32x4*>(q + 32 * c + 4);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) { qf[ct][c][j] = qok[ct] ? (bf16_t)a[j] : (bf16_t)0.f; qf[ct][c][4 + j] = qok[ct] ? (bf16_t)b[j] : (bf16_t)0.f; }
+    }
+  }
+  const float scale = 1.0f / sqrtf((float)DH);
+  float m_run[CT], l_run[CT];
+  f32x4 oacc[CT][DT];
+#pragma unroll
+  for (int ct = 0; ct < CT; ++ct) {
+    m_run[ct] = -INFINITY; l_run[ct] = 0.f;
+#pragma unroll
+    for (int d = 0; d < DT; ++d) oacc[ct][d] = f32x4{};
+  }
+
+  const int n_tiles = (wlast >> 5) + 1;
+  int my_page = bt[lane < last_page ? lane : last_page];     // page ids of tiles 0..31 (64 pages), one per lane
+  auto load_tile = [&](int tile, bf16x8 (&kk)[2][KC], bf16x4 (&vv)[2][DT]) {
+#pragma unroll
+    for (int p = 0; p < 2; ++p) {
+      int pl = 2 * tile + p;
+      pl = pl < last_page ? pl : last_page;                   // a missing second page re-reads the last one (masked)
+      const int page = __builtin_amdgcn_readlane(my_page, __builtin_amdgcn_readfirstlane(pl) & 63);
+      const size_t off = ((size_t)page * Hkv + kvh) * blk_elems;
+      const bf16x8* kp = reinterpret_cast<const bf16x8*>(kbase + off);
+      const bf16x4* vp = reinterpret_cast<const bf16x4*>(vbase + off);
+#pragma unroll
+      for (int c = 0; c < KC; ++c) kk[p][c] = kp[c * 64 + lane];
+#pragma unroll
+      for (int d = 0; d < DT; ++d) vv[p][d] = vp[(d * 16 + hh) * 4 + g];
+    }
+  };
+  bf16x8 kf[2][KC];
+  bf16x4 vf[2][DT];
+  load_tile(0, kf, vf);
+  for (int tile = 0; tile < n_tiles; ++tile) {
+    bf16x8 kn[2][KC];
+    bf16x4 vn[2][DT];
+    const int nxt = tile + 1 < n_tiles ? tile + 1 : tile;
+    if ((nxt & 31) == 0 && nxt != tile) {                     // the next tile opens a new group of 64 pages
+      const int i = nxt * 2 + lane;
+      my_page = bt[i < last_page ? i : last_page];
+    }
+    load_tile(nxt, kn, vn);
+    __builtin_amdgcn_sched_barrier(0);
+    const int t0 = tile * 32;
+    bf16x8 af[DT];
+#pragma unroll
+    for (int d = 0; d < DT; ++d)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) { af[d][j] = vf[0][d][j]; af[d][4 + j] = vf[1][d][j]; }
+#pragma unroll
+    for (int ct = 0; ct < CT; ++ct) {
+      if (t0 > __builtin_amdgcn_readfirstlane(wq0 + ct * PPT + PPT - 1)) continue;   // the tile lies beyond every position of this column tile
+      f32x4 sacc[2];
+#pragma unroll
+      for (int p = 0; p < 2; ++p) {
+        sacc[p] = f32x4{};
+#pragma unroll
+        for (int c = 0; c < KC; ++c) sacc[p] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[p][c], qf[ct][c], sacc[p], 0, 0, 0);
+      }
+      float sv[8], mx = -INFINITY;
+#pragma unroll
+      for (int p = 0; p < 2; ++p)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int tok = t0 + p * 16 + 4 * g + i;
+          const float v = tok <= qpos[ct] ? sacc[p][i] * scale : -INFINITY;
+          sv[p * 4 + i] = v;
+          mx = fmaxf(mx, v);
+        }
+      mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      const float m_new = fmaxf(m_run[ct], mx);               // finite from the first tile on: token 0 is visible to every position
+      const float corr = __expf(m_run[ct] - m_new);
+      float rs = 0.f;
+      bf16x8 pf;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const float pe = __expf(sv[e] - m_new);
+        rs += pe;
+        pf[e] = (bf16_t)pe;
+      }
+      rs += __shfl_xor(rs, 16, 64);
+      rs += __shfl_xor(rs, 32, 64);
+      l_run[ct] = l_run[ct] * corr + rs;
+      m_run[ct] = m_new;
+#pragma unroll
+      for (int d = 0; d < DT; ++d) {
+        oacc[ct][d] *= corr;
+        oacc[ct][d] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[d], pf, oacc[ct][d], 0, 0, 0);
+      }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int p = 0; p < 2; ++p) {
+#pragma unroll
+      for (int c = 0; c < KC; ++c) kf[p][c] = kn[p][c];
+#pragma unroll
+      for (int d = 0; d < DT; ++d) vf[p][d] = vn[p][d];
+    }
+  }
+  const int K = Hq * DH;
+#pragma unroll
+  for (int ct = 0; ct < CT; ++ct) {
+    if (!qok[ct]) continue;
+    const float inv = 1.0f / l_run[ct];
+    const int r = row0 + qpos[ct], h = hh % GP;
+#pragma unroll
+    for (int d = 0; d < DT; ++d) {
+      bf16x4 ob;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) ob[i] = (bf16_t)(oacc[ct][d][i] * inv);
+      *reinterpret_cast<bf16x4*>(out + act_index<true>(r, (kvh * G + h) * DH + d * 16 + 4 * g, K)) = ob;
+    }
+  }
+}
+
+// positions per workgroup of the prefill attention for a model with `group` query heads per KV head
+int attn_prefill_tile(int group) {
+  int gp = 1;
+  while (gp < group) gp <<= 1;
+  return 4 * 4 * (16 / gp);
+}
+
+void launch_attn_prefill(hipStream_t st, const int4* items, int n_items, Slots s, const float* q_rot,
+                         const bf16_t* kv_pool, KVLayout kvl, int layer, int n_q_heads, bf16_t* out) {
+  if (n_items <= 0) return;
+  dim3 grid(n_items, kvl.n_kv_heads);
+  const int G = n_q_heads / kvl.n_kv_heads;
+  int gp = 1;
+  while (gp < G) gp <<= 1;
+#define ATT_PF(DH, GP) hipLaunchKernelGGL((attn_prefill_kernel<DH, GP>), grid, dim3(256), 0, st, items, s, q_rot, kv_pool, kvl, layer, n_q_heads, out)
+#define ATT_PF_G(DH) switch (gp) { case 1: ATT_PF(DH, 1); break; case 2: ATT_PF(DH, 2); break; case 4: ATT_PF(DH, 4); break; \
+                                   case 8: ATT_PF(DH, 8); break; default: ATT_PF(DH, 16); break; }
+  switch (kvl.head_dim) {
+    case 32: ATT_PF_G(32); break;
+    case 64: ATT_PF_G(64); break;
+    default: ATT_PF_G(128); break;
+  }
+#undef ATT_PF_G
+#undef ATT_PF
+}
+
 int attn_split_tokens(int head_dim) { return att_split(head_dim); }
 
 void launch_attn_decode(hipStream_t st, RowCtx rc, int row_base, Slots s, const float* q_rot, bf16_t* kv_pool,

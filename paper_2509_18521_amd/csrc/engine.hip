@@ -136,6 +136,8 @@ struct april_ctx {
   int m_cap = 0;
   float *x_res = nullptr, *qkv = nullptr, *q_rot = nullptr, *proj = nullptr, *gu = nullptr, *logits = nullptr;
   float* group_max = nullptr;  // per row, maxima of groups of lmhead_group_cols() logits (MFMA LM head)
+  int* group_idx = nullptr;    // ... and the column of each maximum (greedy sampling without logits)
+  bool write_logits = true;    // false: greedy sampling from the group records alone, the LM head writes no logits
   void *h_act = nullptr, *attn_out = nullptr, *act = nullptr, *hf = nullptr;
   float *rope_cos = nullptr, *rope_sin = nullptr;
   int s_qkv = 1, s_o = 1, s_down = 1;
@@ -634,23 +636,25 @@ void forward(april_ctx* c, RowCtx rows, RowCtx srows, const int* gather, double 
   }
   const double SB = gather ? (double)srows.max_rows : B;
   norm(srows, sd, c->final_norm, c->hf, gather, SB, true);
+  float* lg_out = c->write_logits ? c->logits : nullptr;
   {
     ProfScope p(c, KC_GEMM_LMHEAD, (double)V * d * e + SB * d * e, 2.0 * SB * V * d);
     // more than 128 sampling rows: the tiled kernel reads the head once per 256 rows instead of
     // once per 128 (same bits either way)
     if (c->use_mfma && c->group_max && c->tile_gemm && srows.max_rows > 128 && d % 32 == 0)
-      launch_gemm_tile_logits(st, srows, (const bf16_t*)c->hf, c->lm_head_s, c->logits, c->group_max, V, d);
-    else if (c->use_mfma && c->group_max) launch_gemm_mfma_logits(st, srows, (const bf16_t*)c->hf, c->lm_head_s, c->logits, c->group_max, V, d);
+      launch_gemm_tile_logits(st, srows, (const bf16_t*)c->hf, c->lm_head_s, lg_out, c->group_max, V, d, c->group_idx);
+    else if (c->use_mfma && c->group_max) launch_gemm_mfma_logits(st, srows, (const bf16_t*)c->hf, c->lm_head_s, lg_out, c->group_max, V, d, c->group_idx);
     else if (c->use_mfma) launch_gemm_mfma(st, srows, (const bf16_t*)c->hf, c->lm_head_s, c->logits, V, d, 1, 0);
     else if (c->bf16) launch_gemm_ref<bf16_t, true>(st, srows, (const bf16_t*)c->hf, (const bf16_t*)c->lm_head, c->logits, V, d);
     else launch_gemm_ref<float, false>(st, srows, (const float*)c->hf, (const float*)c->lm_head, c->logits, V, d);
   }
   {
-    ProfScope p(c, KC_SAMPLE, SB * V * 4.0, 0);
+    const bool fused = c->group_max && !c->write_logits;
+    ProfScope p(c, KC_SAMPLE, fused ? SB * (V / 64) * 8.0 : SB * V * 4.0, 0);
     const SamplerCfg sc = sampler_cfg(c);
     Watch w = c->cfg.debug_logits ? c->dwatch : Watch{};
     launch_sample(st, srows, c->ds, c->d_ctrl, c->logits, V, sc, w, 1, nullptr, nullptr, nullptr, c->group_max,
-                  lmhead_group_cols());
+                  lmhead_group_cols(), nullptr, c->group_max ? c->group_idx : nullptr);
   }
 }
 
@@ -894,7 +898,14 @@ int april_init(const april_model_cfg* cfg, const april_tensor* weights, int32_t 
   }
   const size_t SR = ((size_t)S + 31) / 32 * 32;
   TRY(dev_alloc(c, &c->logits, SR * V));
-  if (c->use_mfma && V % lmhead_group_cols() == 0) TRY(dev_alloc(c, &c->group_max, SR * (V / lmhead_group_cols())));
+  if (c->use_mfma && V % lmhead_group_cols() == 0) {
+    TRY(dev_alloc(c, &c->group_max, SR * (V / lmhead_group_cols())));
+    TRY(dev_alloc(c, &c->group_idx, SR * (V / lmhead_group_cols())));
+    // the fused sampler must not write logits: greedy sampling needs only the group records;
+    // parity mode, log-probabilities and the candidate search of the sampling modes read logits
+    const char* wl = getenv("APRIL_WRITE_LOGITS");
+    c->write_logits = g.debug_logits || g.logprobs || g.sampler != APRIL_SAMPLER_GREEDY || (wl && !strcmp(wl, "1"));
+  }
   TRY(dev_alloc_bytes(c, &c->h_act, M * d * e));
   TRY(dev_alloc_bytes(c, &c->attn_out, M * nq * e));
   TRY(dev_alloc_bytes(c, &c->act, M * std::max(F, 1) * e));

@@ -139,12 +139,15 @@ void launch_gemm_tile_swiglu(hipStream_t st, RowCtx rc, const bf16_t* x, const b
 bool launch_gemm_tile_swiglu_chain(hipStream_t st, RowCtx rc, const bf16_t* x, const bf16_t* Wg, const bf16_t* Wu,
                                    bf16_t* act, int F, int K, const float* ssq, int ssq_stride, float eps);
 void launch_gemm_tile_logits(hipStream_t st, RowCtx rc, const bf16_t* x, const bf16_t* Wp, float* logits,
-                             float* group_max, int V, int K);
+                             float* group_max, int V, int K, int* group_idx = nullptr);
 // LM head: logits fp32 [rows][V] plus, per row, the maximum of every group of
 // lmhead_group_cols() consecutive logits (group_max [rows][V / group]); V % 64 == 0.
+// group_idx (nullable, same shape): the column inside the group that holds the maximum, the
+// lowest one on ties.  logits may be null: nothing but the group records is written then (all
+// the greedy sampler needs).
 int lmhead_group_cols();
 void launch_gemm_mfma_logits(hipStream_t st, RowCtx rc, const bf16_t* x, const bf16_t* Wp, float* logits,
-                             float* group_max, int V, int K);
+                             float* group_max, int V, int K, int* group_idx = nullptr);
 void launch_shuffle_weights(hipStream_t st, const bf16_t* src, bf16_t* dst, int N, int K);
 
 void launch_rope_table(hipStream_t st, float* cos_t, float* sin_t, int max_pos, int head_dim,
@@ -167,7 +170,7 @@ struct SamplerCfg {
 void launch_sample(hipStream_t st, RowCtx rc, Slots s, Ctrl* ctrl, const float* logits, int vocab,
                    SamplerCfg sc, Watch w, int update, const long long* req_ids,
                    const int* gen_idx, int* out_tokens, const float* group_max, int group,
-                   float* out_logprobs = nullptr);
+                   float* out_logprobs = nullptr, const int* group_idx = nullptr);
 
 void launch_group_max(hipStream_t st, const float* logits, int n_rows, int V, int group, float* out);
 

@@ -199,22 +199,36 @@ __device__ inline void gemm_group(const bf16x8* __restrict__ w0, const bf16x8* _
 
   const int mloc = lane & 31, nhalf = (lane >> 5) << 2;
   if (EPI == EPI_LOGITS) {
-    // per row: the maximum over this wavefront's NT*32 output columns (a group of the
-    // sampler's candidate search), in the order-preserving integer key of the sampler
+    // per row: the maximum over this wavefront's NT*32 output columns (a group of the sampler's
+    // candidate search) and the column that holds it, the lowest one on ties: with those two the
+    // greedy sampler needs no logits at all.  (nf.ssq carries the index array here, or null.)
+    int* gidx = reinterpret_cast<int*>(nf.ssq);
 #pragma unroll
     for (int jq = 0; jq < JT; ++jq) {
       const int j = j0 + jq;
-      float mxv = res[0][jq][0];
+      float bv = -INFINITY;
+      int bn = 0;
 #pragma unroll
       for (int i = 0; i < NT; ++i)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) mxv = fmaxf(mxv, res[i][jq][e]);
-      mxv = fmaxf(mxv, __shfl_xor(mxv, 32, 64));
+        for (int q = 0; q < 4; ++q)
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {             // increasing column: a strict comparison keeps the first maximum
+            const float v = res[i][jq][4 * q + e];
+            if (v > bv) { bv = v; bn = i * 32 + 8 * q + nhalf + e; }
+          }
+      const float ov = __shfl_xor(bv, 32, 64);
+      const int on = __shfl_xor(bn, 32, 64);
+      if (ov > bv || (ov == bv && on < bn)) { bv = ov; bn = on; }
       const int m = (mt0 + j) * 32 + mloc;
-      if (m < rows && lane < 32) reinterpret_cast<float*>(act)[(size_t)m * (N / (32 * NT)) + nt0 / NT] = mxv;
+      if (m < rows && lane < 32) {
+        const size_t gi = (size_t)m * (N / (32 * NT)) + nt0 / NT;
+        reinterpret_cast<float*>(act)[gi] = bv;
+        if (gidx) gidx[gi] = bn;
+      }
     }
   }
-  if (EPI == EPI_F32 || EPI == EPI_LOGITS) {
+  if (EPI == EPI_F32 || (EPI == EPI_LOGITS && out != nullptr)) {
 #pragma unroll
     for (int i = 0; i < NT; ++i)
 #pragma unroll
@@ -374,13 +388,14 @@ void launch_gemm_mfma(hipStream_t st, RowCtx rc, const bf16_t* x, const bf16_t* 
 int lmhead_group_cols() { return 64; }
 
 void launch_gemm_mfma_logits(hipStream_t st, RowCtx rc, const bf16_t* x, const bf16_t* Wp, float* logits,
-                             float* group_max, int V, int K) {
+                             float* group_max, int V, int K, int* group_idx) {
   constexpr int MT = 4;
   const int n_tiles = V >> 5;
   dim3 grid(ceil_div(n_tiles / 2, KW4), 1, ceil_div(ceil_div(rc.max_rows, 32), MT));
   hipLaunchKernelGGL((gemm_mfma_kernel<2, MT, EPI_LOGITS, false>), grid, dim3(64 * KW4), 0, st, rc,
                      reinterpret_cast<const bf16x8*>(x), reinterpret_cast<const bf16x8*>(Wp), nullptr, logits,
-                     reinterpret_cast<bf16_t*>(group_max), V, K, 1, (size_t)0, NormFuse{});
+                     reinterpret_cast<bf16_t*>(group_max), V, K, 1, (size_t)0,
+                     NormFuse{nullptr, reinterpret_cast<float*>(group_idx), 0, 0, 0.f, 0.f});
 }
 
 void launch_gemm_mfma_swiglu(hipStream_t st, RowCtx rc, const bf16_t* x, const bf16_t* Wg, const bf16_t* Wu,

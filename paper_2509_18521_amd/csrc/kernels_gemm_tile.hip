@@ -23,7 +23,7 @@ enum { TEPI_F32 = 0, TEPI_SWIGLU = 1, TEPI_LOGITS = 2 };   // LOGITS: F32 + per-
 template <int MTW, int NTW, int EPI>
 __device__ inline void tile_epilogue(f32x16 (&acc)[NTW][MTW], int nt0, int mt0, int rows, int n_tiles, int N, int lane,
                                      float* __restrict__ out, bf16_t* __restrict__ act,
-                                     const float* row_scale = nullptr, int scale_m0 = 0) {
+                                     const float* row_scale = nullptr, int scale_m0 = 0, int* gidx = nullptr) {
   const int mloc = lane & 31, nhalf = (lane >> 5) << 2;
   if (EPI == TEPI_LOGITS) {
     // act carries the group maxima (float [rows][N / 64]); a group is an aligned pair of weight
@@ -33,18 +33,31 @@ __device__ inline void tile_epilogue(f32x16 (&acc)[NTW][MTW], int nt0, int mt0, 
     if (nt0 < n_tiles) {
 #pragma unroll
       for (int j = 0; j < MTW; ++j) {
-        float mxv = acc[0][j][0];
+        // maximum of the 64 columns and the column holding it (lowest on ties): see the skinny LM head
+        float bv = -INFINITY;
+        int bn = 0;
 #pragma unroll
         for (int i = 0; i < NTW; ++i)
 #pragma unroll
-          for (int e = 0; e < 16; ++e) mxv = fmaxf(mxv, acc[i][j][e]);
-        mxv = fmaxf(mxv, __shfl_xor(mxv, 32, 64));
+          for (int q = 0; q < 4; ++q)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              const float v = acc[i][j][4 * q + e];
+              if (v > bv) { bv = v; bn = i * 32 + 8 * q + nhalf + e; }
+            }
+        const float ov = __shfl_xor(bv, 32, 64);
+        const int on = __shfl_xor(bn, 32, 64);
+        if (ov > bv || (ov == bv && on < bn)) { bv = ov; bn = on; }
         const int m = (mt0 + j) * 32 + mloc;
-        if (m < rows && lane < 32) gmax[(size_t)m * (N >> 6) + (nt0 >> 1)] = mxv;
+        if (m < rows && lane < 32) {
+          const size_t gi = (size_t)m * (N >> 6) + (nt0 >> 1);
+          gmax[gi] = bv;
+          if (gidx) gidx[gi] = bn;
+        }
       }
     }
   }
-  if (EPI == TEPI_F32 || EPI == TEPI_LOGITS) {
+  if (EPI == TEPI_F32 || (EPI == TEPI_LOGITS && out != nullptr)) {
 #pragma unroll
     for (int i = 0; i < NTW; ++i) {
       const int nt = nt0 + i;
@@ -237,6 +250,7 @@ struct TileNorm {              // RMSNorm folded into the SwiGLU epilogue (CHAIN
   const float* ssq;            // [n_ssq][ssq_stride] per-row sums of squares of 32-column slabs; nullptr = none
   int ssq_stride, n_ssq;
   float inv_d, eps;
+  int* gidx;                   // LM head: column of every 64-column group's maximum (nullptr = not wanted)
 };
 
 template <int WGM, int WGN, int MTW, int NTW, int BK, int R, int EPI, bool CHAIN>
@@ -386,15 +400,17 @@ __device__ __forceinline__ void tile_dma_body(RowCtx rc, const bf16x8* __restric
       for (int j = 0; j < MTW; ++j) acc[i][j] = tot[CHAIN ? i : 0][CHAIN ? j : 0] + acc[i][j];
   }
   tile_epilogue<MTW, NTW, EPI>(acc, bx * (EPI == TEPI_SWIGLU ? NT / 2 : NT) + wn * (EPI == TEPI_SWIGLU ? NTW / 2 : NTW),
-                               m0 + wm * MTW, rows, n_tiles, N, lane, out, act, scaled ? row_scale : nullptr, m0 * 32);
+                               m0 + wm * MTW, rows, n_tiles, N, lane, out, act, scaled ? row_scale : nullptr, m0 * 32, tn.gidx);
 }
 
 template <int WGM, int WGN, int MTW, int NTW, int BK, int R, int EPI>
 __global__ __launch_bounds__(64 * WGM * WGN) __attribute__((amdgpu_waves_per_eu(2)))
 void gemm_tile_dma_kernel(RowCtx rc, const bf16x8* __restrict__ x, const bf16x8* __restrict__ w0,
                           const bf16x8* __restrict__ w1, float* __restrict__ out, bf16_t* __restrict__ act, int N,
-                          int K) {
-  tile_dma_body<WGM, WGN, MTW, NTW, BK, R, EPI, false>(rc, x, w0, w1, out, act, N, K, TileNorm{});
+                          int K, int* gidx) {
+  TileNorm tn{};
+  tn.gidx = gidx;
+  tile_dma_body<WGM, WGN, MTW, NTW, BK, R, EPI, false>(rc, x, w0, w1, out, act, N, K, tn);
 }
 
 template <int WGM, int WGN, int MTW, int NTW, int BK, int R, int EPI>
@@ -430,10 +446,10 @@ void launch_gemm_tile(hipStream_t st, RowCtx rc, const bf16_t* x, const bf16_t* 
     hipLaunchKernelGGL((TILE_REGS(TEPI_F32)), grid, dim3(256), 0, st, rc, xv, wv, nullptr, out, nullptr, N, K);
   } else if (wide_tile(n_tiles, 8, m_tiles)) {
     dim3 grid(ceil_div(n_tiles, 8), ceil_div(m_tiles, 8));
-    hipLaunchKernelGGL((TILE_WIDE(TEPI_F32)), grid, dim3(512), 0, st, rc, xv, wv, nullptr, out, nullptr, N, K);
+    hipLaunchKernelGGL((TILE_WIDE(TEPI_F32)), grid, dim3(512), 0, st, rc, xv, wv, nullptr, out, nullptr, N, K, (int*)nullptr);
   } else {
     dim3 grid(ceil_div(n_tiles, 4), ceil_div(m_tiles, 8));
-    hipLaunchKernelGGL((TILE_NARROW(TEPI_F32)), grid, dim3(256), 0, st, rc, xv, wv, nullptr, out, nullptr, N, K);
+    hipLaunchKernelGGL((TILE_NARROW(TEPI_F32)), grid, dim3(256), 0, st, rc, xv, wv, nullptr, out, nullptr, N, K, (int*)nullptr);
   }
 }
 
@@ -448,10 +464,10 @@ void launch_gemm_tile_swiglu(hipStream_t st, RowCtx rc, const bf16_t* x, const b
     hipLaunchKernelGGL((TILE_REGS(TEPI_SWIGLU)), grid, dim3(256), 0, st, rc, xv, gv, uv, nullptr, act, F, K);
   } else if (wide_tile(f_tiles, 4, m_tiles)) {
     dim3 grid(ceil_div(f_tiles, 4), ceil_div(m_tiles, 8));
-    hipLaunchKernelGGL((TILE_WIDE(TEPI_SWIGLU)), grid, dim3(512), 0, st, rc, xv, gv, uv, nullptr, act, F, K);
+    hipLaunchKernelGGL((TILE_WIDE(TEPI_SWIGLU)), grid, dim3(512), 0, st, rc, xv, gv, uv, nullptr, act, F, K, (int*)nullptr);
   } else {
     dim3 grid(ceil_div(f_tiles, 2), ceil_div(m_tiles, 8));
-    hipLaunchKernelGGL((TILE_NARROW(TEPI_SWIGLU)), grid, dim3(256), 0, st, rc, xv, gv, uv, nullptr, act, F, K);
+    hipLaunchKernelGGL((TILE_NARROW(TEPI_SWIGLU)), grid, dim3(256), 0, st, rc, xv, gv, uv, nullptr, act, F, K, (int*)nullptr);
   }
 }
 
@@ -473,11 +489,11 @@ bool launch_gemm_tile_swiglu_chain(hipStream_t st, RowCtx rc, const bf16_t* x, c
     hipLaunchKernelGGL((gemm_tile_chain_kernel<2, 2, 2, 2, 2, 3, TEPI_SWIGLU>), grid, dim3(256), 0, st, rc,
                        reinterpret_cast<const bf16x8*>(x), reinterpret_cast<const bf16x8*>(Wg),
                        reinterpret_cast<const bf16x8*>(Wu), nullptr, act, F, K,
-                       TileNorm{ssq, ssq_stride, K >> 5, 1.0f / (float)K, eps});
+                       TileNorm{ssq, ssq_stride, K >> 5, 1.0f / (float)K, eps, nullptr});
     return true;
   }
   const int f_tiles = F >> 5, m_tiles = ceil_div(rc.max_rows, 32);
-  const TileNorm tn{ssq, ssq_stride, K >> 5, 1.0f / (float)K, eps};
+  const TileNorm tn{ssq, ssq_stride, K >> 5, 1.0f / (float)K, eps, nullptr};
   dim3 grid(ceil_div(f_tiles, 2), ceil_div(m_tiles, 8));
   hipLaunchKernelGGL((gemm_tile_chain_kernel<2, 2, 4, 2, 2, 3, TEPI_SWIGLU>), grid, dim3(256), 0, st, rc,
                      reinterpret_cast<const bf16x8*>(x), reinterpret_cast<const bf16x8*>(Wg),
@@ -489,11 +505,11 @@ bool launch_gemm_tile_swiglu_chain(hipStream_t st, RowCtx rc, const bf16_t* x, c
 // per element as the skinny LM-head kernel (k-tiles in order, one accumulator), so the choice
 // between the two changes no bit.  Needs V % 64 == 0 and K % 32 == 0.
 void launch_gemm_tile_logits(hipStream_t st, RowCtx rc, const bf16_t* x, const bf16_t* Wp, float* logits,
-                             float* group_max, int V, int K) {
+                             float* group_max, int V, int K, int* group_idx) {
   const int n_tiles = V >> 5, m_tiles = ceil_div(rc.max_rows, 32);
   dim3 grid(ceil_div(n_tiles, 8), ceil_div(m_tiles, 8));
   hipLaunchKernelGGL((TILE_WIDE(TEPI_LOGITS)), grid, dim3(512), 0, st, rc, reinterpret_cast<const bf16x8*>(x),
-                     reinterpret_cast<const bf16x8*>(Wp), nullptr, logits, reinterpret_cast<bf16_t*>(group_max), V, K);
+                     reinterpret_cast<const bf16x8*>(Wp), nullptr, logits, reinterpret_cast<bf16_t*>(group_max), V, K, group_idx);
 }
 
 }  // namespace april

@@ -189,7 +189,7 @@ __global__ __launch_bounds__(SAMPLE_THREADS) void sample_kernel(RowCtx rc, Slots
                                                                 Watch w, int update, const long long* req_ids,
                                                                 const int* gen_idx, int* out_tokens,
                                                                 const float* group_max, int group,
-                                                                float* out_logprobs) {
+                                                                float* out_logprobs, const int* group_idx) {
   const int r = blockIdx.x;
   ROW_GUARD(rc, r);
   const int tid = threadIdx.x, lane = tid & 63, wid = tid >> 6;
@@ -214,7 +214,9 @@ __global__ __launch_bounds__(SAMPLE_THREADS) void sample_kernel(RowCtx rc, Slots
     // ---- greedy: maximum, lowest index on ties --------------------------------------
     if (gm) {
       const int gi = block_argmax(gm, n_groups, sh);               // lowest group holding the maximum
-      const int li = block_argmax(lg + (size_t)gi * group, group, sh);
+      // the column inside the group: left by the LM head, else looked up in the logits
+      const int li = group_idx ? group_idx[(size_t)r * n_groups + gi] : block_argmax(lg + (size_t)gi * group, group, sh);
+      __syncthreads();
       if (tid == 0) sh.choice = gi * group + li;
       __syncthreads();
     } else {
@@ -459,9 +461,9 @@ void launch_group_max(hipStream_t st, const float* logits, int n_rows, int V, in
 
 void launch_sample(hipStream_t st, RowCtx rc, Slots s, Ctrl* ctrl, const float* logits, int vocab, SamplerCfg sc,
                    Watch w, int update, const long long* req_ids, const int* gen_idx, int* out_tokens,
-                   const float* group_max, int group, float* out_logprobs) {
+                   const float* group_max, int group, float* out_logprobs, const int* group_idx) {
   hipLaunchKernelGGL(sample_kernel, dim3(rc.max_rows), dim3(SAMPLE_THREADS), 0, st, rc, s, ctrl, logits, vocab,
-                     sc, w, update, req_ids, gen_idx, out_tokens, group_max, group, out_logprobs);
+                     sc, w, update, req_ids, gen_idx, out_tokens, group_max, group, out_logprobs, group_idx);
 }
 
 }  // namespace april

@@ -239,3 +239,33 @@ def test_tiled_decode_gate_up_gives_the_skinny_kernels_bits(monkeypatch, n_targe
     assert [g["tokens"] for g in a] == [g["tokens"] for g in b]
     assert la.keys() == lb.keys() and len(la) > 200
     assert all(np.array_equal(la[k], lb[k]) for k in la)
+
+
+@pytest.mark.parametrize("n_target,n_over", [(30, 40), (100, 150)])      # skinny LM head; tall-batch LM head
+def test_greedy_sampling_without_logits_equals_sampling_from_logits(monkeypatch, n_target, n_over):
+    """Greedy, not in parity mode: the LM head writes no logits, only the maximum of every 64
+    columns and the column holding it, and the sampler works from those.  Same tokens as with
+    the logits written and searched (APRIL_WRITE_LOGITS=1), also where maxima tie exactly: the LM
+    head rows are equal in blocks of 8 here, so every maximum is an 8-way tie across both lane
+    halves of the accumulator tile, and the lowest index must win (a multiple of 8)."""
+    shape = ai.ModelShape(2, 128, 4, 2, 32, 256, 1024)
+    w = ai.Workload("nologits", shape, 8, 9, n_target, n_over, 7, 1.6, 0.3, 3, 7, ai.SAMPLER_GREEDY, 0, 2, 13)
+    weights = ai.make_weights(shape, w.seed)
+    head = weights["lm_head"].copy()
+    head[:] = head[(np.arange(shape.vocab) // 8) * 8]
+    weights["lm_head"] = head
+    reqs = ai.make_requests(w, ai.requests_needed(w))
+    runs = []
+    for flag in ("1", "0"):
+        monkeypatch.setenv("APRIL_WRITE_LOGITS", flag)
+        ctx = make_engine(w, weights)
+        try:
+            runs.append(run_gpu(ctx, reqs, w.n_target, w.n_overprovision, w.max_new, w.steps))
+        finally:
+            ap().april_destroy(ctx)
+    a, b = runs
+    assert_schedule_equal(b, a)
+    assert [g["tokens"] for g in a] == [g["tokens"] for g in b]
+    assert [g["buffer_tokens"] for g in a] == [g["buffer_tokens"] for g in b]
+    toks = [t for g in b for seq in g["tokens"] for t in seq]
+    assert len(toks) > 200 and all(t % 8 == 0 for t in toks)

@@ -279,7 +279,7 @@ __device__ inline void gemm_group(const bf16x8* __restrict__ w0, const bf16x8* _
       ss += __shfl_xor(ss, 32, 64);
       if (m < rows && lane < 32) nf.ssq[(size_t)nt0 * nf.ssq_stride + m] = ss;
     }
-  } else {
+  } else if (EPI == EPI_SWIGLU) {
     // acc[0] = gate tile, acc[1] = up tile of features [nt0*32, nt0*32+32); N is F here.
 #pragma unroll
     for (int jq = 0; jq < JT; ++jq) {

@@ -75,7 +75,7 @@ __device__ inline void tile_epilogue(f32x16 (&acc)[NTW][MTW], int nt0, int mt0, 
         }
       }
     }
-  } else {
+  } else if (EPI == TEPI_SWIGLU) {
     constexpr int H = NTW / 2;
 #pragma unroll
     for (int i = 0; i < H; ++i) {

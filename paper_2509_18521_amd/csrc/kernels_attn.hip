@@ -44,7 +44,10 @@ namespace april {
 // head_dim 128: +1.6 % on 4000-token rows, -4.5 % on a ragged batch.  512: 7 % slower on long rows.
 constexpr int att_split(int dh) { return dh == 64 ? ATT_SPLIT_64 : (dh == 128 ? ATT_SPLIT_128 : 1024); }
 // wavefronts per workgroup (8 for head_dim <= 64 was measured: 11.8 us against 10.6 us per launch)
-constexpr int att_waves(int dh, bool fused) { return 4; }
+#ifndef ATT_WAVES_128
+#define ATT_WAVES_128 4
+#endif
+constexpr int att_waves(int dh, bool fused) { return dh == 128 ? ATT_WAVES_128 : 4; }
 
 struct AttnFuse {              // inputs of the fused rotary + append (FUSED only)
   const float* qkv;            // fp32 [n_partials][rows][(Hq + 2 Hkv) * dh] split-K partials of the QKV GEMM

@@ -148,6 +148,9 @@ struct april_ctx {
   int tile_decode_rows = 128;   // decode gate/up goes through the LDS-tiled kernel from this bound on the rows in flight (0 = never)
   float* ssq = nullptr;         // [d_model / 32][m_cap] per-row partial sums of squares (fused norm)
   int attn_chunk = 256, attn_max_splits = 1, attn_ws_rows = 0;
+  int4* d_att_items = nullptr;   // work list of the decode attention, rebuilt by the scheduler kernel every iteration
+  int att_items_cap = 0;         // entries beyond the header
+  bool att_list = true;
   float* attn_ws = nullptr;
   int* d_dummy = nullptr;       // target of the empty kernel that calibrates event-pair timing
   int step_max_ctx = 0;        // bound on the context length of any row in the current pass
@@ -567,7 +570,8 @@ void forward(april_ctx* c, RowCtx rows, RowCtx srows, const int* gather, double 
           ProfScope p(c, KC_ATTN, C * 2.0 * nkv * e + B * nq * (4.0 + e), 4.0 * C * nq);
           launch_attn_decode(st, sub, base, c->ds, c->q_rot, (bf16_t*)c->kv_pool, c->kvl, l, Hq,
                              (bf16_t*)c->attn_out, c->attn_ws, c->attn_max_splits, gs,
-                             fuse_rope ? c->qkv : nullptr, sq, c->qkv_stride, c->rope_cos, c->rope_sin);
+                             fuse_rope ? c->qkv : nullptr, sq, c->qkv_stride, c->rope_cos, c->rope_sin,
+                             fuse_rope && c->att_list && rows.max_rows <= c->attn_ws_rows ? c->d_att_items : nullptr);
         }
         if (gs > 1) {      // some row may span several KV splits: merge their partial results
           ProfScope p(c, KC_ATTN_MERGE, 0, 0);
@@ -705,7 +709,8 @@ static int iter_graph(april_ctx* c, int rows_cap, int gs, int n_iters, hipGraphE
     c->step_max_ctx = ctx_grid;
     HIPCHK(c, hipStreamBeginCapture(st, hipStreamCaptureModeThreadLocal));
     for (int q = 0; q < n_iters; ++q) {
-      launch_sched(st, c->d_ctrl, c->ds, c->d_row_slot, c->d_row_pos, c->d_free_stack, 16, 0, rows_cap, ctx_grid);
+      launch_sched(st, c->d_ctrl, c->ds, c->d_row_slot, c->d_row_pos, c->d_free_stack, 16, 0, rows_cap, ctx_grid,
+                   c->d_att_items, c->attn_chunk, std::min(c->att_items_cap, rows_cap * gs));
       forward(c, grc, grc, nullptr, 0, 0);
     }
     HIPCHK(c, hipStreamEndCapture(st, &graph));
@@ -920,6 +925,12 @@ int april_init(const april_model_cfg* cfg, const april_tensor* weights, int32_t 
     const int by_bytes = (int)std::min<size_t>(4096, ((size_t)1 << 30) / ws_row_bytes) / 32 * 32;
     c->attn_ws_rows = std::min<int>(c->m_cap, std::max({512, (S + 31) / 32 * 32, by_bytes}));
     TRY(dev_alloc(c, &c->attn_ws, (size_t)c->attn_ws_rows * g.n_kv_heads * c->attn_max_splits * rec, false));
+    const char* al = getenv("APRIL_ATTN_LIST");
+    c->att_list = c->fuse_rope && !(al && !strcmp(al, "0"));
+    if (c->att_list) {
+      c->att_items_cap = S * c->attn_max_splits;
+      TRY(dev_alloc(c, &c->d_att_items, (size_t)c->att_items_cap + 1));
+    }
   }
   TRY(dev_alloc(c, &c->rope_cos, (size_t)g.max_ctx * g.head_dim / 2, false));
   TRY(dev_alloc(c, &c->rope_sin, (size_t)g.max_ctx * g.head_dim / 2, false));
@@ -1632,7 +1643,9 @@ int april_rollout_step(april_ctx* c, const april_request* new_reqs, int32_t n_ne
     }
     // iteration 1: resident rollouts decode, the others are (re-)prefilled
     const int NOCAP = 0x7fffffff;
-    launch_sched(st, c->d_ctrl, c->ds, c->d_row_slot, c->d_row_pos, c->d_free_stack, blk, 0, NOCAP, NOCAP);
+    launch_sched(st, c->d_ctrl, c->ds, c->d_row_slot, c->d_row_pos, c->d_free_stack, blk, 0, NOCAP, NOCAP,
+                 c->d_att_items, c->attn_chunk,
+                 std::min(c->att_items_cap, n_resident * std::min(c->attn_max_splits, std::max(1, ceil_div(decode_max_ctx, c->attn_chunk)))));
     if (n_resident > 0) {
       drc.max_rows = n_resident;
       forward(c, drc, drc, nullptr, n_resident, 0);
@@ -1742,7 +1755,8 @@ int april_rollout_step(april_ctx* c, const april_request* new_reqs, int32_t n_ne
         {
           ProfScope p(c, KC_SCHED, 0, 0);
           launch_sched(st, c->d_ctrl, c->ds, c->d_row_slot, c->d_row_pos, c->d_free_stack, blk, 0,
-                       fail_here ? 0 : rows_cap, ctx_grid);
+                       fail_here ? 0 : rows_cap, ctx_grid, c->d_att_items, c->attn_chunk,
+                       std::min(c->att_items_cap, rows_cap * gs));
           if (fail_here) c->debug_fail_step = -1;      // one shot
         }
         double B = 0, C = 0;

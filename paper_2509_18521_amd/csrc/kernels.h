@@ -42,8 +42,14 @@ __device__ inline float silu_mul(float g, float u) { return g * u * __builtin_am
 // check_only = 1: only the "N complete => stop" test (end of a chunk of iterations).
 // row_cap / ctx_cap: the bounds the host sized this iteration's launches for (live rows, longest
 // context); exceeding one sets error bit 2 in the control block and stops the step.
+// att_items (or null): work list for the decode attention, written when rows are rebuilt: entry 0
+// = {count, 0, 0, 0}, entry 1 + i = {row, KV split, slot, position}, one per (row, split of
+// att_split tokens the row's context reaches), full splits first, then the rows' last splits by
+// descending length (classes of att_split / 32 tokens; the order inside a class is arbitrary).
+// att_cap = entries the list holds beyond the first; more items than that raise error bit 2.
 void launch_sched(hipStream_t st, Ctrl* ctrl, Slots s, int* row_slot, int* row_pos,
-                  int* free_stack, int blk, int check_only, int row_cap, int ctx_cap);
+                  int* free_stack, int blk, int check_only, int row_cap, int ctx_cap,
+                  int4* att_items = nullptr, int att_split = 0, int att_cap = 0);
 void launch_alloc_prefill(hipStream_t st, Ctrl* ctrl, Slots s, const int* slot_list,
                           const int* n_blocks_needed, int n, int* free_stack);
 void launch_free_slots(hipStream_t st, Ctrl* ctrl, Slots s, const int* slot_list, int n,
@@ -95,11 +101,13 @@ void launch_attn_ref(hipStream_t st, RowCtx rc, Slots s, const float* q_rot, con
 int attn_split_tokens(int head_dim);
 // fused_qkv != nullptr (decode iterations): the kernel also rotates q / the new key and
 // appends the new key / value itself from the QKV GEMM's split-K partials (q_rot unused).
+// items != nullptr (row_base 0, rows listed by launch_sched in this iteration): a 1-D launch of
+// rc.max_rows * grid_splits * KV heads workgroups that takes its (row, split) from the work list.
 void launch_attn_decode(hipStream_t st, RowCtx rc, int row_base, Slots s, const float* q_rot,
                         bf16_t* kv_pool, KVLayout kvl, int layer, int n_q_heads, bf16_t* out,
                         float* ws, int max_splits, int grid_splits,
                         const float* fused_qkv, int n_partials, size_t partial_stride,
-                        const float* rope_cos, const float* rope_sin);
+                        const float* rope_cos, const float* rope_sin, const int4* items = nullptr);
 // Causal attention over prefill rows, one workgroup per (item, KV head); an item = {slot, first
 // row of the sequence in the row arrays, tokens of the sequence, first position of the tile},
 // tiles of attn_prefill_tile(query heads per KV head) positions.  q_rot and the pages must hold

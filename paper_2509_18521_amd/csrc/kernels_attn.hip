@@ -60,7 +60,8 @@ struct AttnFuse {              // inputs of the fused rotary + append (FUSED onl
 template <int DH, bool FUSED>
 __global__ __launch_bounds__(64 * att_waves(DH, FUSED)) __attribute__((amdgpu_waves_per_eu(2))) void attn_decode_kernel(
     RowCtx rc, int row_base, Slots s, const float* __restrict__ q_rot, bf16_t* kv_pool, KVLayout L, int layer,
-    int Hq, bf16_t* __restrict__ out, float* __restrict__ ws, int max_splits, AttnFuse fz) {
+    int Hq, bf16_t* __restrict__ out, float* __restrict__ ws, int max_splits, AttnFuse fz,
+    const int4* __restrict__ items) {
   constexpr int KC = DH / 32;      // k-chunks of the QK product
   constexpr int DT = DH / 16;      // dim tiles of the PV product
   constexpr int REC = 32 + 16 * DH;   // floats of one partial result: m[16], l[16], o[16][DH]
@@ -73,12 +74,33 @@ __global__ __launch_bounds__(64 * att_waves(DH, FUSED)) __attribute__((amdgpu_wa
   // plain mapping would put every (KV head, split) of a row on one XCD and a long row would
   // overload it.  Rotating the row index by the other two coordinates spreads a row's
   // workgroups over the XCDs (a bijection of blockIdx.x for fixed y and z).
-  const int kvh = blockIdx.y, split = blockIdx.z;
-  const int wr = (int)((blockIdx.x + blockIdx.y + 3u * blockIdx.z) % gridDim.x), r = row_base + wr;   // wr: workspace row
-  // the row arrays hold max_rows entries: fetch them together with the control word
-  const int slot_raw = rc.row_slot[r], pos = rc.row_pos[r];
-  ROW_GUARD(rc, r);
-  const int slot = slot_raw;
+  //
+  // With a work list (items != nullptr; 1-D launch) the scheduler kernel has listed this
+  // iteration's (row, split) pairs longest first: entry 0 holds their number, entry 1 + i =
+  // {row, split, slot, position}.  Workgroup id = item * n_kv_heads + KV head, so the long items
+  // start first, the launch ends on the short ones, no workgroup is launched for a split its row
+  // does not have, and the KV heads of one item go to different XCDs.
+  int kvh, split, wr, slot, pos;
+  if (items != nullptr) {
+    const int nkv = L.n_kv_heads;
+    const int item = (int)blockIdx.x / nkv;
+    kvh = (int)blockIdx.x - item * nkv;
+    const int4 head = items[0], it = items[1 + item];
+    const int2 ctl = *rc.ctl;
+    if (ctl.y || item >= head.x) return;
+    wr = __builtin_amdgcn_readfirstlane(it.x);
+    split = __builtin_amdgcn_readfirstlane(it.y);
+    slot = __builtin_amdgcn_readfirstlane(it.z);
+    pos = __builtin_amdgcn_readfirstlane(it.w);
+  } else {
+    kvh = blockIdx.y; split = blockIdx.z;
+    wr = (int)((blockIdx.x + blockIdx.y + 3u * blockIdx.z) % gridDim.x);     // wr: workspace row
+    // the row arrays hold max_rows entries: fetch them together with the control word
+    const int slot_raw = rc.row_slot[row_base + wr], pos_raw = rc.row_pos[row_base + wr];
+    ROW_GUARD(rc, row_base + wr);
+    slot = slot_raw; pos = pos_raw;
+  }
+  const int r = row_base + wr;
   const int ctx = pos + 1;
   constexpr int ATT_SPLIT = att_split(DH), PR = ATT_SPLIT / 1024;
   static_assert(ATT_SPLIT % 1024 == 0 && PR >= 1, "split length");
@@ -691,12 +713,14 @@ int attn_split_tokens(int head_dim) { return att_split(head_dim); }
 void launch_attn_decode(hipStream_t st, RowCtx rc, int row_base, Slots s, const float* q_rot, bf16_t* kv_pool,
                         KVLayout kvl, int layer, int n_q_heads, bf16_t* out, float* ws,
                         int max_splits, int grid_splits, const float* fused_qkv, int n_partials,
-                        size_t partial_stride, const float* rope_cos, const float* rope_sin) {
+                        size_t partial_stride, const float* rope_cos, const float* rope_sin, const int4* items) {
+  // items: the scheduler's work list of this iteration (decode, row_base 0), or null
   dim3 grid(rc.max_rows, kvl.n_kv_heads, grid_splits);
+  if (items != nullptr) grid = dim3((unsigned)rc.max_rows * grid_splits * kvl.n_kv_heads);
   AttnFuse fz{fused_qkv, n_partials, partial_stride, rope_cos, rope_sin};
 #define ATT_LAUNCH(DH, F)                                                                                    \
   hipLaunchKernelGGL((attn_decode_kernel<DH, F>), grid, dim3(64 * att_waves(DH, F)), 0, st, rc, row_base, s, q_rot, kv_pool, kvl, layer, \
-                     n_q_heads, out, ws, max_splits, fz)
+                     n_q_heads, out, ws, max_splits, fz, items)
   const bool fused = fused_qkv != nullptr;
   switch (kvl.head_dim) {
     case 32: if (fused) ATT_LAUNCH(32, true); else ATT_LAUNCH(32, false); break;

@@ -39,7 +39,7 @@ template <typename T> __device__ inline T from_f32(float v) { return (T)v; }
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(1024) void sched_kernel(Ctrl* c, Slots s, int* row_slot, int* row_pos,
                                                      int* free_stack, int blk, int check_only, int row_cap,
-                                                     int ctx_cap) {
+                                                     int ctx_cap, int4* att_items, int att_split, int att_cap) {
   __shared__ int sh_a[16], sh_b[16], sh_err[16];
   __shared__ long long sh_ctx[16];
   const int tid = threadIdx.x, lane = tid & 63, wid = tid >> 6;
@@ -132,6 +132,43 @@ __global__ __launch_bounds__(1024) void sched_kernel(Ctrl* c, Slots s, int* row_
     base_live += ta;
     base_need += tb;
   }
+  // Work list of the decode attention: one item per (row, KV split), longest first.  Class 0 =
+  // full splits, class 1 + j = last splits that are j 32nds of a split short of full; a
+  // counting sort over the classes (shared-memory counters; the order inside a class does not
+  // matter, every item's result is independent of where it runs).
+  if (att_items != nullptr) {
+    __shared__ int sh_hist[33], sh_cur[33];
+    if (tid < 33) sh_hist[tid] = 0;
+    __syncthreads();                                   // also: this workgroup's row_slot / row_pos stores are visible
+    for (int r = tid; r < base_live; r += 1024) {
+      const int ctx = row_pos[r] + 1;
+      const int ns = (ctx + att_split - 1) / att_split, last = ctx - (ns - 1) * att_split;
+      const int cl = 1 + (int)(((long long)(att_split - last) * 32) / att_split);
+      if (ns > 1) atomicAdd(&sh_hist[0], ns - 1);
+      atomicAdd(&sh_hist[cl], 1);
+    }
+    __syncthreads();
+    if (tid == 0) {
+      int acc = 0;
+      for (int i = 0; i < 33; ++i) { sh_cur[i] = acc; acc += sh_hist[i]; }
+      if (acc > att_cap) { acc = 0; err |= 2; }
+      sh_hist[0] = acc;
+      att_items[0] = make_int4(acc, 0, 0, 0);
+    }
+    __syncthreads();
+    if (sh_hist[0] > 0) {
+      for (int r = tid; r < base_live; r += 1024) {
+        const int pos = row_pos[r], slot = row_slot[r], ctx = pos + 1;
+        const int ns = (ctx + att_split - 1) / att_split, last = ctx - (ns - 1) * att_split;
+        const int cl = 1 + (int)(((long long)(att_split - last) * 32) / att_split);
+        if (ns > 1) {
+          const int p0 = atomicAdd(&sh_cur[0], ns - 1);
+          for (int j = 0; j < ns - 1; ++j) att_items[1 + p0 + j] = make_int4(r, j, slot, pos);
+        }
+        att_items[1 + atomicAdd(&sh_cur[cl], 1)] = make_int4(r, ns - 1, slot, pos);
+      }
+    }
+  }
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1) {
     ctx_sum += __shfl_xor(ctx_sum, off, 64);
@@ -159,9 +196,9 @@ __global__ __launch_bounds__(1024) void sched_kernel(Ctrl* c, Slots s, int* row_
 }
 
 void launch_sched(hipStream_t st, Ctrl* ctrl, Slots s, int* row_slot, int* row_pos, int* free_stack, int blk,
-                  int check_only, int row_cap, int ctx_cap) {
+                  int check_only, int row_cap, int ctx_cap, int4* att_items, int att_split, int att_cap) {
   hipLaunchKernelGGL(sched_kernel, dim3(1), dim3(1024), 0, st, ctrl, s, row_slot, row_pos, free_stack, blk,
-                     check_only, row_cap, ctx_cap);
+                     check_only, row_cap, ctx_cap, att_items, att_split, att_cap);
 }
 
 // Pages for freshly admitted rollouts (prefill): slot_list[i] gets need[i] pages.

@@ -241,6 +241,43 @@ def test_tiled_decode_gate_up_gives_the_skinny_kernels_bits(monkeypatch, n_targe
     assert all(np.array_equal(la[k], lb[k]) for k in la)
 
 
+@pytest.mark.parametrize("head_dim", [64, 128])
+def test_attention_work_list_gives_the_grid_launch_bits(monkeypatch, head_dim):
+    """Decode attention takes its (row, KV split) items from the list the scheduler kernel sorts
+    by length every iteration; APRIL_ATTN_LIST=0 launches one workgroup per (row, head, split)
+    of a grid instead.  Contexts of 1003-1070 tokens (and 2030-2100 with the longer prompt) put
+    rows with different split counts and last-split lengths into the same iteration; no bit of
+    any logit may depend on which launch ran, nor any token or scheduling decision."""
+    shape = ai.ModelShape(1, 256, 256 // head_dim, 2, head_dim, 256, 512)
+    runs = []
+    for flag in ("0", "1"):
+        monkeypatch.setenv("APRIL_ATTN_LIST", flag)
+        per_prompt = []
+        for prompt_len in (1000, 2030):
+            w = ai.Workload("att_list", shape, 6, prompt_len, 10, 16, 70, 3.3, 0.8, 3, 70, ai.SAMPLER_GREEDY, 0, 2, 21)
+            weights = ai.make_weights(shape, w.seed)
+            reqs = ai.make_requests(w, ai.requests_needed(w))
+            ctx = make_engine(w, weights, debug=True)
+            try:
+                for r in reqs:
+                    ap().april_debug_watch(ctx, r.request_id, 0, w.max_new)
+                got = run_gpu(ctx, reqs, w.n_target, w.n_overprovision, w.max_new, w.steps)
+                logits = {}
+                for g in got:
+                    for rid, toks in list(zip(g["ids"], g["tokens"])) + list(g["buffer_tokens"].items()):
+                        for i in range(len(toks)):
+                            logits[(rid, i)] = ap().april_debug_logits(ctx, rid, i, shape.vocab)[0]
+                per_prompt.append((got, logits))
+            finally:
+                ap().april_destroy(ctx)
+        runs.append(per_prompt)
+    for (a, la), (b, lb) in zip(*runs):
+        assert_schedule_equal(b, a)
+        assert [g["tokens"] for g in a] == [g["tokens"] for g in b]
+        assert la.keys() == lb.keys() and len(la) > 300
+        assert all(np.array_equal(la[k], lb[k]) for k in la)
+
+
 @pytest.mark.parametrize("n_target,n_over", [(30, 40), (100, 150)])      # skinny LM head; tall-batch LM head
 def test_greedy_sampling_without_logits_equals_sampling_from_logits(monkeypatch, n_target, n_over):
     """Greedy, not in parity mode: the LM head writes no logits, only the maximum of every 64

@@ -494,6 +494,15 @@ bool launch_gemm_tile_swiglu_chain(hipStream_t st, RowCtx rc, const bf16_t* x, c
   }
   const int f_tiles = F >> 5, m_tiles = ceil_div(rc.max_rows, 32);
   const TileNorm tn{ssq, ssq_stride, K >> 5, 1.0f / (float)K, eps, nullptr};
+  if (rc.max_rows <= 192) {
+    // 192-row tile (3 accumulator row tiles per wavefront): a quarter less matrix work and LDS
+    // traffic than the full tile would spend on rows that are not there
+    dim3 grid(ceil_div(f_tiles, 2), 1);
+    hipLaunchKernelGGL((gemm_tile_chain_kernel<2, 2, 3, 2, 2, 3, TEPI_SWIGLU>), grid, dim3(256), 0, st, rc,
+                       reinterpret_cast<const bf16x8*>(x), reinterpret_cast<const bf16x8*>(Wg),
+                       reinterpret_cast<const bf16x8*>(Wu), nullptr, act, F, K, tn);
+    return true;
+  }
   dim3 grid(ceil_div(f_tiles, 2), ceil_div(m_tiles, 8));
   hipLaunchKernelGGL((gemm_tile_chain_kernel<2, 2, 4, 2, 2, 3, TEPI_SWIGLU>), grid, dim3(256), 0, st, rc,
                      reinterpret_cast<const bf16x8*>(x), reinterpret_cast<const bf16x8*>(Wg),

@@ -209,6 +209,78 @@ def test_cfg2_bench_launch_configuration_sampled_outputs():
         ap().april_destroy(ctx)
 
 
+def test_cfg3_bench_launch_configuration_sampled_outputs():
+    """Configuration 3 (the benchmark's default workload) at full size, launched as the benchmark
+    launches it: 36 layers, 152 k vocabulary, N = 128, N' = 192, max_new = 4096, greedy sampling
+    from the LM head's (maximum, column) records with no logits written, graph replay, the
+    GPU's own tokens.  One step: APRIL's invariants; then the same step on an engine in parity
+    mode (logits written and kept for two rollouts) must give every rollout the same tokens, and
+    the kept logits at sampled positions are compared with the oracle fed with the same prefix."""
+    from concurrent.futures import ThreadPoolExecutor
+    from oracle.model import Decoder
+    w = ai.WORKLOADS["cfg3_mid_bf16"]
+    s = w.shape
+    specs = ai.weight_specs(s)
+
+    def one(spec):
+        name, shape, kind = spec
+        a = ai.weight_tensor(s, name, shape, kind, w.seed)
+        return name, a, ap().pack_weights(s, {name: a})[name]
+    weights, packed = {}, {}
+    with ThreadPoolExecutor(max_workers=16) as ex:
+        for name, a, pk in ex.map(one, specs):
+            weights[name], packed[name] = a, pk
+    reqs = ai.make_requests(w, w.n_overprovision)
+    lens = {r.request_id: min(r.forced_len, w.max_new) for r in reqs}
+    short = next(r for r in reqs if 40 <= r.forced_len <= 120)        # completes in the first step
+    long_ = next(r for r in reqs if r.forced_len >= 2500)             # still running when it ends
+    n_watch = 96
+    runs = []
+    kept = {}
+    for debug in (False, True):
+        cfg = ap().make_cfg(s, max_inflight=w.n_overprovision + 8, max_ctx=w.prompt_len + w.max_new + 16,
+                            sampler=w.sampler, top_k=max(w.top_k, 1), temperature=1.0, seed=w.seed,
+                            debug_logits=debug)
+        ctx = ap().april_init(cfg, packed)
+        try:
+            if debug:
+                ap().april_debug_watch(ctx, short.request_id, 0, short.forced_len)
+                ap().april_debug_watch(ctx, long_.request_id, 0, n_watch)
+            got = run_gpu(ctx, reqs, w.n_target, w.n_overprovision, w.max_new, 1)[0]
+            runs.append(got)
+            if debug:
+                for r, n in ((short, short.forced_len), (long_, n_watch)):
+                    for i in sorted({0, 1, n // 3, n // 2, n - 2, n - 1}):
+                        kept[(r.request_id, i)] = ap().april_debug_logits(ctx, r.request_id, i, s.vocab)
+        finally:
+            ap().april_destroy(ctx)
+    got, ref_run = runs
+    assert len(got["ids"]) == w.n_target and len(set(got["ids"])) == w.n_target
+    assert all(len(t) == lens[rid] for rid, t in zip(got["ids"], got["tokens"]))
+    assert len(got["buffer"]) == w.n_overprovision - w.n_target
+    assert set(got["ids"]) | {b[0] for b in got["buffer"]} == set(lens)          # nobody lost
+    assert got["generated"] == sum(len(t) for t in got["tokens"]) + sum(b[1] for b in got["buffer"])
+    assert short.request_id in got["ids"] and long_.request_id in got["buffer_tokens"]
+    assert_schedule_equal([got], [ref_run])
+    assert got["tokens"] == ref_run["tokens"] and got["buffer_tokens"] == ref_run["buffer_tokens"]
+    dec = Decoder(s, weights)
+    worst = 0.0
+    for r, toks, n in ((short, got["tokens"][got["ids"].index(short.request_id)], short.forced_len),
+                       (long_, got["buffer_tokens"][long_.request_id][:n_watch], n_watch)):
+        feed = np.concatenate([r.tokens, np.asarray(toks[:n - 1], dtype=np.int32)])
+        ref_all = dec.forward_block(feed, dec.new_cache())          # row P-1+i predicts generated token i
+        for (rid, i), (lg, sampled) in kept.items():
+            if rid != r.request_id:
+                continue
+            ref = ref_all[w.prompt_len - 1 + i]
+            worst = max(worst, float(np.max(np.abs(lg - ref))) / max(1.0, float(np.max(np.abs(ref)))))
+            assert sampled == toks[i] == int(np.argmax(lg))
+            top2 = np.sort(ref)[-2:]
+            if top2[1] - top2[0] > 2 * BF16_LOGIT_TOL * max(1.0, float(np.max(np.abs(ref)))):
+                assert sampled == int(np.argmax(ref))
+    assert worst <= BF16_LOGIT_TOL, worst
+
+
 @pytest.mark.parametrize("n_target,n_over", [(30, 40), (100, 150)])      # half-height tile; full tile
 def test_tiled_decode_gate_up_gives_the_skinny_kernels_bits(monkeypatch, n_target, n_over):
     """With many rows in flight the decode gate/up GEMM runs in the LDS-tiled kernel, which

@@ -33,14 +33,18 @@ def note(msg):
     print(f"[bench {time.strftime('%H:%M:%S')}] {msg}", file=sys.stderr, flush=True)
 
 
-def run_arm(ap, ctx, reqs, n_target, n_over, max_new, steps, profile_every=0, between=None):
+def run_arm(ap, ctx, reqs, n_target, n_over, max_new, steps, profile_every=0, between=None, group_size=0):
     """Run `steps` rollout steps from a clean context state; returns per-step results.
-    between(ctx): called after every step but the last (e.g. a weight update)."""
+    between(ctx): called after every step but the last (e.g. a weight update).
+    group_size G > 1: request r belongs to group r // G (instance-level completion)."""
     ap.april_profile_enable(ctx, profile_every)
     nxt, results = 0, []
     t0 = time.perf_counter()
     for k in range(steps):
         new = [dict(request_id=r.request_id, tokens=r.tokens, forced_len=r.forced_len) for r in reqs[nxt:nxt + n_over]]
+        if group_size > 1:
+            for d in new:
+                d["group_id"] = d["request_id"] // group_size
         res = ap.april_rollout_step(ctx, new, n_target, n_over, max_new)
         nxt += res.n_new_consumed
         results.append(res)
@@ -149,6 +153,11 @@ def main():
     p.add_argument("--update-weights", type=int, default=0, metavar="STEPS",
                    help="extra APRIL arm of STEPS steps with a policy update (april_update_weights, device-resident "
                         "source) after every step: once re-prefilling the parked rollouts, once keeping their stale KV")
+    p.add_argument("--next-rows", type=int, default=0, metavar="STEPS",
+                   help="also measure, over STEPS steps each on a fresh engine: the paper's rollout sampling "
+                        "(temperature 0.8 over the whole vocabulary, log-probabilities returned) and its evaluation "
+                        "sampling (top-p 0.7), instance-level completion in groups of 8, and releasing / re-mapping "
+                        "the KV pool and the weights")
     p.add_argument("--kv-pool-gib", type=float, default=0.0, help="KV pool size (0 = the library's default)")
     p.add_argument("--copy-calibration", action="store_true",
                    help="also run three 1 GiB device copies first (reference dispatches for --pmc counter runs)")
@@ -316,6 +325,59 @@ def main():
             sum(r.tokens_generated for r in res_april[:args.update_weights]) / t_same if t_same > 0 else None)
         del dev_w
     ap.april_destroy(ctx)
+
+    if args.next_rows > 0:
+        nx = {"steps": args.next_rows}
+        base_kw = dict(max_inflight=w.n_overprovision + 32, max_ctx=w.prompt_len + w.max_new + 16, seed=w.seed,
+                       kv_pool_bytes=int(args.kv_pool_gib * (1 << 30)),
+                       stream=torch.cuda.current_stream().cuda_stream or None)
+
+        def arm(label, group_size=0, **kw):
+            c = ap.april_init(ap.make_cfg(s, **base_kw, **kw), packed)
+            try:
+                res, _ = run_arm(ap, c, reqs, w.n_target, w.n_overprovision, w.max_new, args.next_rows, 0,
+                                 group_size=group_size)
+            finally:
+                ap.april_destroy(c)
+            tok, t = sum(r.tokens_generated for r in res), sum(r.t_total_s for r in res)
+            nx[label] = {"tokens_per_s": tok / t, "tokens_generated": tok, "step_time_s": t,
+                         "decode_iters": sum(r.decode_iters for r in res)}
+        # same steps of the main arm (greedy, rollout-level completion), for comparison
+        t_same = sum(r.t_total_s for r in res_april[:args.next_rows])
+        nx["main_arm_same_steps_tokens_per_s"] = sum(r.tokens_generated for r in res_april[:args.next_rows]) / t_same
+        arm("rollout_sampling_T0.8_full_vocab_logprobs", sampler=ap.APRIL_SAMPLER_CATEGORICAL, temperature=0.8, logprobs=True)
+        arm("eval_sampling_top_k64_top_p0.7_T0.8", sampler=ap.APRIL_SAMPLER_TOPK, top_k=64, top_p=0.7, temperature=0.8)
+        if w.n_target % 8 == 0 and w.n_overprovision % 8 == 0:
+            arm("groups_of_8_instance_level", group_size=8, sampler=w.sampler, top_k=max(w.top_k, 1),
+                n_samples_per_prompt=8)
+        # releasing and re-mapping the physical memory of the KV pool and of the weights
+        c = ap.april_init(ap.make_cfg(s, **base_kw, sampler=w.sampler, top_k=max(w.top_k, 1), pausable=True), packed)
+        try:
+            inf = ap.april_get_info(c)
+            res0, _ = run_arm(ap, c, reqs, w.n_target, w.n_overprovision, w.max_new, 1, 0)
+            dev_w = {k: torch.from_numpy(v.view(np.int16) if v.dtype == np.uint16 else v).cuda() for k, v in packed.items()}
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            ap.april_memory_pause(c, ap.APRIL_MEM_KV | ap.APRIL_MEM_WEIGHTS)
+            torch.cuda.synchronize()
+            t1 = time.perf_counter()
+            ap.april_memory_resume(c, ap.APRIL_MEM_KV | ap.APRIL_MEM_WEIGHTS)
+            torch.cuda.synchronize()
+            t2 = time.perf_counter()
+            ap.april_update_weights(c, dev_w, keep_kv=False)
+            torch.cuda.synchronize()
+            t3 = time.perf_counter()
+            res1 = ap.april_rollout_step(c, [dict(request_id=r.request_id, tokens=r.tokens, forced_len=r.forced_len)
+                                             for r in reqs[res0[0].n_new_consumed:][:w.n_overprovision]],
+                                         w.n_target, w.n_overprovision, w.max_new)
+            nx["memory_pause_resume"] = {
+                "bytes_released": inf["kv_pool_bytes"] + inf["weight_bytes"], "pause_s": t1 - t0, "resume_s": t2 - t1,
+                "weights_reload_device_to_device_s": t3 - t2, "step_after_resume_tokens_per_s": res1.tokens_generated / res1.t_total_s,
+                "step_before_pause_tokens_per_s": res0[0].tokens_generated / res0[0].t_total_s}
+            del dev_w
+        finally:
+            ap.april_destroy(c)
+        out["next_rows"] = nx
 
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, weights, reqs)

@@ -250,9 +250,12 @@ int vm_map_region(april_ctx* c, april_ctx::VmRegion& r) {
     e = hipMemMap(r.va + off, n, 0, h, 0);
     if (e != hipSuccess) { hipMemRelease(h); return fail(c, APRIL_EDEVICE, "hipMemMap failed: %s", hipGetErrorString(e)); }
     r.chunks.push_back(h);
-    e = hipMemSetAccess(r.va + off, n, &acc, 1);
-    if (e != hipSuccess) return fail(c, APRIL_EDEVICE, "hipMemSetAccess failed: %s", hipGetErrorString(e));
   }
+  // One call for the whole range: set per piece, the call is refused (invalid argument) for a
+  // last piece that is smaller than the ones before it.
+  const hipError_t e = hipMemSetAccess(r.va, r.bytes, &acc, 1);
+  if (e != hipSuccess)
+    return fail(c, APRIL_EDEVICE, "hipMemSetAccess(%zu-byte region) failed: %s", r.bytes, hipGetErrorString(e));
   r.mapped = true;
   return APRIL_OK;
 }

@@ -106,16 +106,18 @@ def generate_weights(ai, ap, s, seed, keep_fp32, threads=16):
     return packed, weights
 
 
-def measured_traffic(workload, kernel_class):
+def measured_traffic(workload, kernel_class, key="traffic_bytes_per_launch"):
     """HBM bytes per launch of a kernel class (fetch + write), from the committed summary of
     the two rocprofv3 --pmc runs over this benchmark's command (already scaled by the copy
-    calibration recorded in the same file); None when no summary covers the class."""
+    calibration recorded in the same file); None when no summary covers the class.
+    key = "algorithmic_bytes_per_launch_same_run": the algorithmic bytes per launch of the
+    counter run itself (one layer, one step: shorter contexts than a long run sees)."""
     path = os.path.join(ROOT, "profiles", f"hbm_traffic_{workload}.txt")
     try:
         with open(path) as f:
             for line in f:
                 parts = line.split()
-                if len(parts) >= 3 and parts[0] == "traffic_bytes_per_launch" and parts[1] == kernel_class:
+                if len(parts) >= 3 and parts[0] == key and parts[1] == kernel_class:
                     return float(parts[2])
     except OSError:
         pass
@@ -278,7 +280,9 @@ def main():
         out["roofline"] = {"kernel": dom["name"], "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS,
                            "unit": "GB/s", "frac": ach / HBM_PEAK_GBS, "traffic": measured_traffic(w.name, dom["name"]),
                            "traffic_source": f"profiles/hbm_traffic_{w.name}.txt (committed rocprofv3 --pmc reading of this "
-                                             "command with --layers 1, not a measurement of this run)",
+                                             "command with --layers 1 --steps 1, not a measurement of this run: compare it with "
+                                             "traffic_run_alg_bytes_per_launch, the algorithmic bytes per launch of that counter run)",
+                           "traffic_run_alg_bytes_per_launch": measured_traffic(w.name, dom["name"], "algorithmic_bytes_per_launch_same_run"),
                            "alg_bytes_per_launch": dom["alg_bytes"] / dom["launches"],
                            "avg_launch_us": launch_us(dom),
                            "avg_event_pair_us": 1e3 * dom["total_ms"] / dom["launches"],

@@ -117,14 +117,14 @@ def class_forced_tokens(w, n_classes, seed_tag=303):
     return rng.integers(0, w.shape.vocab, size=(n_classes, w.max_new), dtype=np.int32)
 
 
-def run_oracle_schedule(reqs, forced, n_target, n_over, max_new, steps):
+def run_oracle_schedule(reqs, forced, n_target, n_over, max_new, steps, pool=None):
     """Scheduling half of the oracle alone (integers), fed the forced tokens."""
     from oracle.scheduler import Rollout, rollout_step
     rolls = [Rollout(request_id=r.request_id, prompt_len=len(r.tokens), forced_len=r.forced_len) for r in reqs]
     buf, nxt, out = [], 0, []
     for _ in range(steps):
         o = rollout_step(buf, rolls[nxt:], n_target, n_over, max_new,
-                         next_token=lambda r: int(forced[r.request_id][r.gen]))
+                         next_token=lambda r: int(forced[r.request_id][r.gen]), pool=pool)
         buf = o.buffer
         nxt += o.n_new_consumed
         out.append(dict(ids=[r.request_id for r in o.completed], tokens=[list(r.tokens) for r in o.completed],
@@ -132,7 +132,8 @@ def run_oracle_schedule(reqs, forced, n_target, n_over, max_new, steps):
                         iters=o.decode_iters, generated=o.tokens_generated,
                         buffer=[(r.request_id, r.gen, int(r.done)) for r in o.buffer],
                         buffer_tokens={r.request_id: list(r.tokens) for r in o.buffer},
-                        sum_live=sum(o.live_per_iter)))
+                        sum_live=sum(o.live_per_iter), n_preempted=len(o.preempted),
+                        kv_resident={r.request_id: int(r.kv > 0) for r in o.buffer}))
     return out
 
 

@@ -209,6 +209,41 @@ def test_cfg2_bench_launch_configuration_sampled_outputs():
         ap().april_destroy(ctx)
 
 
+def test_bf16_kv_pool_exhaustion_schedule_is_bit_exact():
+    """A KV pool of 40 pages under ten bf16 rollouts with 40-token prompts and up to 60 generated
+    tokens: admission stops when prompt pages do not fit, the scheduler kernel preempts the
+    youngest decoding rollouts, and the rows it then lists for the MFMA attention (its work list
+    is rebuilt after the preemption pass) are the survivors.  Tokens are teacher-forced, so the
+    whole schedule - ids, iteration counts, who was preempted, who still holds K/V - is compared
+    bit for bit with the oracle's page arithmetic, and the delivered tokens are the forced ones."""
+    from oracle.scheduler import PagePool
+    from gpu_common import run_oracle_schedule
+    shape = ai.ModelShape(2, 128, 4, 2, 32, 256, 512)
+    w = ai.Workload("pool_bf16", shape, 8, 40, 6, 10, 60, 3.2, 0.6, 4, 60, ai.SAMPLER_GREEDY, 0, 6, 31)
+    weights = ai.make_weights(shape, w.seed)
+    reqs = ai.make_requests(w, ai.requests_needed(w, 6))
+    rng = np.random.default_rng(4)
+    forced = {r.request_id: rng.integers(0, shape.vocab, size=w.max_new, dtype=np.int32)[:min(r.forced_len, w.max_new)]
+              for r in reqs}
+    n_pages = 40
+    page_bytes = 16 * 2 * shape.n_layers * shape.n_kv_heads * shape.head_dim * 2
+    want = run_oracle_schedule(reqs, forced, w.n_target, w.n_overprovision, w.max_new, 6,
+                               pool=PagePool(total=n_pages, page_tokens=16))
+    assert sum(o["n_preempted"] for o in want) > 0
+    ctx = make_engine(w, weights, kv_pool_bytes=n_pages * page_bytes, debug=True)     # teacher forcing needs parity mode
+    try:
+        got = run_gpu(ctx, reqs, w.n_target, w.n_overprovision, w.max_new, 6, forced=forced)
+        assert_schedule_equal(got, want)
+        for g, o in zip(got, want):
+            assert g["n_preempted"] == o["n_preempted"]
+            assert g["kv_resident"] == o["kv_resident"]
+            assert g["tokens"] == o["tokens"]
+        assert sum(g["res"].reprefill_tokens for g in got) > 0
+        assert ap().april_get_info(ctx)["kv_blocks_total"] == n_pages
+    finally:
+        ap().april_destroy(ctx)
+
+
 def test_cfg3_bench_launch_configuration_sampled_outputs():
     """Configuration 3 (the benchmark's default workload) at full size, launched as the benchmark
     launches it: 36 layers, 152 k vocabulary, N = 128, N' = 192, max_new = 4096, greedy sampling

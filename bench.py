@@ -58,7 +58,7 @@ def run_arm(ap, ctx, reqs, n_target, n_over, max_new, steps, profile_every=0, be
     return results, wall
 
 
-def cpu_baseline(w, weights, reqs, budget_s=12.0):
+def cpu_baseline(w, weights, reqs, budget_s=10.0):
     """The oracle as it stands, timed on the host cores for a bounded slice of the
     workload: whole rollouts (prefill of the prompt, then decode) one after another
     until the time budget is used."""

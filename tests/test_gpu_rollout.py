@@ -510,6 +510,57 @@ def test_failed_step_loses_no_rollout(monkeypatch):
         A.april_destroy(ctx)
 
 
+def test_failed_step_loses_no_rollout_with_groups(monkeypatch):
+    """The same forced failure with instance-level completion (groups of 4): the members of
+    resumed groups, complete or not, go back to the pending set, the new groups are not consumed,
+    and the repeated call goes on.  Every group is delivered whole and exactly once, every request
+    with the tokens it gets in an undisturbed run."""
+    G, n_target, n_over = 4, 8, 16
+    shape = ai.ModelShape(2, 64, 4, 2, 32, 96, 200, dtype=ai.DTYPE_FP32)
+    w = ai.Workload("groups_fail", shape, 8, 21, n_target, n_over, 40, 2.4, 0.8, 2, 40, ai.SAMPLER_GREEDY, 0, 4, 21)
+    weights = ai.make_weights(w.shape, w.seed)
+    reqs = ai.make_requests(w, n_over + 5 * n_over)
+    A = ap()
+    ref_ctx = make_engine(w, weights, group_size=G, max_inflight=n_over + 8)
+    try:
+        want = run_gpu(ref_ctx, reqs, n_target, n_over, w.max_new, 4, group_size=G)
+    finally:
+        A.april_destroy(ref_ctx)
+    want_tokens = {rid: t for g in want for rid, t in zip(g["ids"], g["tokens"])}
+    monkeypatch.setenv("APRIL_DEBUG_FAIL_AT", "2:4")
+    ctx = make_engine(w, weights, group_size=G, max_inflight=n_over + 8)
+    monkeypatch.delenv("APRIL_DEBUG_FAIL_AT")
+    try:
+        nxt, steps, failed, delivered, last_buffer = 0, 0, 0, {}, []
+        while steps < 4:
+            try:
+                res = A.april_rollout_step(ctx, req_dicts(reqs[nxt:], group_size=G), n_target, n_over, w.max_new)
+            except A.AprilError as e:
+                assert e.code == A.APRIL_EDEVICE and failed == 0 and steps == 1
+                failed += 1
+                continue
+            steps += 1
+            nxt += res.n_new_consumed
+            assert res.n_new_consumed % G == 0
+            ids = list(res.request_id)
+            assert len(ids) == n_target
+            for k in range(0, len(ids), G):                         # whole groups, members in id order
+                assert ids[k] % G == 0 and ids[k:k + G] == list(range(ids[k], ids[k] + G))
+            for rid, t in zip(ids, res.tokens):
+                assert rid not in delivered
+                delivered[rid] = t.tolist()
+            last_buffer = [p["request_id"] for p in A.april_buffer_export(ctx, res.buffer)]
+            A.april_resume(ctx, res.buffer)
+        assert failed == 1
+        assert sorted(list(delivered) + last_buffer) == list(range(nxt))      # nobody lost, nobody twice
+        common = set(delivered) & set(want_tokens)
+        assert len(common) >= 2 * n_target
+        for rid in common:
+            assert delivered[rid] == want_tokens[rid], rid
+    finally:
+        A.april_destroy(ctx)
+
+
 def test_kv_pool_exhaustion_preempts_youngest_and_reprefills():
     """A KV pool far smaller than the worst case of the step: admission stops when prompt
     pages do not fit, the youngest decoding rollouts are preempted on the device, come back

@@ -144,6 +144,8 @@ struct april_ctx {
   size_t qkv_stride = 0, proj_stride = 0;
   // bf16 MFMA attention: split-KV workspace
   bool attn_mfma = false, fuse_rope = true, tile_gemm = true, fuse_norm = true, fuse_down = false;
+  bool moe_tile = true;         // prefill: expert GEMMs on the LDS-tiled kernel
+  bf16_t* h_rows = nullptr;     // plain [row][d] copy of the MLP input (routed experts, prefill)
   int moe_tall_rows = 2048;     // expert GEMMs: 4 m-tiles per workgroup from this row bound (prefill), 2 below
   int tile_decode_rows = 128;   // decode gate/up goes through the LDS-tiled kernel from this bound on the rows in flight (0 = never)
   float* ssq = nullptr;         // [d_model / 32][m_cap] per-row partial sums of squares (fused norm)
@@ -524,11 +526,12 @@ void forward(april_ctx* c, RowCtx rows, RowCtx srows, const int* gather, double 
   }
   // mlp_in = true: the partials are the previous layer's MLP output (for routed experts: the
   // top-k expert outputs of each row, gathered and weighted)
-  auto norm = [&](RowCtx rc, int n_part, const float* gain, void* out, const int* gth, double rowsB, bool mlp_in) {
+  auto norm = [&](RowCtx rc, int n_part, const float* gain, void* out, const int* gth, double rowsB, bool mlp_in,
+                  bf16_t* out_rows = nullptr) {
     ProfScope p(c, KC_NORM, rowsB * d * (4.0 * (2 + (n_part > 0 ? 1 : 0)) + e), 0);
     if (c->moe && mlp_in && n_part > 0)
       launch_add_rmsnorm<bf16_t, true>(st, rc, c->x_res, c->moe_out, c->top_k_experts, 0, gain, (bf16_t*)out, d, m.rms_eps, gth, c->moe_pos, c->moe_wts);
-    else if (c->bf16) launch_add_rmsnorm<bf16_t, true>(st, rc, c->x_res, c->proj, n_part, c->proj_stride, gain, (bf16_t*)out, d, m.rms_eps, gth);
+    else if (c->bf16) launch_add_rmsnorm<bf16_t, true>(st, rc, c->x_res, c->proj, n_part, c->proj_stride, gain, (bf16_t*)out, d, m.rms_eps, gth, nullptr, nullptr, out_rows);
     else launch_add_rmsnorm<float, false>(st, rc, c->x_res, c->proj, n_part, c->proj_stride, gain, (float*)out, d, m.rms_eps, gth);
   };
   // Prefill rows (hundreds to thousands) go through the LDS-tiled GEMM, which needs no k-split
@@ -595,23 +598,32 @@ void forward(april_ctx* c, RowCtx rows, RowCtx srows, const int* gather, double 
                              c->ssq, c->m_cap, d, nq);
     } else {
       gemm(KC_GEMM_O, rows, c->attn_out, L.wo, L.wo_s, c->proj, d, nq, so, c->proj_stride, B);
-      norm(rows, so, L.mlp_norm, c->h_act, nullptr, B, false);
+      // (routed experts in prefill gather token rows: they get a plain [row][d] copy as well)
+      norm(rows, so, L.mlp_norm, c->h_act, nullptr, B, false, c->moe && tile && c->moe_tile ? c->h_rows : nullptr);
     }
     if (c->moe) {
       const int E = c->n_experts, Fe = c->d_expert, tk = c->top_k_experts;
       gemm(KC_MOE_ROUTE, rows, c->h_act, nullptr, L.router_s, c->router_out, E, d, sr, c->router_stride, B);
       launch_moe_route(st, rows, c->router_out, sr, c->router_stride, E, tk, c->moe_ids, c->moe_wts);
+      // prefill: LDS-tiled expert GEMMs over row groups of 128 packed rows (the dispatch aligns the
+      // expert segments to what the GEMM workgroups cover: same bound to all three launches)
+      const bool moe_tiled = tile && c->moe_tile;
+      const int tall = moe_tiled ? 1 : c->moe_tall_rows;
+      const int n_groups = moe_group_count(rows.max_rows, tk, E, moe_tile_rows());
       launch_moe_dispatch(st, rows, c->moe_ids, E, tk, c->moe_cnt, c->moe_base, c->moe_pos, c->moe_src, c->moe_p_cap,
-                          rows.ctl == reinterpret_cast<const int2*>(c->d_ctrl) ? c->d_ctrl : nullptr, c->moe_tall_rows,
+                          rows.ctl == reinterpret_cast<const int2*>(c->d_ctrl) ? c->d_ctrl : nullptr, tall,
                           c->moe_group);
       const double hit = std::min<double>(E, B * tk);   // bookkeeping estimate: experts that receive a token
       {
         ProfScope p(c, KC_MOE_GATEUP, hit * 2.0 * Fe * d * e + B * tk * (d + Fe) * e, 4.0 * B * tk * Fe * d);
-        launch_moe_gateup(st, rows, c->moe_cnt, c->moe_base, c->moe_group, c->moe_src, (const bf16_t*)c->h_act, L.eg_s, L.eu_s, c->moe_act, E, tk, Fe, d, c->moe_tall_rows);
+        if (!(moe_tiled && launch_moe_tile_gateup(st, rows, c->moe_cnt, c->moe_base, c->moe_group, c->moe_src, c->h_rows,
+                                                  L.eg_s, L.eu_s, c->moe_act, Fe, d, n_groups)))
+          launch_moe_gateup(st, rows, c->moe_cnt, c->moe_base, c->moe_group, c->moe_src, (const bf16_t*)c->h_act, L.eg_s, L.eu_s, c->moe_act, E, tk, Fe, d, tall);
       }
       {
         ProfScope p(c, KC_MOE_DOWN, hit * 1.0 * Fe * d * e + B * tk * (Fe * e + d * 4.0), 2.0 * B * tk * Fe * d);
-        launch_moe_down(st, rows, c->moe_cnt, c->moe_base, c->moe_group, c->moe_act, L.ed_s, c->moe_out, E, tk, Fe, d, c->moe_tall_rows);
+        if (!(moe_tiled && launch_moe_tile_down(st, rows, c->moe_cnt, c->moe_base, c->moe_group, c->moe_act, L.ed_s, c->moe_out, Fe, d, n_groups)))
+          launch_moe_down(st, rows, c->moe_cnt, c->moe_base, c->moe_group, c->moe_act, L.ed_s, c->moe_out, E, tk, Fe, d, tall);
       }
       continue;
     }
@@ -781,6 +793,7 @@ int april_init(const april_model_cfg* cfg, const april_tensor* weights, int32_t 
   c->fuse_down = fd && !strcmp(fd, "1");
   if (const char* td = getenv("APRIL_TILE_DECODE_ROWS")) c->tile_decode_rows = atoi(td);   // debug switch
   if (const char* mt = getenv("APRIL_MOE_TALL_ROWS")) c->moe_tall_rows = atoi(mt);          // debug switch
+  if (const char* mt = getenv("APRIL_MOE_TILE")) c->moe_tile = strcmp(mt, "0") != 0;
   if (const char* fa = getenv("APRIL_DEBUG_FAIL_AT")) {                                       // debug switch
     if (sscanf(fa, "%d:%d", &c->debug_fail_step, &c->debug_fail_iter) != 2) c->debug_fail_step = c->debug_fail_iter = -1;
   }
@@ -903,6 +916,7 @@ int april_init(const april_model_cfg* cfg, const april_tensor* weights, int32_t 
     TRY(dev_alloc(c, &c->moe_group, c->moe_p_cap / 64 + 1));
     TRY(dev_alloc(c, &c->moe_act, (size_t)c->moe_p_cap * Fe));
     TRY(dev_alloc(c, &c->moe_out, (size_t)c->moe_p_cap * d));
+    if (c->moe_tile) TRY(dev_alloc(c, &c->h_rows, M * d));
   }
   const size_t SR = ((size_t)S + 31) / 32 * 32;
   TRY(dev_alloc(c, &c->logits, SR * V));

@@ -69,15 +69,28 @@ template <typename T, bool XF>
 void launch_add_rmsnorm(hipStream_t st, RowCtx rc, float* x_res, const float* partials,
                         int n_partials, size_t partial_stride, const float* gain, T* h,
                         int d, float eps, const int* gather, const int* pos_of = nullptr,
-                        const float* wts = nullptr);
+                        const float* wts = nullptr, T* h_rows = nullptr);
 
 // --- routed experts (bf16) ---------------------------------------------------------
 void launch_moe_route(hipStream_t st, RowCtx rc, const float* logits, int n_partials, size_t partial_stride,
                       int E, int top_k, int* ids, float* wts);
 void launch_moe_dispatch(hipStream_t st, RowCtx rc, const int* ids, int E, int top_k, int* cnt, int* base,
                          int* pos_of, int* src_row, int p_cap, Ctrl* ctrl, int tall_rows, int* group_expert);
+// upper bound on the row groups (of `align` rows) of a launch over at most max_rows rows
+int moe_group_count(int max_rows, int top_k, int E, int align);
 // tall_rows: row bound from which a GEMM workgroup takes 4 m-tiles of an expert instead of 2
 // (the dispatch aligns the expert segments accordingly: pass the same value to all three)
+// LDS-tiled expert GEMMs for prefill passes (kernels_gemm_tile.hip): row groups of moe_tile_rows()
+// packed rows (the dispatch must have aligned the expert segments to that), one accumulator chain
+// per output element.  Return false (nothing launched) for shapes they do not take.
+int moe_tile_rows();
+// (gate/up: h_rows is the plain [row][d] copy of the normalised activations that
+// launch_add_rmsnorm writes on request; its rows are gathered through src_row)
+bool launch_moe_tile_gateup(hipStream_t st, RowCtx rc, const int* cnt, const int* base, const int* group_expert,
+                            const int* src_row, const bf16_t* h_rows, const bf16_t* Wg, const bf16_t* Wu, bf16_t* act,
+                            int Fe, int d, int n_groups);
+bool launch_moe_tile_down(hipStream_t st, RowCtx rc, const int* cnt, const int* base, const int* group_expert,
+                          const bf16_t* act, const bf16_t* Wd, float* out, int Fe, int d, int n_groups);
 void launch_moe_gateup(hipStream_t st, RowCtx rc, const int* cnt, const int* base, const int* group_expert,
                        const int* src_row, const bf16_t* h, const bf16_t* Wg, const bf16_t* Wu, bf16_t* act, int E,
                        int top_k, int Fe, int d, int tall_rows);

@@ -310,7 +310,7 @@ __global__ __launch_bounds__(256) void add_rmsnorm_kernel(RowCtx rc, float* x_re
                                                           int n_partials_rt, size_t partial_stride,
                                                           const float* gain, T* h, int d, float eps,
                                                           const int* gather, const int* pos_of,
-                                                          const float* wts) {
+                                                          const float* wts, T* h_rows) {
   const int r = blockIdx.x;
   ROW_GUARD(rc, r);
   const int rin = gather ? gather[r] : r;
@@ -366,18 +366,26 @@ __global__ __launch_bounds__(256) void add_rmsnorm_kernel(RowCtx rc, float* x_re
     const int ch = threadIdx.x + c * 256;
     if (ch < nchunk) {
       T* hp = h + act_index<XF>(r, ch * 8, d);
+      T hv[8];
 #pragma unroll
-      for (int j = 0; j < 8; ++j) hp[j] = from_f32<T>(v[c][j] * rinv * gain[ch * 8 + j]);
+      for (int j = 0; j < 8; ++j) hv[j] = from_f32<T>(v[c][j] * rinv * gain[ch * 8 + j]);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) hp[j] = hv[j];
+      if (h_rows != nullptr) {           // second copy, plain [row][d]: rows that a later kernel gathers one by one
+        T* rp = h_rows + (size_t)r * d + ch * 8;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) rp[j] = hv[j];
+      }
     }
   }
 }
 template <typename T, bool XF>
 void launch_add_rmsnorm(hipStream_t st, RowCtx rc, float* x_res, const float* partials, int n_partials,
                         size_t partial_stride, const float* gain, T* h, int d, float eps, const int* gather,
-                        const int* pos_of, const float* wts) {
+                        const int* pos_of, const float* wts, T* h_rows) {
 #define ARN_CASE(NP)                                                                                          \
   hipLaunchKernelGGL((add_rmsnorm_kernel<T, XF, NP>), dim3(rc.max_rows), dim3(256), 0, st, rc, x_res, partials, \
-                     n_partials, partial_stride, gain, h, d, eps, gather, pos_of, wts)
+                     n_partials, partial_stride, gain, h, d, eps, gather, pos_of, wts, h_rows)
   switch (n_partials) {
     case 0: ARN_CASE(0); break;
     case 1: ARN_CASE(1); break;
@@ -392,8 +400,8 @@ void launch_add_rmsnorm(hipStream_t st, RowCtx rc, float* x_res, const float* pa
   }
 #undef ARN_CASE
 }
-template void launch_add_rmsnorm<float, false>(hipStream_t, RowCtx, float*, const float*, int, size_t, const float*, float*, int, float, const int*, const int*, const float*);
-template void launch_add_rmsnorm<bf16_t, true>(hipStream_t, RowCtx, float*, const float*, int, size_t, const float*, bf16_t*, int, float, const int*, const int*, const float*);
+template void launch_add_rmsnorm<float, false>(hipStream_t, RowCtx, float*, const float*, int, size_t, const float*, float*, int, float, const int*, const int*, const float*, float*);
+template void launch_add_rmsnorm<bf16_t, true>(hipStream_t, RowCtx, float*, const float*, int, size_t, const float*, bf16_t*, int, float, const int*, const int*, const float*, bf16_t*);
 
 // ---------------------------------------------------------------------------
 // Rotary tables, computed once in double precision: cos/sin[pos][i], i < head_dim/2,

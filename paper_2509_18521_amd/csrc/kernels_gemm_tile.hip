@@ -253,10 +253,26 @@ struct TileNorm {              // RMSNorm folded into the SwiGLU epilogue (CHAIN
   int* gidx;                   // LM head: column of every 64-column group's maximum (nullptr = not wanted)
 };
 
-template <int WGM, int WGN, int MTW, int NTW, int BK, int R, int EPI, bool CHAIN>
+// Routed experts (MOE): blockIdx.y is a row group of the dispatch kernel's packed list (MT m-tiles
+// of one expert; the expert segments are aligned to MT * 32 rows), rows are packed-row indices,
+// the weights are the expert's, and the activation rows are either the packed tiles (down
+// projection) or token rows gathered through src_row from a plain [row][K] copy of the
+// activations (gate/up: each lane copies its own 16 bytes, so a gathered fragment lands in LDS
+// exactly like a dense one; gathering from the fragment-tiled layout would use 16 bytes of
+// every 128-byte line it touches).
+struct TileMoe {
+  const int* cnt;              // [E] rows of every expert
+  const int* base;             // [E] first packed row of every expert
+  const int* group_expert;     // [row groups] expert of the group, -1 = none
+  const int* src_row;          // [packed rows] token row, or nullptr (activations already packed)
+  size_t w_expert_stride;      // bf16x8 units between the experts' matrices
+};
+
+template <int WGM, int WGN, int MTW, int NTW, int BK, int R, int EPI, bool CHAIN, bool MOE = false>
 __device__ __forceinline__ void tile_dma_body(RowCtx rc, const bf16x8* __restrict__ x, const bf16x8* __restrict__ w0,
                                               const bf16x8* __restrict__ w1, float* __restrict__ out,
-                                              bf16_t* __restrict__ act, int N, int K, const TileNorm& tn) {
+                                              bf16_t* __restrict__ act, int N, int K, const TileNorm& tn,
+                                              const TileMoe& mo = TileMoe{}) {
   constexpr int NW = WGM * WGN, MT = WGM * MTW, NT = WGN * NTW, FR = MT + NT;
   constexpr int PER = FR * BK / NW;
   static_assert(FR * BK % NW == 0 && NW % BK == 0, "staging split");
@@ -264,19 +280,39 @@ __device__ __forceinline__ void tile_dma_body(RowCtx rc, const bf16x8* __restric
   static_assert(R >= 3 && (R - 2) * PER < 64, "ring depth");
   __shared__ bf16x8 lds[R][BK][FR][64];
   const int bx = blockIdx.x, by = blockIdx.y;
-  const int rows = rows_or_zero(rc);
+  int rows = rows_or_zero(rc);
   const int m0 = by * MT;
-  if (m0 * 32 >= rows) return;
+  if constexpr (MOE) {
+    if (rows == 0) return;                       // step stopped, or nothing to do
+    const int e = mo.group_expert[by];
+    if (e < 0) return;
+    const int rows_e = mo.cnt[e], p0 = mo.base[e];
+    if (m0 * 32 < p0 || m0 * 32 - p0 >= rows_e) return;
+    rows = p0 + rows_e;                          // one past the expert's last packed row
+    w0 += (size_t)e * mo.w_expert_stride;
+    if (w1 != nullptr) w1 += (size_t)e * mo.w_expert_stride;
+  } else {
+    if (m0 * 32 >= rows) return;
+  }
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int wm = wave / WGN, wn = wave % WGN;
   const int KT = K >> 4;
   const int m_last = (rows - 1) >> 5;
   const int n_tiles = N >> 5;
-  auto slot_base = [&](int t) -> const bf16x8* {
+  auto slot_base = [&](int t) -> const bf16x8* {        // this lane's piece of the slot's fragment at k-tile 0
     if (t < MT) {
+      if constexpr (MOE) {
+        if (mo.src_row != nullptr) {
+          int p = (m0 + t) * 32 + (lane & 31);
+          if (p > rows - 1) p = rows - 1;                 // rows beyond the expert's repeat its last one (never written)
+          int row = mo.src_row[p];
+          if (row < 0) row = 0;
+          return x + ((size_t)row * KT * 2 + (lane >> 5));   // plain [row][K]: a k-tile of a row is two 16-byte pieces
+        }
+      }
       int mt = m0 + t;
       if (mt > m_last) mt = m_last;
-      return x + (size_t)mt * KT * 64;
+      return x + (size_t)mt * KT * 64 + lane;
     }
     const int i = t - MT;
     if (EPI == TEPI_SWIGLU) {
@@ -284,23 +320,27 @@ __device__ __forceinline__ void tile_dma_body(RowCtx rc, const bf16x8* __restric
       const int col = i / NTW, ii = i % NTW;
       int f = bx * (NT / 2) + col * H + (ii < H ? ii : ii - H);
       if (f >= n_tiles) f = n_tiles - 1;
-      return (ii < H ? w0 : w1) + (size_t)f * KT * 64;
+      return (ii < H ? w0 : w1) + (size_t)f * KT * 64 + lane;
     }
     int nt = bx * NT + i;
     if (nt >= n_tiles) nt = n_tiles - 1;
-    return w0 + (size_t)nt * KT * 64;
+    return w0 + (size_t)nt * KT * 64 + lane;
   };
   const int skk = wave % BK, st0 = wave / BK;
   const bf16x8* src[PER];
 #pragma unroll
-  for (int u = 0; u < PER; ++u) src[u] = slot_base(st0 + (NW / BK) * u) + lane;
+  for (int u = 0; u < PER; ++u) src[u] = slot_base(st0 + (NW / BK) * u);
   const int n_stages = KT / BK;
+  const bool gathered = MOE && mo.src_row != nullptr;
   auto issue = [&](int s) {
     const size_t off = (size_t)(s * BK + skk) * 64;
+    const size_t off_rows = (size_t)(s * BK + skk) * 2;      // gathered activation rows advance 32 bytes per k-tile
     const int slot = s % R;
 #pragma unroll
-    for (int u = 0; u < PER; ++u)
-      copy_fragment_to_lds(src[u] + off, &lds[slot][skk][st0 + (NW / BK) * u][0]);
+    for (int u = 0; u < PER; ++u) {
+      const int t = st0 + (NW / BK) * u;
+      copy_fragment_to_lds(src[u] + (gathered && t < MT ? off_rows : off), &lds[slot][skk][t][0]);
+    }
   };
 
   f32x16 acc[NTW][MTW];
@@ -419,6 +459,40 @@ void gemm_tile_chain_kernel(RowCtx rc, const bf16x8* __restrict__ x, const bf16x
                             const bf16x8* __restrict__ w1, float* __restrict__ out, bf16_t* __restrict__ act, int N,
                             int K, TileNorm tn) {
   tile_dma_body<WGM, WGN, MTW, NTW, BK, R, EPI, true>(rc, x, w0, w1, out, act, N, K, tn);
+}
+
+// Routed experts in prefill: 128 packed rows (one row group of the dispatch list) x 256 weight
+// rows per workgroup, 4 wavefronts side by side (each 128 x 64), ring of 3 stages (72 KiB, two
+// workgroups per CU).  One accumulator chain per output element, like every prefill GEMM.
+template <int EPI>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2)))
+void moe_tile_kernel(RowCtx rc, const bf16x8* __restrict__ x, const bf16x8* __restrict__ w0,
+                     const bf16x8* __restrict__ w1, float* __restrict__ out, bf16_t* __restrict__ act, int N, int K,
+                     TileMoe mo) {
+  tile_dma_body<1, 4, 4, 2, 2, 3, EPI, false, true>(rc, x, w0, w1, out, act, N, K, TileNorm{}, mo);
+}
+
+int moe_tile_rows() { return 128; }
+
+bool launch_moe_tile_gateup(hipStream_t st, RowCtx rc, const int* cnt, const int* base, const int* group_expert,
+                            const int* src_row, const bf16_t* h_rows, const bf16_t* Wg, const bf16_t* Wu, bf16_t* act,
+                            int Fe, int d, int n_groups) {
+  if (d % 32 != 0 || Fe % 32 != 0 || n_groups <= 0 || h_rows == nullptr) return false;
+  const TileMoe mo{cnt, base, group_expert, src_row, (size_t)Fe * d / 8};
+  dim3 grid(ceil_div(Fe >> 5, 4), n_groups);            // 4 feature tiles (gate + up: 8 weight tiles) per workgroup
+  hipLaunchKernelGGL((moe_tile_kernel<TEPI_SWIGLU>), grid, dim3(256), 0, st, rc, reinterpret_cast<const bf16x8*>(h_rows),
+                     reinterpret_cast<const bf16x8*>(Wg), reinterpret_cast<const bf16x8*>(Wu), nullptr, act, Fe, d, mo);
+  return true;
+}
+
+bool launch_moe_tile_down(hipStream_t st, RowCtx rc, const int* cnt, const int* base, const int* group_expert,
+                          const bf16_t* act, const bf16_t* Wd, float* out, int Fe, int d, int n_groups) {
+  if (d % 32 != 0 || Fe % 32 != 0 || n_groups <= 0) return false;
+  const TileMoe mo{cnt, base, group_expert, nullptr, (size_t)d * Fe / 8};
+  dim3 grid(ceil_div(d >> 5, 8), n_groups);
+  hipLaunchKernelGGL((moe_tile_kernel<TEPI_F32>), grid, dim3(256), 0, st, rc, reinterpret_cast<const bf16x8*>(act),
+                     reinterpret_cast<const bf16x8*>(Wd), nullptr, out, nullptr, d, Fe, mo);
+  return true;
 }
 
 // Tile shapes.  WIDE: 256 x 256 outputs on 8 wavefronts (2 per SIMD, each 128 x 64), ring of

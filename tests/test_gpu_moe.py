@@ -110,9 +110,10 @@ def test_moe_resumed_equals_uninterrupted():
 
 
 def test_expert_gemm_grouping_changes_no_bit(monkeypatch):
-    """Tall batches (prefill) give a workgroup 4 m-tiles of an expert's rows instead of 2; the
-    grouping is not part of any summation chain: forcing either for every launch of a run
-    (prefill and decode) leaves every logit bit-identical."""
+    """Decode batches beyond a row bound give a workgroup 4 m-tiles of an expert's rows instead of
+    2; the grouping is not part of any summation chain: forcing either for every decode launch
+    of a run leaves every logit bit-identical.  (Prefill passes run the LDS-tiled expert kernels,
+    whatever the bound.)"""
     shape = ai.ModelShape(2, 128, 4, 2, 32, 0, 512, n_experts=32, experts_per_tok=2, d_expert_ffn=64)
     w = ai.Workload("moe_group", shape, 6, 150, 6, 9, 6, 1.5, 0.3, 3, 6, ai.SAMPLER_GREEDY, 0, 2, 23)
     weights = ai.make_weights(shape, w.seed)

@@ -37,11 +37,15 @@ namespace april {
 #define ATT_SPLIT_64 1024
 #endif
 #ifndef ATT_SPLIT_128
-#define ATT_SPLIT_128 1024
+#define ATT_SPLIT_128 4096
 #endif
 // tokens per KV split, a multiple of 1024 (a lane holds one page id per 1024 tokens of the split).
-// 2048 was measured for both head sizes: head_dim 64 (small model, 5 steps) 1.6 % slower end to end;
-// head_dim 128: +1.6 % on 4000-token rows, -4.5 % on a ragged batch.  512: 7 % slower on long rows.
+// head_dim 64 (small model, 2 KV heads): 2048 was 1.6 % slower end to end than 1024; 512: 7 % slower
+// on long rows.  head_dim 128, launched over the length-sorted work list: the kernel itself is
+// 1 % slower with 4096-token splits than with 1024 (160.8 against 158.7 us on the 4.4 B
+// configuration), but few rows then need the merge kernel at all, and the run is 1 % faster end to
+// end on each of the three wide configurations (before the work list, on a grid launch, 2048-token
+// splits cost 4.5 % on a ragged batch).
 constexpr int att_split(int dh) { return dh == 64 ? ATT_SPLIT_64 : (dh == 128 ? ATT_SPLIT_128 : 1024); }
 // wavefronts per workgroup (8 for head_dim <= 64 was measured: 11.8 us against 10.6 us per launch)
 #ifndef ATT_WAVES_128

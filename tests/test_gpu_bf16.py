@@ -101,11 +101,12 @@ def test_wide_shapes_head_dim_128_gqa4(name):
 
 @pytest.mark.parametrize("head_dim", [64, 128])
 def test_long_context_spans_several_kv_splits(head_dim):
-    """Contexts beyond 1024 and 2048 tokens: the attention kernel cuts them into KV splits whose
-    partial results a second kernel merges; prefill rows and decode rows both cross the
-    boundaries here (2100-token prompts, then a resumed step on resident KV)."""
+    """Contexts beyond a KV split (1024 tokens for head_dim 64, 4096 for 128): the decode attention
+    cuts them into splits whose partial results a second kernel merges.  2100-token prompts
+    (three splits) and 4150-token prompts (two), then a resumed step on resident KV."""
     shape = ai.ModelShape(1, 256, 256 // head_dim, 2, head_dim, 256, 512)
-    w = ai.Workload("long_ctx", shape, 3, 2100, 2, 3, 8, 1.6, 0.4, 3, 8, ai.SAMPLER_GREEDY, 0, 2, 77)
+    prompt_len = 2100 if head_dim == 64 else 4150
+    w = ai.Workload("long_ctx", shape, 3, prompt_len, 2, 3, 8, 1.6, 0.4, 3, 8, ai.SAMPLER_GREEDY, 0, 2, 77)
     teacher_forced_parity(w, 2, 5, min_rows=12)
 
 
@@ -352,15 +353,16 @@ def test_tiled_decode_gate_up_gives_the_skinny_kernels_bits(monkeypatch, n_targe
 def test_attention_work_list_gives_the_grid_launch_bits(monkeypatch, head_dim):
     """Decode attention takes its (row, KV split) items from the list the scheduler kernel sorts
     by length every iteration; APRIL_ATTN_LIST=0 launches one workgroup per (row, head, split)
-    of a grid instead.  Contexts of 1003-1070 tokens (and 2030-2100 with the longer prompt) put
-    rows with different split counts and last-split lengths into the same iteration; no bit of
-    any logit may depend on which launch ran, nor any token or scheduling decision."""
+    of a grid instead.  Prompts that end 24-60 tokens short of a split boundary (1024 and 2048
+    tokens for head_dim 64, 4096 for 128) put rows with different split counts and last-split
+    lengths into the same iteration; no bit of any logit may depend on which launch ran, nor any
+    token or scheduling decision."""
     shape = ai.ModelShape(1, 256, 256 // head_dim, 2, head_dim, 256, 512)
     runs = []
     for flag in ("0", "1"):
         monkeypatch.setenv("APRIL_ATTN_LIST", flag)
         per_prompt = []
-        for prompt_len in (1000, 2030):
+        for prompt_len in ((1000, 2030) if head_dim == 64 else (1000, 4060)):
             w = ai.Workload("att_list", shape, 6, prompt_len, 10, 16, 70, 3.3, 0.8, 3, 70, ai.SAMPLER_GREEDY, 0, 2, 21)
             weights = ai.make_weights(shape, w.seed)
             reqs = ai.make_requests(w, ai.requests_needed(w))

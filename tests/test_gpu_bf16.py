@@ -317,7 +317,7 @@ def test_cfg3_bench_launch_configuration_sampled_outputs():
     assert worst <= BF16_LOGIT_TOL, worst
 
 
-@pytest.mark.parametrize("n_target,n_over", [(30, 40), (100, 150)])      # half-height tile; full tile
+@pytest.mark.parametrize("n_target,n_over", [(30, 40), (100, 150), (150, 230)])      # 128-, 192- and 256-row tile
 def test_tiled_decode_gate_up_gives_the_skinny_kernels_bits(monkeypatch, n_target, n_over):
     """With many rows in flight the decode gate/up GEMM runs in the LDS-tiled kernel, which
     closes its accumulator chain at the skinny kernel's quarter boundaries and folds the same

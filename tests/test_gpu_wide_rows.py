@@ -125,6 +125,39 @@ def test_dense_wide_layer_many_rows(name, n_target, n_over):
     assert got[0]["sum_live"] >= n_over * 2
 
 
+@pytest.mark.parametrize("n_over", [150, 230, 300])
+def test_wide_layer_batch_size_changes_no_bit(n_over):
+    """At the width of configuration 3 the row count picks the kernels: qkv and down with one or
+    several m-groups, the output projection with one or four m-tiles per workgroup, gate/up on
+    the skinny kernel (4 rows, and 300), the 192-row LDS tile (150) or the 256-row one (230),
+    the LM head skinny or tall.  Each choice keeps every output element's summation chain, so
+    the first four requests must get bit-identical logits whether they run alone or among n_over
+    rollouts (teacher-forced tokens, so both runs feed the same sequences)."""
+    base = ai.WORKLOADS["cfg3_mid_bf16"]
+    shape = ai.reduced(base, n_layers=1, vocab=8192).shape
+    runs = []
+    for n_flight in (4, n_over):
+        w = ai.Workload(f"cfg3_L1_bits_{n_flight}", shape, 37, 7, n_flight, n_flight, 5, 1.45, 0.2, 5, 5,
+                        ai.SAMPLER_GREEDY, 0, 1, base.seed)
+        weights = _weights(w.shape, w.seed)
+        reqs = ai.make_requests(w, n_flight)
+        ctoks = class_forced_tokens(w, w.n_prompts)
+        forced = {r.request_id: ctoks[r.request_id % w.n_prompts][:w.max_new] for r in reqs}
+        ctx = make_engine(w, weights, debug=True, max_inflight=n_flight + 8)
+        try:
+            for rid in range(4):
+                ap().april_debug_watch(ctx, rid, 0, w.max_new)
+            got = run_gpu(ctx, reqs, n_flight, n_flight, w.max_new, 1, forced=forced)[0]
+            assert sorted(got["ids"]) == list(range(n_flight))
+            runs.append({(rid, i): ap().april_debug_logits(ctx, rid, i, shape.vocab)[0]
+                         for rid in range(4) for i in range(w.max_new)})
+        finally:
+            ap().april_destroy(ctx)
+    alone, crowd = runs
+    assert alone.keys() == crowd.keys() and len(alone) == 20
+    assert all(np.array_equal(alone[k], crowd[k]) for k in alone)
+
+
 def test_moe_cfg5_layer_many_rows():
     """One layer of configuration 5 (128 experts, 8 per token, expert ffn 768, d 2048), 384
     rollouts in flight over 5 prompt classes: a class's rows take the same experts, so in decode

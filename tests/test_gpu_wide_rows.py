@@ -112,8 +112,8 @@ def test_dense_wide_layer_many_rows(name, n_target, n_over):
     in flight, two steps (the second decodes resumed rollouts next to a fresh prefill).
     Decode launches reached (rocprofv3 kernel trace of this test): qkv and down through
     gemm_mfma_kernel<2,4,EPI_F32,true> with 2-3 m-groups; the output projection through
-    gemm_mfma_kernel<1,4,EPI_RESID,true>; gate/up through gemm_tile_chain_kernel<2,2,4,2,2,3>
-    (192 rows; 300 rows of configuration 4: two row groups) or, for 300 rows of configuration
+    gemm_mfma_kernel<1,4,EPI_RESID,true>; gate/up through gemm_tile_chain_kernel<2,2,3,2,2,3>
+    (192 rows) and <4,2,2,2,2,3> (300 rows of configuration 4: two row groups) or, for 300 rows of configuration
     3, gemm_mfma_kernel<2,4,EPI_SWIGLU,true> with three m-groups; the LM head through the
     tall-batch kernel."""
     base = ai.WORKLOADS[name]

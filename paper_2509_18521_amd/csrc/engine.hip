@@ -145,6 +145,7 @@ struct april_ctx {
   // bf16 MFMA attention: split-KV workspace
   bool attn_mfma = false, fuse_rope = true, tile_gemm = true, fuse_norm = true, fuse_down = false;
   bool moe_tile = true;         // prefill: expert GEMMs on the LDS-tiled kernel
+  bool tile_f32 = true;         // decode above 128 rows: split-k projections on the LDS-tiled kernel
   bf16_t* h_rows = nullptr;     // plain [row][d] copy of the MLP input (routed experts, prefill)
   int moe_tall_rows = 2048;     // expert GEMMs: 4 m-tiles per workgroup from this row bound (prefill), 2 below
   int tile_decode_rows = 128;   // decode gate/up goes through the LDS-tiled kernel from this bound on the rows in flight (0 = never)
@@ -543,6 +544,13 @@ void forward(april_ctx* c, RowCtx rows, RowCtx srows, const int* gather, double 
                   int ks, size_t stride, double rowsB, const float* ssq = nullptr) {
     ProfScope p(c, kc, (double)N * K * e + rowsB * K * e + rowsB * N * 4.0, 2.0 * rowsB * N * K);
     if (tile) launch_gemm_tile(st, rc, (const bf16_t*)x, w_s, out, N, K);
+    else if (c->use_mfma && c->tile_f32 && rc.max_rows > 128 && ssq == nullptr && N >= 1024 && (N / 64) * ks >= 128 &&
+             K / ks >= 3072 && launch_gemm_tile_chain_f32(st, rc, (const bf16_t*)x, w_s, out, N, K, ks, stride)) {
+      // decode with more than 128 rows, wide matrix, long k slices: LDS-tiled kernel with the skinny
+      // kernel's chains.  Measured at 230 rows: the 4096 x 14336 down projection (4 slices of
+      // 3584) 57.4 us against 62.4 us; qkv projections with slices of 1280 / 2048 are slower
+      // there (18.1 against 16.4 us, 34.2 against 30.4 us), hence the bound on the slice length.
+    }
     else if (c->use_mfma) launch_gemm_mfma(st, rc, (const bf16_t*)x, w_s, out, N, K, ks, stride, ssq, (int)c->m_cap, m.rms_eps);
     else if (c->bf16) launch_gemm_ref<bf16_t, true>(st, rc, (const bf16_t*)x, (const bf16_t*)w_plain, out, N, K);
     else launch_gemm_ref<float, false>(st, rc, (const float*)x, (const float*)w_plain, out, N, K);
@@ -794,6 +802,7 @@ int april_init(const april_model_cfg* cfg, const april_tensor* weights, int32_t 
   if (const char* td = getenv("APRIL_TILE_DECODE_ROWS")) c->tile_decode_rows = atoi(td);   // debug switch
   if (const char* mt = getenv("APRIL_MOE_TALL_ROWS")) c->moe_tall_rows = atoi(mt);          // debug switch
   if (const char* mt = getenv("APRIL_MOE_TILE")) c->moe_tile = strcmp(mt, "0") != 0;
+  if (const char* tf = getenv("APRIL_TILE_F32")) c->tile_f32 = strcmp(tf, "0") != 0;
   if (const char* fa = getenv("APRIL_DEBUG_FAIL_AT")) {                                       // debug switch
     if (sscanf(fa, "%d:%d", &c->debug_fail_step, &c->debug_fail_iter) != 2) c->debug_fail_step = c->debug_fail_iter = -1;
   }

@@ -159,6 +159,11 @@ void launch_gemm_tile_swiglu(hipStream_t st, RowCtx rc, const bf16_t* x, const b
                              bf16_t* act, int F, int K);
 bool launch_gemm_tile_swiglu_chain(hipStream_t st, RowCtx rc, const bf16_t* x, const bf16_t* Wg, const bf16_t* Wu,
                                    bf16_t* act, int F, int K, const float* ssq, int ssq_stride, float eps);
+// Split-k partial-sum GEMM (qkv, down) for more than 128 rows on the LDS-tiled kernel with the skinny
+// kernel's summation chains: out[slice][m][n], slices partial_stride floats apart.  Returns false
+// (nothing launched) when the k slices do not fall on the kernel's stage boundaries.
+bool launch_gemm_tile_chain_f32(hipStream_t st, RowCtx rc, const bf16_t* x, const bf16_t* Wp, float* out, int N, int K,
+                                int ksplit, size_t partial_stride);
 void launch_gemm_tile_logits(hipStream_t st, RowCtx rc, const bf16_t* x, const bf16_t* Wp, float* logits,
                              float* group_max, int V, int K, int* group_idx = nullptr);
 // LM head: logits fp32 [rows][V] plus, per row, the maximum of every group of

@@ -251,6 +251,8 @@ struct TileNorm {              // RMSNorm folded into the SwiGLU epilogue (CHAIN
   int ssq_stride, n_ssq;
   float inv_d, eps;
   int* gidx;                   // LM head: column of every 64-column group's maximum (nullptr = not wanted)
+  int ksplit = 0;              // CHAIN, plain epilogue: blockIdx.z = k slice of ksplit (0: the whole k range)
+  size_t partial_stride = 0;   // floats between the slices' partial outputs
 };
 
 // Routed experts (MOE): blockIdx.y is a row group of the dispatch kernel's packed list (MT m-tiles
@@ -330,11 +332,20 @@ __device__ __forceinline__ void tile_dma_body(RowCtx rc, const bf16x8* __restric
   const bf16x8* src[PER];
 #pragma unroll
   for (int u = 0; u < PER; ++u) src[u] = slot_base(st0 + (NW / BK) * u);
-  const int n_stages = KT / BK;
+  // k range of this workgroup: everything, or slice blockIdx.z of tn.ksplit (the skinny kernel's
+  // slices; the launcher has checked that slices and their quarters fall on stage boundaries)
+  int kt0 = 0, kt1 = KT;
+  if (CHAIN && EPI == TEPI_F32 && tn.ksplit > 0) {
+    kt0 = (int)((long long)KT * blockIdx.z / tn.ksplit);
+    kt1 = (int)((long long)KT * (blockIdx.z + 1) / tn.ksplit);
+    out += (size_t)blockIdx.z * tn.partial_stride;
+  }
+  const int klen = kt1 - kt0;
+  const int n_stages = klen / BK;
   const bool gathered = MOE && mo.src_row != nullptr;
   auto issue = [&](int s) {
-    const size_t off = (size_t)(s * BK + skk) * 64;
-    const size_t off_rows = (size_t)(s * BK + skk) * 2;      // gathered activation rows advance 32 bytes per k-tile
+    const size_t off = (size_t)(kt0 + s * BK + skk) * 64;
+    const size_t off_rows = (size_t)(kt0 + s * BK + skk) * 2;      // gathered activation rows advance 32 bytes per k-tile
     const int slot = s % R;
 #pragma unroll
     for (int u = 0; u < PER; ++u) {
@@ -349,7 +360,7 @@ __device__ __forceinline__ void tile_dma_body(RowCtx rc, const bf16x8* __restric
 #pragma unroll
     for (int j = 0; j < MTW; ++j) acc[i][j] = f32x16{};
   f32x16 tot[CHAIN ? NTW : 1][CHAIN ? MTW : 1];
-  int quarter = 1, next_close = CHAIN ? (KT / 4) / BK : -1;       // stage at which the next chain closes
+  int quarter = 1, next_close = CHAIN ? (klen / 4) / BK : -1;     // stage at which the next chain closes
 
 #pragma unroll
   for (int r = 0; r < R - 1; ++r)
@@ -397,7 +408,7 @@ __device__ __forceinline__ void tile_dma_body(RowCtx rc, const bf16x8* __restric
           acc[i][j] = f32x16{};
         }
       ++quarter;
-      next_close = quarter < 4 ? (int)(((long long)KT * quarter / 4) / BK) : -1;
+      next_close = quarter < 4 ? (int)(((long long)klen * quarter / 4) / BK) : -1;
     }
     // wait for this wavefront's copies of stage s (s_waitcnt vmcnt only: expcnt/lgkmcnt fields all-ones)
     constexpr int LEFT = (R - 2) * PER;
@@ -584,6 +595,26 @@ bool launch_gemm_tile_swiglu_chain(hipStream_t st, RowCtx rc, const bf16_t* x, c
   hipLaunchKernelGGL((gemm_tile_chain_kernel<4, 2, 2, 2, 2, 3, TEPI_SWIGLU>), grid, dim3(512), 0, st, rc,
                      reinterpret_cast<const bf16x8*>(x), reinterpret_cast<const bf16x8*>(Wg),
                      reinterpret_cast<const bf16x8*>(Wu), nullptr, act, F, K, tn);
+  return true;
+}
+
+// Split-k projections (qkv, down) with more than 128 rows in flight: 256 rows x 64 columns per
+// workgroup on 4 wavefronts of 64 x 64, one k slice per workgroup (grid.z), the skinny kernel's
+// summation chains (four quarter chains per slice, added in order; the consumer adds the slices).
+// Each weight tile is fetched once for all rows (the skinny kernel runs a second group of rows
+// over the same weights).  Returns false (nothing launched) unless every slice and every quarter
+// of a slice is a whole number of stages.
+bool launch_gemm_tile_chain_f32(hipStream_t st, RowCtx rc, const bf16_t* x, const bf16_t* Wp, float* out, int N, int K,
+                                int ksplit, size_t partial_stride) {
+  const int KT = K >> 4, n_tiles = N >> 5, m_tiles = ceil_div(rc.max_rows, 32);
+  if (K % 16 != 0 || N % 32 != 0 || ksplit < 1 || KT % (ksplit * 4 * 2) != 0) return false;
+  TileNorm tn{};
+  tn.ksplit = ksplit;
+  tn.partial_stride = partial_stride;
+  dim3 grid(ceil_div(n_tiles, 2), ceil_div(m_tiles, 8), ksplit);
+  hipLaunchKernelGGL((gemm_tile_chain_kernel<4, 1, 2, 2, 2, 3, TEPI_F32>), grid, dim3(256), 0, st, rc,
+                     reinterpret_cast<const bf16x8*>(x), reinterpret_cast<const bf16x8*>(Wp), nullptr, out, nullptr, N, K,
+                     tn);
   return true;
 }
 

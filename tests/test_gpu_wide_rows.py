@@ -125,19 +125,23 @@ def test_dense_wide_layer_many_rows(name, n_target, n_over):
     assert got[0]["sum_live"] >= n_over * 2
 
 
-@pytest.mark.parametrize("n_over", [150, 230, 300])
-def test_wide_layer_batch_size_changes_no_bit(n_over):
-    """At the width of configuration 3 the row count picks the kernels: qkv and down with one or
-    several m-groups, the output projection with one or four m-tiles per workgroup, gate/up on
-    the skinny kernel (4 rows, and 300), the 192-row LDS tile (150) or the 256-row one (230),
-    the LM head skinny or tall.  Each choice keeps every output element's summation chain, so
-    the first four requests must get bit-identical logits whether they run alone or among n_over
-    rollouts (teacher-forced tokens, so both runs feed the same sequences)."""
-    base = ai.WORKLOADS["cfg3_mid_bf16"]
+@pytest.mark.parametrize("name,n_over", [("cfg3_mid_bf16", 150), ("cfg3_mid_bf16", 230), ("cfg3_mid_bf16", 300),
+                                         ("cfg4_8b_bf16", 230), ("cfg4_8b_bf16", 300)])
+def test_wide_layer_batch_size_changes_no_bit(name, n_over):
+    """At the widths of configurations 3 and 4 the row count picks the kernels: qkv and down on the
+    skinny kernel with one or several m-groups, except the down projection of configuration 4,
+    which above 128 rows runs on the LDS-tiled kernel with the same summation chains (long k
+    slices that fall on stage boundaries); the output projection with
+    one or four m-tiles per workgroup; gate/up on the skinny kernel (4 rows, and 300 of
+    configuration 3), the 192-row LDS tile (150) or the 256-row one (230, and 300 of
+    configuration 4); the LM head skinny or tall.  Each choice keeps every output element's
+    summation chain, so the first four requests must get bit-identical logits whether they run
+    alone or among n_over rollouts (teacher-forced tokens: both runs feed the same sequences)."""
+    base = ai.WORKLOADS[name]
     shape = ai.reduced(base, n_layers=1, vocab=8192).shape
     runs = []
     for n_flight in (4, n_over):
-        w = ai.Workload(f"cfg3_L1_bits_{n_flight}", shape, 37, 7, n_flight, n_flight, 5, 1.45, 0.2, 5, 5,
+        w = ai.Workload(f"{name}_L1_bits_{n_flight}", shape, 37, 7, n_flight, n_flight, 5, 1.45, 0.2, 5, 5,
                         ai.SAMPLER_GREEDY, 0, 1, base.seed)
         weights = _weights(w.shape, w.seed)
         reqs = ai.make_requests(w, n_flight)
